@@ -1,0 +1,168 @@
+/*
+ * moe_cache.h - C ABI of the batch-1 MoE decode path with cache-conditional routing.
+ *
+ * One MoE layer step for one token is
+ *   z = W_gate x, w = softmax(z)                                  (paper Eq. 3)
+ *   z' = z + lambda * Delta_avg * m~_t, select top-K of z'          (Sec. 3.3, Eq. 9, Eq. 10)
+ *   hits/misses against the cache as it stood before the token     (Sec. 2.2, Eq. 4)
+ *   LRU update of the expert cache                                 (Sec. 4.2)
+ *   y = sum_k w_k E_k(x) (+ shared expert), E = SwiGLU             (Eq. 1)
+ * The paper's DRAM tier is a pool of `capacity` expert slots per layer in device memory,
+ * its Flash tier is pinned host memory holding every expert; a miss is filled by an
+ * asynchronous host-to-device copy on `copy_stream`.
+ *
+ * Conventions
+ *  - Every function returns MOE_OK or a negative moe_status; nothing throws or aborts.
+ *    moe_last_error() gives a message for the calling thread's last failure.
+ *  - "device" pointers are HIP device memory, "host" pointers ordinary host memory, "pinned"
+ *    is page-locked host memory.  All buffers handed in are BORROWED: the caller allocates them,
+ *    keeps them alive until moe_cache_destroy and frees them afterwards.  The library allocates
+ *    only its own small tables (state, route records, partial sums).
+ *  - Streams are hipStream_t passed as void*; both are borrowed.  Calls on one context must come
+ *    from one thread at a time.
+ *  - Expert ids are 0..n_experts-1, slots 0..capacity-1.  n_experts <= 64, top_k <= 8.
+ */
+#ifndef MOE_CACHE_H
+#define MOE_CACHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOE_MAX_EXPERTS 64
+#define MOE_MAX_TOPK 8
+
+typedef struct moe_cache moe_cache_t; /* opaque, owned by the library */
+
+enum moe_status { MOE_OK = 0, MOE_EINVAL = -1, MOE_ENOMEM = -2, MOE_EHIP = -3, MOE_ESTATE = -4 };
+enum moe_weight_fmt { MOE_W_FP32 = 0, MOE_W_BF16 = 1, MOE_W_INT8_PC = 2, MOE_W_INT4_G128 = 3 };
+enum moe_act_fmt { MOE_A_FP32 = 0, MOE_A_BF16 = 1 };
+enum moe_delta_mode { MOE_DELTA_RUNNING_MEAN = 0, MOE_DELTA_FIXED = 1 };
+/* How the ranking vector is altered before the top-K cut.  CACHE_PRIOR is the paper's method
+ * (Sec. 3.3); MAX_RANK (Sec. 3.1, Eq. 6-7) and CUMSUM (Sec. 3.2, Eq. 8) are its two baselines. */
+enum moe_route_mode { MOE_ROUTE_CACHE_PRIOR = 0, MOE_ROUTE_MAX_RANK = 1, MOE_ROUTE_CUMSUM = 2 };
+
+typedef struct moe_cache_config {
+  int32_t n_layers;
+  int32_t hidden;       /* d; a multiple of 64 * (16 / bytes per weight) */
+  int32_t n_experts;    /* N <= 64 */
+  int32_t inter;        /* I, SwiGLU intermediate of a routed expert */
+  int32_t shared_inter; /* intermediate of the always-on shared expert, 0 = none */
+  int32_t top_k;        /* K <= 8 */
+  int32_t top_j;        /* router's own top-J always selected (Sec. 3.3), 0..top_k */
+  int32_t capacity;     /* expert slots per layer, top_k <= capacity <= n_experts */
+  int32_t weight_fmt;   /* moe_weight_fmt of expert blobs */
+  int32_t act_fmt;      /* moe_act_fmt of x, y and the router matrix */
+  int32_t renormalize;  /* 1: divide the K weights by their sum (Sec. 2.1) */
+  int32_t delta_mode;   /* moe_delta_mode: running mean of Eq. 10, or delta_fixed */
+  int32_t route_mode;   /* moe_route_mode */
+  int32_t max_rank;     /* M of Eq. 6 (MOE_ROUTE_MAX_RANK) */
+  float lambda;         /* >= 0, strength of the cache prior (Eq. 9) */
+  float delta_fixed;    /* Delta_avg when delta_mode == MOE_DELTA_FIXED */
+  float cumsum_p;       /* p of Eq. 8 (MOE_ROUTE_CUMSUM) */
+  int32_t reserved;
+  void *compute_stream; /* hipStream_t for kernels */
+  void *copy_stream;    /* hipStream_t for miss fills; must differ from compute_stream */
+} moe_cache_config_t;
+
+typedef struct moe_cache_buffers {
+  const void *const *host_expert_blob; /* [n_layers*n_experts] pinned host, packed blobs (moe_pack_expert) */
+  void *const *slot_pool;              /* [n_layers] device, capacity*moe_slot_bytes each, 256-byte aligned */
+  const void *const *gate_w;           /* [n_layers] device, router matrix [N,d] row-major, act_fmt */
+  const void *const *shared_blob;      /* [n_layers] device packed blob of the shared expert, or NULL */
+  const int32_t *initial_resident;     /* host [n_layers*n_initial] experts preloaded into slots 0.., or NULL */
+  int32_t n_initial;                   /* 0..capacity (App. G: empty or random initial cache) */
+} moe_cache_buffers_t;
+
+/* What one routing step decided; entries 0..top_k-1 are valid, ranked by the altered logits. */
+typedef struct moe_route_out {
+  int32_t sel_expert[MOE_MAX_TOPK];
+  int32_t sel_slot[MOE_MAX_TOPK];   /* slot each selected expert occupies after the step */
+  float sel_weight[MOE_MAX_TOPK];   /* softmax of the UNMODIFIED logits (Sec. 3.3), renormalised if asked */
+  int32_t miss[MOE_MAX_TOPK];       /* 1 if the expert was not resident before the step (Eq. 4) */
+  int32_t evicted[MOE_MAX_TOPK];    /* expert that lost its slot to this one, or -1 */
+  int32_t n_miss;
+  int32_t token;                    /* index of this step within the layer, from 0 */
+  float delta;                      /* Delta_avg used (Eq. 10) */
+  float margin;                     /* gap between the K-th and (K+1)-th altered logit */
+  float logits[MOE_MAX_EXPERTS];    /* z, as used */
+  uint32_t seq;                     /* internal completion tag */
+  uint32_t pad_[3];
+} moe_route_out_t;
+
+typedef struct moe_cache_stats {
+  int64_t tokens, selections, hits, misses, cold_misses, evictions, bytes_filled;
+} moe_cache_stats_t;
+
+/* Per-layer tables, for checking against a reference (host struct). */
+typedef struct moe_cache_tables {
+  int32_t expert_slot[MOE_MAX_EXPERTS]; /* expert -> slot or -1 */
+  int32_t slot_expert[MOE_MAX_EXPERTS]; /* slot -> expert or -1 */
+  int64_t stamp[MOE_MAX_EXPERTS];       /* recency stamp of resident experts: token*K + position */
+  float delta_sum;                      /* running sum of max(z)-min(z) (Eq. 10) */
+  int32_t count;                        /* tokens seen */
+} moe_cache_tables_t;
+
+/* Bytes of one packed expert with intermediate size `inter` (0 on invalid arguments).  A slot and a
+ * host blob are moe_blob_bytes(fmt, hidden, cfg.inter); the shared blob uses cfg.shared_inter. */
+size_t moe_blob_bytes(int32_t weight_fmt, int32_t hidden, int32_t inter);
+
+/* Pack one expert from canonical row-major weights into the blob layout the kernels stream
+ * (record i = gate row i | up row i | column i of down).  All pointers are device memory:
+ *  fp32/bf16: gate,up [I,d], down [d,I] of that type; scale pointers NULL.
+ *  int8: int8 values as above, fp16 scales gate_s,up_s [I], down_s [d] (one per output row).
+ *  int4: bytes [I,d/2], [I,d/2], [d,I/2] (nibble = q+8, even column low), fp16 scales
+ *        [I,d/128], [I,d/128], [d,I/128] (Sec. 4.5 names 4- and 8-bit weights; the format is ours).
+ * Runs asynchronously on `stream`.  MOE_EINVAL on bad shapes/NULLs, MOE_EHIP on launch failure. */
+int moe_pack_expert(int32_t weight_fmt, int32_t hidden, int32_t inter, const void *gate, const void *up,
+                    const void *down, const void *gate_s, const void *up_s, const void *down_s, void *blob_dev,
+                    void *stream);
+
+/* Create a context (problem statement of Sec. 2.1-2.2 and 3.3).  Validates everything before touching
+ * the GPU (MOE_EINVAL), preloads initial residents synchronously, leaves the cache otherwise empty. */
+int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *bufs, moe_cache_t **out);
+void moe_cache_destroy(moe_cache_t *ctx);
+
+/* Routing step of one layer for one token (Eq. 3, Eq. 9-10, Eq. 4, Sec. 4.2): exactly one of x_dev
+ * (device [d], act_fmt: the router GEMV is computed) and logits_dev (device [N] fp32: used as z) is
+ * non-NULL.  On return the decision is known on the host, written to *out_host if non-NULL, and the
+ * copies filling missed experts' slots are enqueued on copy_stream.  MOE_ESTATE if the layer's
+ * previous step has not been followed by moe_expert_forward. */
+int moe_route_step(moe_cache_t *ctx, int32_t layer, const void *x_dev, const float *logits_dev,
+                   moe_route_out_t *out_host);
+
+/* Eq. 1 for the layer's last routing step: y = sum_k w_k E_k(x) + shared(x); x_dev, y_dev device [d]
+ * in act_fmt.  Asynchronous on compute_stream (which first waits for the step's miss fills).
+ * MOE_ESTATE without a preceding moe_route_step. */
+int moe_expert_forward(moe_cache_t *ctx, int32_t layer, const void *x_dev, void *y_dev);
+
+/* Counters of one layer, or summed over layers with layer = -1 (Eq. 4 numerators/denominators).
+ * Synchronises compute_stream. */
+int moe_cache_stats(moe_cache_t *ctx, int32_t layer, moe_cache_stats_t *out_host);
+/* Slot table, stamps and Delta accumulator of one layer.  Synchronises compute_stream. */
+int moe_cache_tables(moe_cache_t *ctx, int32_t layer, moe_cache_tables_t *out_host);
+/* Change lambda (and for the baselines M / p) between steps. */
+int moe_cache_set_lambda(moe_cache_t *ctx, float lambda);
+int moe_cache_set_baseline(moe_cache_t *ctx, int32_t route_mode, int32_t max_rank, float cumsum_p);
+/* Empty every layer's cache (then preload the initial residents again), zero Delta_avg and counters. */
+int moe_cache_reset(moe_cache_t *ctx);
+
+/* Workload glue for multi-layer synthetic stacks (not part of the paper's method):
+ * h += y + perturb * a (a may be NULL); x = h / sqrt(mean(h^2) + 1e-6) rounded to act_fmt.
+ * h: device fp32 [d] in/out; y: device act_fmt [d] or NULL; a: device fp32 [d] or NULL; x: device act_fmt [d]. */
+int moe_residual_rmsnorm(float *h_dev, const void *y_dev, const float *a_dev, float perturb, void *x_dev,
+                         int32_t hidden, int32_t act_fmt, void *stream);
+
+/* Average duration in microseconds of the expert-GEMV kernel launches since the last call with
+ * reset != 0 (measured with events on compute_stream when profiling is on), and their count. */
+int moe_cache_profile(moe_cache_t *ctx, int32_t enable, int32_t reset, double *avg_us, int64_t *launches);
+
+const char *moe_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_CACHE_H */

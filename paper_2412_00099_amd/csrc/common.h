@@ -1,0 +1,95 @@
+// Internal declarations shared by the translation units of libmoe_cache (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "moe_cache.h"
+
+namespace moe {
+
+constexpr int kWave = 64;
+
+// Per-layer cache state, device resident.  One wavefront owns it during a routing step:
+// lane e holds expert e's entries, lane s holds slot s's entry.
+struct LayerState {
+  int32_t expert_slot[MOE_MAX_EXPERTS];  // expert -> slot, -1 = not resident
+  int32_t slot_expert[MOE_MAX_EXPERTS];  // slot -> expert, -1 = empty
+  int64_t stamp[MOE_MAX_EXPERTS];        // recency stamp per expert (valid while resident)
+  uint64_t ever_used;                    // bit s: slot s has held an expert
+  float delta_sum;                       // Eq. 10 accumulator
+  int32_t count;                         // tokens routed
+  int64_t selections, hits, misses, cold_misses, evictions;
+};
+
+struct RouteParams {
+  int32_t n_experts, top_k, top_j, capacity, hidden;
+  int32_t act_fmt, renormalize, delta_mode, route_mode, max_rank;
+  float lambda, delta_fixed, cumsum_p;
+  uint32_t seq;
+};
+
+struct GemvParams {
+  const uint8_t *slot_pool;      // this layer's slots
+  const uint8_t *shared_blob;    // or nullptr
+  const moe_route_out_t *route;  // device record of the layer's last routing step
+  const void *x;                 // [d] act_fmt
+  float *partial;                // [grid][d] fp32
+  int32_t hidden, inter, shared_inter, top_k, act_fmt;
+  int64_t slot_bytes;
+};
+
+// Blob geometry (see moe_blob_bytes).
+struct BlobLayout {
+  int64_t rec_bytes;    // bytes of one record (gate row | up row | down column [| inline scales])
+  int64_t row_bytes;    // bytes of one d-long row of weights
+  int64_t tail_offset;  // start of the out-of-record scales
+  int64_t total;        // whole blob, multiple of 256
+};
+BlobLayout blob_layout(int fmt, int hidden, int inter);
+
+// launchers (each returns the hipError_t of the launch)
+hipError_t launch_route(const RouteParams &p, const void *gate_w, const void *x, const float *logits,
+                        LayerState *state, moe_route_out_t *out_dev, moe_route_out_t *out_host_mapped,
+                        hipStream_t s);
+hipError_t launch_expert_gemv(const GemvParams &p, int weight_fmt, int grid, hipStream_t s);
+hipError_t launch_partial_reduce(const float *partial, int n_partial, void *y, int hidden, int act_fmt,
+                                 hipStream_t s);
+hipError_t launch_pack(int fmt, int hidden, int inter, const void *gate, const void *up, const void *down,
+                       const void *gs, const void *us, const void *ds, void *blob, hipStream_t s);
+hipError_t launch_residual_rmsnorm(float *h, const void *y, const float *a, float perturb, void *x, int hidden,
+                                   int act_fmt, hipStream_t s);
+hipError_t launch_state_init(LayerState *state, int n_layers, const int32_t *initial_dev, int n_initial,
+                             hipStream_t s);
+bool gemv_shape_supported(int weight_fmt, int hidden);
+
+// ---- device helpers -------------------------------------------------------------------------
+#if defined(__HIPCC__)
+__device__ __forceinline__ float bf16_lo(uint32_t v) { return __uint_as_float(v << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t v) { return __uint_as_float(v & 0xffff0000u); }
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // NaN stays NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+// Sum over the 64 lanes, result in every lane, fixed order (rotations inside rows of 16, then rows).
+__device__ __forceinline__ float wave_sum(float v) {
+  v += dpp_f32<0x128>(v);  // row_ror:8
+  v += dpp_f32<0x124>(v);  // row_ror:4
+  v += dpp_f32<0x122>(v);  // row_ror:2
+  v += dpp_f32<0x121>(v);  // row_ror:1
+  float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+  float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+  float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+  float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+  return (r0 + r1) + (r2 + r3);
+}
+#endif
+
+}  // namespace moe

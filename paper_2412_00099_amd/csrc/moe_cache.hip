@@ -1,0 +1,445 @@
+// Host side of libmoe_cache: argument checking, the context, the per-layer step sequence
+// (route kernel -> host learns the misses -> fills on the copy stream -> expert kernels) and statistics.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <chrono>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "common.h"
+
+using namespace moe;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char *fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                        \
+  do {                                                                                       \
+    hipError_t e_ = (expr);                                                                  \
+    if (e_ != hipSuccess) return fail(MOE_EHIP, "%s: %s", #expr, hipGetErrorString(e_));     \
+  } while (0)
+
+bool valid_wfmt(int f) { return f >= MOE_W_FP32 && f <= MOE_W_INT4_G128; }
+bool valid_afmt(int f) { return f == MOE_A_FP32 || f == MOE_A_BF16; }
+
+}  // namespace
+
+struct moe_cache {
+  moe_cache_config_t cfg{};
+  std::vector<const void *> host_blob;
+  std::vector<void *> slot_pool;
+  std::vector<const void *> gate_w;
+  std::vector<const void *> shared_blob;
+  std::vector<int32_t> initial;
+  int32_t n_initial = 0;
+  BlobLayout slot_layout{};
+  hipStream_t compute = nullptr, copy = nullptr;
+
+  LayerState *d_state = nullptr;
+  moe_route_out_t *d_route = nullptr;
+  moe_route_out_t *h_route = nullptr;      // pinned, mapped
+  moe_route_out_t *h_route_dev = nullptr;  // device view of h_route
+  int32_t *d_initial = nullptr;
+  float *d_partial = nullptr;
+  int gemv_grid = 0;
+  hipEvent_t ev_route = nullptr;
+  std::vector<hipEvent_t> ev_copy;
+  std::vector<uint8_t> routed;        // per layer: a route step awaits its expert_forward
+  std::vector<uint8_t> copy_pending;  // per layer: fills were enqueued for the pending step
+  std::vector<int64_t> bytes_filled;
+  uint32_t seq = 0;
+  bool poll = false;
+
+  // optional timing of the expert GEMV launches
+  bool profiling = false;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_events;
+  size_t prof_used = 0;
+};
+
+namespace {
+
+int check_layer(const moe_cache_t *ctx, int32_t layer) {
+  if (!ctx) return fail(MOE_EINVAL, "context is NULL");
+  if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(MOE_EINVAL, "layer %d out of range [0,%d)", layer, ctx->cfg.n_layers);
+  return MOE_OK;
+}
+
+int do_reset(moe_cache_t *c) {
+  HIP_TRY(hipStreamSynchronize(c->compute));
+  HIP_TRY(hipStreamSynchronize(c->copy));
+  if (c->n_initial > 0)
+    HIP_TRY(hipMemcpy(c->d_initial, c->initial.data(), c->initial.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+  HIP_TRY(launch_state_init(c->d_state, c->cfg.n_layers, c->d_initial, c->n_initial, c->compute));
+  const int N = c->cfg.n_experts;
+  for (int l = 0; l < c->cfg.n_layers; ++l) {
+    for (int i = 0; i < c->n_initial; ++i) {
+      const int e = c->initial[(size_t)l * c->n_initial + i];
+      HIP_TRY(hipMemcpy(static_cast<uint8_t *>(c->slot_pool[l]) + (size_t)i * c->slot_layout.total,
+                        c->host_blob[(size_t)l * N + e], c->slot_layout.total, hipMemcpyHostToDevice));
+    }
+    c->routed[l] = 0;
+    c->copy_pending[l] = 0;
+    c->bytes_filled[l] = 0;
+  }
+  HIP_TRY(hipStreamSynchronize(c->compute));
+  return MOE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *moe_last_error(void) { return g_err.c_str(); }
+
+size_t moe_blob_bytes(int32_t weight_fmt, int32_t hidden, int32_t inter) {
+  if (!valid_wfmt(weight_fmt) || hidden <= 0 || inter <= 0) return 0;
+  if (!gemv_shape_supported(weight_fmt, hidden)) return 0;
+  return (size_t)blob_layout(weight_fmt, hidden, inter).total;
+}
+
+int moe_pack_expert(int32_t weight_fmt, int32_t hidden, int32_t inter, const void *gate, const void *up,
+                    const void *down, const void *gate_s, const void *up_s, const void *down_s, void *blob_dev,
+                    void *stream) {
+  if (!valid_wfmt(weight_fmt)) return fail(MOE_EINVAL, "unknown weight format %d", weight_fmt);
+  if (hidden <= 0 || inter <= 0 || !gemv_shape_supported(weight_fmt, hidden))
+    return fail(MOE_EINVAL, "unsupported shape hidden=%d inter=%d for weight format %d", hidden, inter, weight_fmt);
+  if (!gate || !up || !down || !blob_dev) return fail(MOE_EINVAL, "NULL weight or blob pointer");
+  const bool quant = weight_fmt == MOE_W_INT8_PC || weight_fmt == MOE_W_INT4_G128;
+  if (quant && (!gate_s || !up_s || !down_s)) return fail(MOE_EINVAL, "quantised format needs scale pointers");
+  HIP_TRY(launch_pack(weight_fmt, hidden, inter, gate, up, down, gate_s, up_s, down_s, blob_dev,
+                      static_cast<hipStream_t>(stream)));
+  return MOE_OK;
+}
+
+int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, moe_cache_t **out) {
+  if (!out) return fail(MOE_EINVAL, "out is NULL");
+  *out = nullptr;
+  if (!cfg || !b) return fail(MOE_EINVAL, "config or buffers is NULL");
+  // ---- everything below is checked before the first HIP call ----
+  if (cfg->n_layers <= 0) return fail(MOE_EINVAL, "n_layers must be positive");
+  if (cfg->n_experts <= 0 || cfg->n_experts > MOE_MAX_EXPERTS)
+    return fail(MOE_EINVAL, "n_experts must be in 1..%d", MOE_MAX_EXPERTS);
+  if (cfg->top_k <= 0 || cfg->top_k > MOE_MAX_TOPK) return fail(MOE_EINVAL, "top_k must be in 1..%d", MOE_MAX_TOPK);
+  if (cfg->top_j < 0 || cfg->top_j > cfg->top_k) return fail(MOE_EINVAL, "top_j must be in 0..top_k");
+  if (cfg->capacity < cfg->top_k) return fail(MOE_EINVAL, "capacity %d < top_k %d: a token's experts must all be resident", cfg->capacity, cfg->top_k);
+  if (cfg->capacity > cfg->n_experts) return fail(MOE_EINVAL, "capacity exceeds n_experts");
+  if (!valid_wfmt(cfg->weight_fmt) || !valid_afmt(cfg->act_fmt)) return fail(MOE_EINVAL, "unknown weight or activation format");
+  if (cfg->inter <= 0 || cfg->shared_inter < 0) return fail(MOE_EINVAL, "bad intermediate size");
+  if (!gemv_shape_supported(cfg->weight_fmt, cfg->hidden))
+    return fail(MOE_EINVAL, "hidden=%d unsupported for weight format %d (needs 64*{1,2,4,8} 16-byte loads per row)", cfg->hidden, cfg->weight_fmt);
+  if (cfg->hidden % 8 != 0) return fail(MOE_EINVAL, "hidden must be a multiple of 8");
+  if (!(cfg->lambda >= 0.f) || !std::isfinite(cfg->lambda)) return fail(MOE_EINVAL, "lambda must be finite and >= 0");
+  if (cfg->delta_mode != MOE_DELTA_RUNNING_MEAN && cfg->delta_mode != MOE_DELTA_FIXED) return fail(MOE_EINVAL, "bad delta_mode");
+  if (cfg->delta_mode == MOE_DELTA_FIXED && !std::isfinite(cfg->delta_fixed)) return fail(MOE_EINVAL, "delta_fixed must be finite");
+  if (cfg->route_mode < MOE_ROUTE_CACHE_PRIOR || cfg->route_mode > MOE_ROUTE_CUMSUM) return fail(MOE_EINVAL, "bad route_mode");
+  if (cfg->route_mode == MOE_ROUTE_MAX_RANK && (cfg->max_rank < 0 || cfg->max_rank > cfg->n_experts))
+    return fail(MOE_EINVAL, "max_rank must be in 0..n_experts");
+  if (cfg->route_mode == MOE_ROUTE_CUMSUM && !(cfg->cumsum_p >= 0.f)) return fail(MOE_EINVAL, "cumsum_p must be >= 0");
+  if (cfg->renormalize != 0 && cfg->renormalize != 1) return fail(MOE_EINVAL, "renormalize must be 0 or 1");
+  if (cfg->compute_stream == cfg->copy_stream) return fail(MOE_EINVAL, "copy_stream must differ from compute_stream");
+  if (!b->host_expert_blob || !b->slot_pool || !b->gate_w) return fail(MOE_EINVAL, "NULL buffer table");
+  if (cfg->shared_inter > 0 && !b->shared_blob) return fail(MOE_EINVAL, "shared_inter > 0 needs shared_blob");
+  if (b->n_initial < 0 || b->n_initial > cfg->capacity) return fail(MOE_EINVAL, "n_initial must be in 0..capacity");
+  if (b->n_initial > 0 && !b->initial_resident) return fail(MOE_EINVAL, "n_initial > 0 needs initial_resident");
+  const int L = cfg->n_layers, N = cfg->n_experts;
+  for (int l = 0; l < L; ++l) {
+    if (!b->slot_pool[l] || !b->gate_w[l]) return fail(MOE_EINVAL, "NULL slot pool or gate matrix for layer %d", l);
+    if (reinterpret_cast<uintptr_t>(b->slot_pool[l]) % 256 != 0) return fail(MOE_EINVAL, "slot pool of layer %d not 256-byte aligned", l);
+    if (cfg->shared_inter > 0 && !b->shared_blob[l]) return fail(MOE_EINVAL, "NULL shared blob for layer %d", l);
+    for (int e = 0; e < N; ++e)
+      if (!b->host_expert_blob[(size_t)l * N + e]) return fail(MOE_EINVAL, "NULL host blob for layer %d expert %d", l, e);
+    uint64_t seen = 0;
+    for (int i = 0; i < b->n_initial; ++i) {
+      const int e = b->initial_resident[(size_t)l * b->n_initial + i];
+      if (e < 0 || e >= N || ((seen >> e) & 1)) return fail(MOE_EINVAL, "initial_resident of layer %d: bad or repeated expert %d", l, e);
+      seen |= 1ull << e;
+    }
+  }
+
+  moe_cache_t *c = new (std::nothrow) moe_cache;
+  if (!c) return fail(MOE_ENOMEM, "out of host memory");
+  c->cfg = *cfg;
+  c->host_blob.assign(b->host_expert_blob, b->host_expert_blob + (size_t)L * N);
+  c->slot_pool.assign(b->slot_pool, b->slot_pool + L);
+  c->gate_w.assign(b->gate_w, b->gate_w + L);
+  if (cfg->shared_inter > 0) c->shared_blob.assign(b->shared_blob, b->shared_blob + L);
+  c->n_initial = b->n_initial;
+  if (b->n_initial > 0) c->initial.assign(b->initial_resident, b->initial_resident + (size_t)L * b->n_initial);
+  c->slot_layout = blob_layout(cfg->weight_fmt, cfg->hidden, cfg->inter);
+  c->compute = static_cast<hipStream_t>(cfg->compute_stream);
+  c->copy = static_cast<hipStream_t>(cfg->copy_stream);
+  c->routed.assign(L, 0);
+  c->copy_pending.assign(L, 0);
+  c->bytes_filled.assign(L, 0);
+  c->ev_copy.assign(L, nullptr);
+
+  auto bail = [&](int code) {
+    moe_cache_destroy(c);
+    return code;
+  };
+#define HIP_INIT(expr)                                                                      \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess) {                                                                 \
+      fail(e_ == hipErrorOutOfMemory ? MOE_ENOMEM : MOE_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+      return bail(e_ == hipErrorOutOfMemory ? MOE_ENOMEM : MOE_EHIP);                       \
+    }                                                                                       \
+  } while (0)
+
+  int dev = 0;
+  HIP_INIT(hipGetDevice(&dev));
+  int cus = 0;
+  HIP_INIT(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  int per_cu = 1;
+  if (const char *s = getenv("MOE_GEMV_WGS_PER_CU")) per_cu = atoi(s) > 0 ? atoi(s) : 1;
+  c->gemv_grid = cus * per_cu;
+  if (const char *s = getenv("MOE_GEMV_GRID")) {
+    if (atoi(s) > 0) c->gemv_grid = atoi(s);
+  }
+  const int total_rec = cfg->top_k * cfg->inter + cfg->shared_inter;
+  if (c->gemv_grid > total_rec) c->gemv_grid = total_rec;
+  if (const char *s = getenv("MOE_HOST_SYNC")) c->poll = strcmp(s, "poll") == 0;
+
+  HIP_INIT(hipMalloc(&c->d_state, sizeof(LayerState) * L));
+  HIP_INIT(hipMalloc(&c->d_route, sizeof(moe_route_out_t) * L));
+  HIP_INIT(hipMemset(c->d_route, 0, sizeof(moe_route_out_t) * L));
+  HIP_INIT(hipHostMalloc(reinterpret_cast<void **>(&c->h_route), sizeof(moe_route_out_t) * L,
+                         hipHostMallocMapped | hipHostMallocCoherent));
+  memset(c->h_route, 0, sizeof(moe_route_out_t) * L);
+  HIP_INIT(hipHostGetDevicePointer(reinterpret_cast<void **>(&c->h_route_dev), c->h_route, 0));
+  HIP_INIT(hipMalloc(&c->d_initial, sizeof(int32_t) * (size_t)L * (b->n_initial > 0 ? b->n_initial : 1)));
+  HIP_INIT(hipMalloc(&c->d_partial, sizeof(float) * (size_t)c->gemv_grid * cfg->hidden));
+  HIP_INIT(hipEventCreateWithFlags(&c->ev_route, hipEventDisableTiming));
+  for (int l = 0; l < L; ++l) HIP_INIT(hipEventCreateWithFlags(&c->ev_copy[l], hipEventDisableTiming));
+#undef HIP_INIT
+  int rc = do_reset(c);
+  if (rc != MOE_OK) return bail(rc);
+  *out = c;
+  return MOE_OK;
+}
+
+void moe_cache_destroy(moe_cache_t *c) {
+  if (!c) return;
+  (void)hipStreamSynchronize(c->compute);
+  (void)hipStreamSynchronize(c->copy);
+  if (c->d_state) (void)hipFree(c->d_state);
+  if (c->d_route) (void)hipFree(c->d_route);
+  if (c->h_route) (void)hipHostFree(c->h_route);
+  if (c->d_initial) (void)hipFree(c->d_initial);
+  if (c->d_partial) (void)hipFree(c->d_partial);
+  if (c->ev_route) (void)hipEventDestroy(c->ev_route);
+  for (hipEvent_t e : c->ev_copy)
+    if (e) (void)hipEventDestroy(e);
+  for (auto &pr : c->prof_events) {
+    (void)hipEventDestroy(pr.first);
+    (void)hipEventDestroy(pr.second);
+  }
+  delete c;
+}
+
+int moe_route_step(moe_cache_t *c, int32_t layer, const void *x_dev, const float *logits_dev,
+                   moe_route_out_t *out_host) {
+  if (int rc = check_layer(c, layer)) return rc;
+  if ((x_dev == nullptr) == (logits_dev == nullptr)) return fail(MOE_EINVAL, "exactly one of x_dev and logits_dev must be given");
+  if (c->routed[layer]) return fail(MOE_ESTATE, "layer %d: previous route step not followed by moe_expert_forward", layer);
+  const moe_cache_config_t &g = c->cfg;
+  RouteParams p{};
+  p.n_experts = g.n_experts;
+  p.top_k = g.top_k;
+  p.top_j = g.top_j;
+  p.capacity = g.capacity;
+  p.hidden = g.hidden;
+  p.act_fmt = g.act_fmt;
+  p.renormalize = g.renormalize;
+  p.delta_mode = g.delta_mode;
+  p.route_mode = g.route_mode;
+  p.max_rank = g.max_rank;
+  p.lambda = g.lambda;
+  p.delta_fixed = g.delta_fixed;
+  p.cumsum_p = g.cumsum_p;
+  if (++c->seq == 0) c->seq = 1;
+  p.seq = c->seq;
+  moe_route_out_t *h = c->h_route + layer;
+  HIP_TRY(launch_route(p, c->gate_w[layer], x_dev, logits_dev, c->d_state + layer, c->d_route + layer,
+                       c->h_route_dev + layer, c->compute));
+  bool seen = false;
+  if (c->poll) {
+    // the kernel stores the record to mapped host memory and then the tag, with a system-scope release
+    const auto t0 = std::chrono::steady_clock::now();
+    volatile uint32_t *tag = &h->seq;
+    for (uint32_t spin = 0;; ++spin) {
+      if (__atomic_load_n(tag, __ATOMIC_ACQUIRE) == p.seq) {
+        seen = true;
+        break;
+      }
+      if ((spin & 0x3ff) == 0x3ff &&
+          std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(200))
+        break;  // fall back to a stream synchronisation (also surfaces launch errors)
+    }
+  }
+  if (!seen) {
+    HIP_TRY(hipEventRecord(c->ev_route, c->compute));
+    HIP_TRY(hipEventSynchronize(c->ev_route));
+    if (h->seq != p.seq) return fail(MOE_EHIP, "route kernel of layer %d did not publish its result", layer);
+  }
+  const size_t slot_bytes = (size_t)c->slot_layout.total;
+  if (h->n_miss > 0) {
+    for (int k = 0; k < g.top_k; ++k) {
+      if (!h->miss[k]) continue;
+      const int e = h->sel_expert[k], s = h->sel_slot[k];
+      if (e < 0 || e >= g.n_experts || s < 0 || s >= g.capacity)
+        return fail(MOE_EHIP, "route kernel returned expert %d slot %d out of range", e, s);
+      HIP_TRY(hipMemcpyAsync(static_cast<uint8_t *>(c->slot_pool[layer]) + (size_t)s * slot_bytes,
+                             c->host_blob[(size_t)layer * g.n_experts + e], slot_bytes, hipMemcpyHostToDevice,
+                             c->copy));
+      c->bytes_filled[layer] += (int64_t)slot_bytes;
+    }
+    HIP_TRY(hipEventRecord(c->ev_copy[layer], c->copy));
+    c->copy_pending[layer] = 1;
+  }
+  c->routed[layer] = 1;
+  if (out_host) *out_host = *h;
+  return MOE_OK;
+}
+
+int moe_expert_forward(moe_cache_t *c, int32_t layer, const void *x_dev, void *y_dev) {
+  if (int rc = check_layer(c, layer)) return rc;
+  if (!x_dev || !y_dev) return fail(MOE_EINVAL, "x_dev or y_dev is NULL");
+  if (!c->routed[layer]) return fail(MOE_ESTATE, "layer %d: moe_expert_forward without a preceding moe_route_step", layer);
+  const moe_cache_config_t &g = c->cfg;
+  if (c->copy_pending[layer]) {
+    HIP_TRY(hipStreamWaitEvent(c->compute, c->ev_copy[layer], 0));
+    c->copy_pending[layer] = 0;
+  }
+  GemvParams p{};
+  p.slot_pool = static_cast<const uint8_t *>(c->slot_pool[layer]);
+  p.shared_blob = g.shared_inter > 0 ? static_cast<const uint8_t *>(c->shared_blob[layer]) : nullptr;
+  p.route = c->d_route + layer;
+  p.x = x_dev;
+  p.partial = c->d_partial;
+  p.hidden = g.hidden;
+  p.inter = g.inter;
+  p.shared_inter = g.shared_inter;
+  p.top_k = g.top_k;
+  p.act_fmt = g.act_fmt;
+  p.slot_bytes = c->slot_layout.total;
+  const bool prof = c->profiling && c->prof_used < (1u << 16);
+  if (prof) {
+    if (c->prof_used == c->prof_events.size()) {
+      hipEvent_t a, b;
+      HIP_TRY(hipEventCreate(&a));
+      HIP_TRY(hipEventCreate(&b));
+      c->prof_events.emplace_back(a, b);
+    }
+    HIP_TRY(hipEventRecord(c->prof_events[c->prof_used].first, c->compute));
+  }
+  HIP_TRY(launch_expert_gemv(p, g.weight_fmt, c->gemv_grid, c->compute));
+  if (prof) {
+    HIP_TRY(hipEventRecord(c->prof_events[c->prof_used].second, c->compute));
+    ++c->prof_used;
+  }
+  HIP_TRY(launch_partial_reduce(c->d_partial, c->gemv_grid, y_dev, g.hidden, g.act_fmt, c->compute));
+  c->routed[layer] = 0;
+  return MOE_OK;
+}
+
+int moe_cache_stats(moe_cache_t *c, int32_t layer, moe_cache_stats_t *out) {
+  if (!c || !out) return fail(MOE_EINVAL, "NULL argument");
+  if (layer != -1)
+    if (int rc = check_layer(c, layer)) return rc;
+  HIP_TRY(hipStreamSynchronize(c->compute));
+  std::vector<LayerState> st(c->cfg.n_layers);
+  HIP_TRY(hipMemcpy(st.data(), c->d_state, sizeof(LayerState) * st.size(), hipMemcpyDeviceToHost));
+  memset(out, 0, sizeof *out);
+  for (int l = 0; l < c->cfg.n_layers; ++l) {
+    if (layer != -1 && l != layer) continue;
+    out->tokens += st[l].count;
+    out->selections += st[l].selections;
+    out->hits += st[l].hits;
+    out->misses += st[l].misses;
+    out->cold_misses += st[l].cold_misses;
+    out->evictions += st[l].evictions;
+    out->bytes_filled += c->bytes_filled[l];
+  }
+  return MOE_OK;
+}
+
+int moe_cache_tables(moe_cache_t *c, int32_t layer, moe_cache_tables_t *out) {
+  if (int rc = check_layer(c, layer)) return rc;
+  if (!out) return fail(MOE_EINVAL, "out is NULL");
+  HIP_TRY(hipStreamSynchronize(c->compute));
+  LayerState st;
+  HIP_TRY(hipMemcpy(&st, c->d_state + layer, sizeof st, hipMemcpyDeviceToHost));
+  memcpy(out->expert_slot, st.expert_slot, sizeof out->expert_slot);
+  memcpy(out->slot_expert, st.slot_expert, sizeof out->slot_expert);
+  memcpy(out->stamp, st.stamp, sizeof out->stamp);
+  out->delta_sum = st.delta_sum;
+  out->count = st.count;
+  return MOE_OK;
+}
+
+int moe_cache_set_lambda(moe_cache_t *c, float lambda) {
+  if (!c) return fail(MOE_EINVAL, "context is NULL");
+  if (!(lambda >= 0.f) || !std::isfinite(lambda)) return fail(MOE_EINVAL, "lambda must be finite and >= 0");
+  c->cfg.lambda = lambda;
+  return MOE_OK;
+}
+
+int moe_cache_set_baseline(moe_cache_t *c, int32_t route_mode, int32_t max_rank, float cumsum_p) {
+  if (!c) return fail(MOE_EINVAL, "context is NULL");
+  if (route_mode < MOE_ROUTE_CACHE_PRIOR || route_mode > MOE_ROUTE_CUMSUM) return fail(MOE_EINVAL, "bad route_mode");
+  if (route_mode == MOE_ROUTE_MAX_RANK && (max_rank < 0 || max_rank > c->cfg.n_experts))
+    return fail(MOE_EINVAL, "max_rank must be in 0..n_experts");
+  if (route_mode == MOE_ROUTE_CUMSUM && !(cumsum_p >= 0.f)) return fail(MOE_EINVAL, "cumsum_p must be >= 0");
+  c->cfg.route_mode = route_mode;
+  c->cfg.max_rank = max_rank;
+  c->cfg.cumsum_p = cumsum_p;
+  return MOE_OK;
+}
+
+int moe_cache_reset(moe_cache_t *c) {
+  if (!c) return fail(MOE_EINVAL, "context is NULL");
+  return do_reset(c);
+}
+
+int moe_residual_rmsnorm(float *h_dev, const void *y_dev, const float *a_dev, float perturb, void *x_dev,
+                         int32_t hidden, int32_t act_fmt, void *stream) {
+  if (!h_dev || !x_dev) return fail(MOE_EINVAL, "h_dev or x_dev is NULL");
+  if (hidden <= 0 || !valid_afmt(act_fmt)) return fail(MOE_EINVAL, "bad hidden or act_fmt");
+  HIP_TRY(launch_residual_rmsnorm(h_dev, y_dev, a_dev, perturb, x_dev, hidden, act_fmt,
+                                  static_cast<hipStream_t>(stream)));
+  return MOE_OK;
+}
+
+int moe_cache_profile(moe_cache_t *c, int32_t enable, int32_t reset, double *avg_us, int64_t *launches) {
+  if (!c) return fail(MOE_EINVAL, "context is NULL");
+  HIP_TRY(hipStreamSynchronize(c->compute));
+  double total_ms = 0.0;
+  for (size_t i = 0; i < c->prof_used; ++i) {
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, c->prof_events[i].first, c->prof_events[i].second));
+    total_ms += ms;
+  }
+  if (avg_us) *avg_us = c->prof_used ? total_ms * 1000.0 / (double)c->prof_used : 0.0;
+  if (launches) *launches = (int64_t)c->prof_used;
+  if (reset) c->prof_used = 0;
+  c->profiling = enable != 0;
+  return MOE_OK;
+}
+
+}  // extern "C"

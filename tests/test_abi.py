@@ -1,0 +1,108 @@
+"""CPU-side checks of the C ABI: the library loads, exports what the header declares, validates arguments."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2412_00099_amd import binding
+
+    return binding
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "moe_cache.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(B):
+    names = declared_functions()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(B.lib, n), f"{n} declared in moe_cache.h but not exported"
+    assert sorted(B.EXPORTS) == names
+
+
+def test_struct_sizes_match_header(B):
+    assert C.sizeof(B.moe_route_out_t) == 4 * (5 * 8 + 4 + 64 + 4)
+    assert C.sizeof(B.moe_cache_stats_t) == 56
+    assert C.sizeof(B.moe_cache_tables_t) == 64 * 4 * 2 + 64 * 8 + 8
+    assert C.sizeof(B.moe_cache_config_t) == 18 * 4 + 16
+
+
+def test_blob_bytes(B):
+    # record = gate row | up row | down column, I records
+    assert B.moe_blob_bytes(B.MOE_W_BF16, 2048, 1408) == 3 * 2048 * 1408 * 2
+    assert B.moe_blob_bytes(B.MOE_W_FP32, 256, 512) == 3 * 256 * 512 * 4
+    assert B.moe_blob_bytes(B.MOE_W_BF16, 2048, 1408) % 256 == 0
+    assert B.moe_blob_bytes(B.MOE_W_BF16, 100, 64) == 0  # hidden not a multiple of 512
+    assert B.moe_blob_bytes(7, 2048, 64) == 0
+
+
+def _cfg(B, **kw):
+    c = B.moe_cache_config_t()
+    c.n_layers, c.hidden, c.n_experts, c.inter, c.shared_inter = 1, 256, 16, 512, 0
+    c.top_k, c.top_j, c.capacity = 2, 0, 8
+    c.weight_fmt, c.act_fmt = B.MOE_W_FP32, B.MOE_A_FP32
+    c.lambda_ = 0.5
+    c.compute_stream, c.copy_stream = 1, 2  # never dereferenced: validation fails first
+    for k, v in kw.items():
+        setattr(c, k, v)
+    return c
+
+
+@pytest.mark.parametrize(
+    "bad",
+    [
+        dict(n_layers=0), dict(n_experts=65), dict(top_k=9), dict(top_k=0), dict(top_j=3), dict(capacity=1),
+        dict(capacity=17), dict(weight_fmt=9), dict(act_fmt=2), dict(hidden=100), dict(inter=0),
+        dict(lambda_=-1.0), dict(lambda_=float("nan")), dict(copy_stream=1), dict(route_mode=5), dict(renormalize=2),
+        dict(shared_inter=128),  # needs shared_blob
+    ],
+)
+def test_init_rejects_bad_config_without_touching_the_gpu(B, bad):
+    cfg = _cfg(B, **bad)
+    bufs = B.moe_cache_buffers_t()
+    host = (C.c_void_p * 16)(*([0x1000] * 16))
+    one = (C.c_void_p * 1)(0x100000)
+    bufs.host_expert_blob, bufs.slot_pool, bufs.gate_w = host, one, one
+    out = C.c_void_p()
+    rc = B.lib.moe_cache_init(C.byref(cfg), C.byref(bufs), C.byref(out))
+    assert rc == B.MOE_EINVAL and not out.value
+    assert B.moe_last_error()
+
+
+def test_init_rejects_null_tables_and_bad_initial(B):
+    out = C.c_void_p()
+    assert B.lib.moe_cache_init(None, None, C.byref(out)) == B.MOE_EINVAL
+    cfg = _cfg(B)
+    bufs = B.moe_cache_buffers_t()
+    assert B.lib.moe_cache_init(C.byref(cfg), C.byref(bufs), C.byref(out)) == B.MOE_EINVAL
+    host = (C.c_void_p * 16)(*([0x1000] * 16))
+    one = (C.c_void_p * 1)(0x100000)
+    bufs.host_expert_blob, bufs.slot_pool, bufs.gate_w = host, one, one
+    bufs.n_initial = 2
+    bufs.initial_resident = (C.c_int32 * 2)(3, 3)  # repeated expert
+    assert B.lib.moe_cache_init(C.byref(cfg), C.byref(bufs), C.byref(out)) == B.MOE_EINVAL
+    assert "repeated" in B.moe_last_error()
+    unaligned = (C.c_void_p * 1)(0x100010)
+    bufs.n_initial = 0
+    bufs.slot_pool = unaligned
+    assert B.lib.moe_cache_init(C.byref(cfg), C.byref(bufs), C.byref(out)) == B.MOE_EINVAL
+
+
+def test_null_context_calls_fail_cleanly(B):
+    assert B.lib.moe_route_step(None, 0, None, None, None) == B.MOE_EINVAL
+    assert B.lib.moe_expert_forward(None, 0, None, None) == B.MOE_EINVAL
+    assert B.lib.moe_cache_stats(None, 0, None) == B.MOE_EINVAL
+    assert B.lib.moe_cache_set_lambda(None, 0.0) == B.MOE_EINVAL
+    assert B.lib.moe_cache_reset(None) == B.MOE_EINVAL
+    assert B.lib.moe_pack_expert(B.MOE_W_BF16, 2048, 64, None, None, None, None, None, None, None, None) == B.MOE_EINVAL
+    assert B.lib.moe_residual_rmsnorm(None, None, None, 0.5, None, 256, 0, None) == B.MOE_EINVAL
+    B.lib.moe_cache_destroy(None)
