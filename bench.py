@@ -1,0 +1,257 @@
+"""Benchmark of the batch-1 MoE decode path with cache-conditional routing on one MI355X.
+
+Workload (config.workload): the Qwen1.5-MoE-A2.7B-shaped stack, bf16, attention omitted - 24 layers,
+hidden 2048, 60 routed experts of intermediate 1408 (top-4) plus a shared SwiGLU of intermediate 5632,
+30 of 60 experts cached per layer, random N(0, 0.02) weights, AR(1) (rho = 0.9) hidden-state streams with
+a residual add between layers.  A step is one decode token through all layers: per layer the stack glue,
+the fused router kernel, the miss fills and the expert GEMV.  All weights and inputs are resident (device
+slots / pinned host tier) before the timed region.
+
+Prints ONE JSON line.  `value` is tokens/s at the headline strength lambda = 0.5; `roofline` is the expert
+GEMV kernel (HIP events on the compute stream around every launch, in a second pass over the same tokens);
+`cpu_baseline` is the CPU oracle on the first tokens of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+HEADLINE_LAMBDA = 0.5
+PERTURB = 0.5
+
+
+def log(msg):
+    print(f"[bench] {msg}", file=sys.stderr, flush=True)
+
+
+def decode_tokens(dec, a, h, x, y, t0, t1):
+    """Tokens t0..t1-1 through the whole stack (all calls asynchronous except the router's host hand-off)."""
+    L = dec.store.L
+    for t in range(t0, t1):
+        for l in range(L):
+            # h_0 = a[t,0]; h_{l} = h_{l-1} + y_{l-1} + 0.5 a[t,l]; x_l = rmsnorm(h_l)
+            if l == 0:
+                dec.residual_rmsnorm(h, None, a[t, 0], 1.0, x, carry=False)
+            else:
+                dec.residual_rmsnorm(h, y, a[t, l], PERTURB, x, carry=True)
+            dec.route_step(l, x=x)
+            dec.expert_forward(l, x, y)
+
+
+def timed_run(dec, a, h, x, y, warmup, steps):
+    import torch
+
+    dec.reset()
+    decode_tokens(dec, a, h, x, y, 0, warmup)
+    torch.cuda.synchronize()
+    s0 = dec.stats()
+    t_start = time.perf_counter()
+    decode_tokens(dec, a, h, x, y, warmup, warmup + steps)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    s1 = dec.stats()
+    sel = s1.selections - s0.selections
+    return dict(
+        tok_s=steps / elapsed, ms_per_step=1e3 * elapsed / steps,
+        miss_rate=(s1.misses - s0.misses) / max(sel, 1),
+        miss_rate_incl_warmup=s1.misses / max(s1.selections, 1),
+        cold_misses=s1.cold_misses, misses=s1.misses - s0.misses,
+        host_link_bytes=s1.bytes_filled - s0.bytes_filled,
+    )
+
+
+def cpu_oracle_baseline(cfg, store_weights, a_cpu, n_tokens):
+    """The oracle, as it stands, on the first n_tokens of the same workload; returns tok/s."""
+    import numpy as np
+
+    from oracle import experts as oexp
+    from oracle import routing, stack
+
+    L, N, K = cfg.n_layers, cfg.n_experts, cfg.top_k
+    routers = [routing.CachePriorRouter(N, K, cfg.capacity, HEADLINE_LAMBDA, cfg.top_j, cfg.renormalize) for _ in range(L)]
+    t0 = time.perf_counter()
+    for t in range(n_tokens):
+        h = a_cpu[t, 0].astype(np.float64)
+        for l in range(L):
+            x = stack.rmsnorm(h).astype(np.float32)
+            z = routing.router_logits(store_weights.gate(l), x)
+            res = routers[l].step(z)
+            y = oexp.moe_output(x, [store_weights.expert(l, int(e)) for e in res.sel], res.weight,
+                                store_weights.shared(l))
+            if l + 1 < L:
+                h = stack.next_hidden(h, y, a_cpu[t, l + 1])
+    return n_tokens / (time.perf_counter() - t0)
+
+
+class LazyWeights:
+    """Canonical weights for the oracle, regenerated from the workload seeds on demand."""
+
+    def __init__(self, cfg, device):
+        from synth import workloads
+
+        self.cfg, self.dev, self.w = cfg, device, workloads
+        self.cache = {}
+
+    @staticmethod
+    def _np(d):
+        return {k: v.float().cpu().numpy() for k, v in d.items()}
+
+    def expert(self, l, e):
+        if (l, e) not in self.cache:
+            self.cache[(l, e)] = self._np(self.w.expert_weights(self.cfg, l, e, self.dev))
+        return self.cache[(l, e)]
+
+    def shared(self, l):
+        if not self.cfg.shared_inter:
+            return None
+        if (l, "s") not in self.cache:
+            self.cache[(l, "s")] = self._np(self.w.shared_weights(self.cfg, l, self.dev))
+        return self.cache[(l, "s")]
+
+    def gate(self, l):
+        if (l, "g") not in self.cache:
+            self.cache[(l, "g")] = self.w.gate_weight(self.cfg, l, self.dev).float().cpu().numpy()
+        return self.cache[(l, "g")]
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=960)
+    ap.add_argument("--warmup", type=int, default=64)
+    ap.add_argument("--workload", default="c2_qwen_bf16")
+    ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debugging)")
+    ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--cpu-tokens", type=int, default=2)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; the path has no multi-GPU part (see DESIGN.md). "
+              "Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2412_00099_amd as pkg
+    from synth import workloads
+    from synth.workloads import CONFIGS
+
+    cfg = CONFIGS[args.workload]
+    if args.layers:
+        cfg = cfg.with_(n_layers=args.layers)
+    T = args.warmup + args.steps
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    t0 = time.perf_counter()
+    store = pkg.ExpertStore(n_layers=cfg.n_layers, hidden=cfg.hidden, n_experts=cfg.n_experts, inter=cfg.inter,
+                            shared_inter=cfg.shared_inter, capacity=cfg.capacity, weight_fmt=cfg.weight_fmt,
+                            act_fmt=cfg.act_fmt, device=dev)
+    log(f"allocated tiers: host {store.host.numel() / 1e9:.1f} GB pinned, slots {store.pools.numel() / 1e9:.1f} GB")
+    store.fill_from(cfg, workloads.expert_weights, workloads.shared_weights, workloads.gate_weight,
+                    progress=lambda l: log(f"layer {l} packed") if l % 6 == 5 else None)
+    a = workloads.ar1_stream(cfg, T, device=dev)
+    log(f"setup {time.perf_counter() - t0:.1f} s")
+    dec = pkg.MoEDecoder(store, top_k=cfg.top_k, top_j=cfg.top_j, lam=HEADLINE_LAMBDA, renormalize=cfg.renormalize)
+    h = torch.zeros(cfg.hidden, dtype=torch.float32, device=dev)
+    x = torch.zeros(cfg.hidden, dtype=cfg.act_dtype, device=dev)
+    y = torch.zeros(cfg.hidden, dtype=cfg.act_dtype, device=dev)
+    torch.cuda.synchronize()
+
+    # ---- headline: lambda = 0.5 ---------------------------------------------------------------
+    head = timed_run(dec, a, h, x, y, args.warmup, args.steps)
+    log(f"lambda={HEADLINE_LAMBDA}: {head['tok_s']:.1f} tok/s, miss rate {head['miss_rate']:.4f}")
+
+    # ---- expert-GEMV kernel time: events around each launch, second pass over the same tokens ----
+    dec.profile(True, reset=True)
+    prof = timed_run(dec, a, h, x, y, args.warmup, args.steps)
+    gemv_us, gemv_launches = dec.profile(False, reset=True)
+    el = 2 if cfg.weight_fmt == "bf16" else 4
+    algo_bytes = cfg.top_k * store.blob_bytes + store.shared_bytes
+    achieved = algo_bytes / (gemv_us * 1e-6) / 1e9 if gemv_us > 0 else 0.0
+    log(f"expert GEMV: {gemv_us:.2f} us avg over {gemv_launches} launches -> {achieved:.0f} GB/s")
+
+    sweep = {}
+    if not args.no_sweep:
+        for lam in (0.0, 0.25, 1.0):
+            dec.set_lambda(lam)
+            r = timed_run(dec, a, h, x, y, args.warmup, args.steps)
+            sweep[str(lam)] = dict(tok_s=round(r["tok_s"], 2), miss_rate=round(r["miss_rate"], 5),
+                                   host_link_GB=round(r["host_link_bytes"] / 1e9, 3))
+            log(f"lambda={lam}: {r['tok_s']:.1f} tok/s, miss rate {r['miss_rate']:.4f}")
+        # miss-free run: with an overwhelming prior the cache freezes after warm-up (Sec. 3.3)
+        dec.set_lambda(1e6)
+        r = timed_run(dec, a, h, x, y, args.warmup, args.steps)
+        sweep["miss_free"] = dict(tok_s=round(r["tok_s"], 2), miss_rate=round(r["miss_rate"], 5))
+        log(f"miss-free: {r['tok_s']:.1f} tok/s")
+        dec.set_lambda(HEADLINE_LAMBDA)
+
+    cpu = None
+    if not args.no_cpu:
+        import numpy as np
+
+        n_tok = args.cpu_tokens
+        lw = LazyWeights(cfg, dev)
+        a_cpu = a[:n_tok].cpu().numpy()
+        # materialise the weights the sample needs outside the timed part (input preparation, not oracle work)
+        probe = cpu_oracle_baseline(cfg, lw, a_cpu, n_tok)
+        tok_s = cpu_oracle_baseline(cfg, lw, a_cpu, n_tok)
+        try:
+            from threadpoolctl import threadpool_info
+
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count()
+        cpu = dict(value=round(tok_s, 4), unit="tok/s", cores=int(cores), kind="oracle",
+                   sample=f"first {n_tok} tokens of {cfg.name} (all {cfg.n_layers} layers, lambda={HEADLINE_LAMBDA}), "
+                          f"numpy fp64, weights already in host memory")
+        del probe
+        log(f"cpu oracle: {tok_s:.3f} tok/s on {cores} threads")
+
+    out = {
+        "metric": "batch1_decode_tok_per_s",
+        "value": round(head["tok_s"], 2),
+        "unit": "tok/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(head["ms_per_step"], 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if cfg.weight_fmt == "bf16" else cfg.weight_fmt,
+        "data": "synthetic",
+        "config": {
+            "workload": f"{cfg.name}: L={cfg.n_layers} d={cfg.hidden} N={cfg.n_experts} I={cfg.inter} "
+                        f"shared_I={cfg.shared_inter} top{cfg.top_k} cache={cfg.capacity}/{cfg.n_experts} "
+                        f"T={T} rho={cfg.rho}",
+            "lambda": HEADLINE_LAMBDA, "top_j": cfg.top_j, "seed": cfg.seed,
+        },
+        "per_layer_us": round(1e3 * head["ms_per_step"] / cfg.n_layers, 3),
+        "miss_rate": round(head["miss_rate"], 5),
+        "miss_rate_incl_warmup": round(head["miss_rate_incl_warmup"], 5),
+        "host_link_GB_filled": round(head["host_link_bytes"] / 1e9, 3),
+        "roofline": {
+            "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+            "kernel": "expert_gemv_kernel", "algorithmic_bytes_per_launch": algo_bytes,
+            "avg_launch_us": round(gemv_us, 3), "launches": gemv_launches,
+            "tok_s_while_profiled": round(prof["tok_s"], 2),
+        },
+        "cpu_baseline": cpu,
+        "lambda_sweep": sweep,
+    }
+    dec.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -151,10 +151,11 @@ int moe_cache_set_baseline(moe_cache_t *ctx, int32_t route_mode, int32_t max_ran
 int moe_cache_reset(moe_cache_t *ctx);
 
 /* Workload glue for multi-layer synthetic stacks (not part of the paper's method):
- * h += y + perturb * a (a may be NULL); x = h / sqrt(mean(h^2) + 1e-6) rounded to act_fmt.
- * h: device fp32 [d] in/out; y: device act_fmt [d] or NULL; a: device fp32 [d] or NULL; x: device act_fmt [d]. */
-int moe_residual_rmsnorm(float *h_dev, const void *y_dev, const float *a_dev, float perturb, void *x_dev,
-                         int32_t hidden, int32_t act_fmt, void *stream);
+ * h = (carry ? h : 0) + y + perturb * a (y, a may be NULL); x = h / sqrt(mean(h^2) + 1e-6) rounded to act_fmt.
+ * h: device fp32 [d] in/out; y: device act_fmt [d] or NULL; a: device fp32 [d] or NULL; x: device act_fmt [d].
+ * carry = 0 starts a new token (h is overwritten). */
+int moe_residual_rmsnorm(float *h_dev, const void *y_dev, const float *a_dev, float perturb, int32_t carry,
+                         void *x_dev, int32_t hidden, int32_t act_fmt, void *stream);
 
 /* Average duration in microseconds of the expert-GEMV kernel launches since the last call with
  * reset != 0 (measured with events on compute_stream when profiling is on), and their count. */

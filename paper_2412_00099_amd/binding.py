@@ -118,7 +118,7 @@ lib.moe_cache_set_baseline.argtypes = [_vp, C.c_int32, C.c_int32, C.c_float]
 lib.moe_cache_reset.restype = C.c_int
 lib.moe_cache_reset.argtypes = [_vp]
 lib.moe_residual_rmsnorm.restype = C.c_int
-lib.moe_residual_rmsnorm.argtypes = [_vp, _vp, _vp, C.c_float, _vp, C.c_int32, C.c_int32, _vp]
+lib.moe_residual_rmsnorm.argtypes = [_vp, _vp, _vp, C.c_float, C.c_int32, _vp, C.c_int32, C.c_int32, _vp]
 lib.moe_cache_profile.restype = C.c_int
 lib.moe_cache_profile.argtypes = [_vp, C.c_int32, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
 lib.moe_last_error.restype = C.c_char_p
@@ -199,8 +199,9 @@ def moe_cache_reset(ctx) -> None:
     _check(lib.moe_cache_reset(ctx), "moe_cache_reset")
 
 
-def moe_residual_rmsnorm(h_dev, y_dev, a_dev, perturb: float, x_dev, hidden: int, act_fmt: int, stream) -> None:
-    _check(lib.moe_residual_rmsnorm(h_dev, y_dev, a_dev, perturb, x_dev, hidden, act_fmt, stream),
+def moe_residual_rmsnorm(h_dev, y_dev, a_dev, perturb: float, carry: int, x_dev, hidden: int, act_fmt: int,
+                         stream) -> None:
+    _check(lib.moe_residual_rmsnorm(h_dev, y_dev, a_dev, perturb, carry, x_dev, hidden, act_fmt, stream),
            "moe_residual_rmsnorm")
 
 

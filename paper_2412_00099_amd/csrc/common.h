@@ -57,8 +57,8 @@ hipError_t launch_partial_reduce(const float *partial, int n_partial, void *y, i
                                  hipStream_t s);
 hipError_t launch_pack(int fmt, int hidden, int inter, const void *gate, const void *up, const void *down,
                        const void *gs, const void *us, const void *ds, void *blob, hipStream_t s);
-hipError_t launch_residual_rmsnorm(float *h, const void *y, const float *a, float perturb, void *x, int hidden,
-                                   int act_fmt, hipStream_t s);
+hipError_t launch_residual_rmsnorm(float *h, const void *y, const float *a, float perturb, int carry, void *x,
+                                   int hidden, int act_fmt, hipStream_t s);
 hipError_t launch_state_init(LayerState *state, int n_layers, const int32_t *initial_dev, int n_initial,
                              hipStream_t s);
 bool gemv_shape_supported(int weight_fmt, int hidden);

@@ -417,11 +417,11 @@ int moe_cache_reset(moe_cache_t *c) {
   return do_reset(c);
 }
 
-int moe_residual_rmsnorm(float *h_dev, const void *y_dev, const float *a_dev, float perturb, void *x_dev,
-                         int32_t hidden, int32_t act_fmt, void *stream) {
+int moe_residual_rmsnorm(float *h_dev, const void *y_dev, const float *a_dev, float perturb, int32_t carry,
+                         void *x_dev, int32_t hidden, int32_t act_fmt, void *stream) {
   if (!h_dev || !x_dev) return fail(MOE_EINVAL, "h_dev or x_dev is NULL");
   if (hidden <= 0 || !valid_afmt(act_fmt)) return fail(MOE_EINVAL, "bad hidden or act_fmt");
-  HIP_TRY(launch_residual_rmsnorm(h_dev, y_dev, a_dev, perturb, x_dev, hidden, act_fmt,
+  HIP_TRY(launch_residual_rmsnorm(h_dev, y_dev, a_dev, perturb, carry, x_dev, hidden, act_fmt,
                                   static_cast<hipStream_t>(stream)));
   return MOE_OK;
 }

@@ -49,14 +49,15 @@ __global__ void pack_plain_kernel(const T *gate, const T *up, const T *down, T *
   }
 }
 
-// h += y + perturb*a ; x = h / sqrt(mean(h^2) + 1e-6) in act_fmt.  One workgroup.
+// h = (carry ? h : 0) + y + perturb*a ; x = h / sqrt(mean(h^2) + 1e-6) in act_fmt.  One workgroup.
 __global__ __launch_bounds__(1024) void residual_rmsnorm_kernel(float *h, const void *y, const float *a,
-                                                                float perturb, void *x, int d, int act_fmt) {
+                                                                float perturb, int carry, void *x, int d,
+                                                                int act_fmt) {
   __shared__ float part[16];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   float ss = 0.f;
   for (int j = tid; j < d; j += blockDim.x) {
-    float v = h[j];
+    float v = carry ? h[j] : 0.f;
     if (y) v += (act_fmt == MOE_A_BF16) ? __uint_as_float((uint32_t) static_cast<const uint16_t *>(y)[j] << 16)
                                         : static_cast<const float *>(y)[j];
     if (a) v = __builtin_fmaf(perturb, a[j], v);
@@ -102,9 +103,10 @@ hipError_t launch_pack(int fmt, int hidden, int inter, const void *gate, const v
   return hipGetLastError();
 }
 
-hipError_t launch_residual_rmsnorm(float *h, const void *y, const float *a, float perturb, void *x, int hidden,
-                                   int act_fmt, hipStream_t s) {
-  hipLaunchKernelGGL(residual_rmsnorm_kernel, dim3(1), dim3(1024), 0, s, h, y, a, perturb, x, hidden, act_fmt);
+hipError_t launch_residual_rmsnorm(float *h, const void *y, const float *a, float perturb, int carry, void *x,
+                                   int hidden, int act_fmt, hipStream_t s) {
+  hipLaunchKernelGGL(residual_rmsnorm_kernel, dim3(1), dim3(1024), 0, s, h, y, a, perturb, carry, x, hidden,
+                     act_fmt);
   return hipGetLastError();
 }
 

@@ -150,8 +150,8 @@ class MoEDecoder:
     def reset(self):
         B.moe_cache_reset(self.ctx)
 
-    def residual_rmsnorm(self, h, y, a, perturb, x):
-        B.moe_residual_rmsnorm(_ptr(h), _ptr(y), _ptr(a), perturb, _ptr(x), self.store.d, self.store.afmt,
+    def residual_rmsnorm(self, h, y, a, perturb, x, carry=True):
+        B.moe_residual_rmsnorm(_ptr(h), _ptr(y), _ptr(a), perturb, int(carry), _ptr(x), self.store.d, self.store.afmt,
                                C.c_void_p(self.compute_stream.cuda_stream))
 
     def profile(self, enable, reset=True):

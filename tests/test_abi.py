@@ -104,5 +104,5 @@ def test_null_context_calls_fail_cleanly(B):
     assert B.lib.moe_cache_set_lambda(None, 0.0) == B.MOE_EINVAL
     assert B.lib.moe_cache_reset(None) == B.MOE_EINVAL
     assert B.lib.moe_pack_expert(B.MOE_W_BF16, 2048, 64, None, None, None, None, None, None, None, None) == B.MOE_EINVAL
-    assert B.lib.moe_residual_rmsnorm(None, None, None, 0.5, None, 256, 0, None) == B.MOE_EINVAL
+    assert B.lib.moe_residual_rmsnorm(None, None, None, 0.5, 1, None, 256, 0, None) == B.MOE_EINVAL
     B.lib.moe_cache_destroy(None)
