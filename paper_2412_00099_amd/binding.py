@@ -4,7 +4,8 @@ from __future__ import annotations
 import ctypes as C
 import os
 
-LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmoe_cache.so")
+# MOE_CACHE_LIB selects another build of the same library (kernel tuning experiments)
+LIB_PATH = os.environ.get("MOE_CACHE_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmoe_cache.so")
 if not os.path.exists(LIB_PATH):
     raise ImportError(
         f"{LIB_PATH} is missing: build it with `python -m paper_2412_00099_amd.build` "

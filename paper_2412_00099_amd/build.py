@@ -28,6 +28,7 @@ COMMON = [
 SOURCES = {
     "router.hip": ["-ffp-contract=off"],
     "expert_gemv.hip": [],
+    "expert_gemv_quant.hip": [],
     "pack.hip": [],
     "moe_cache.hip": [],
 }

@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "moe_cache.h"
@@ -32,7 +33,8 @@ struct RouteParams {
 struct GemvParams {
   const uint8_t *slot_pool;      // this layer's slots
   const uint8_t *shared_blob;    // or nullptr
-  const moe_route_out_t *route;  // device record of the layer's last routing step
+  int64_t seg_off[MOE_MAX_TOPK];  // byte offset of each selected expert's slot in the pool
+  float seg_w[MOE_MAX_TOPK];      // its routing weight (known on the host after the route step)
   const void *x;                 // [d] act_fmt
   float *partial;                // [grid][d] fp32
   int32_t hidden, inter, shared_inter, top_k, act_fmt;
@@ -52,7 +54,16 @@ BlobLayout blob_layout(int fmt, int hidden, int inter);
 hipError_t launch_route(const RouteParams &p, const void *gate_w, const void *x, const float *logits,
                         LayerState *state, moe_route_out_t *out_dev, moe_route_out_t *out_host_mapped,
                         hipStream_t s);
-hipError_t launch_expert_gemv(const GemvParams &p, int weight_fmt, int grid, hipStream_t s);
+// launch shape of the expert GEMV
+struct GemvPlan {
+  int grid;   // workgroups (= fp32 partial rows written)
+  int waves;  // wavefronts per workgroup: 4 or 8
+  int depth;  // records in flight per wavefront: 2 or 3
+  bool dot2;  // packed bf16 dot products (bf16 weights and activations)
+};
+GemvPlan gemv_plan(int n_cus, int total_records, int weight_fmt, int act_fmt);
+hipError_t launch_expert_gemv(const GemvParams &p, int weight_fmt, const GemvPlan &plan, hipStream_t s,
+                              hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
 hipError_t launch_partial_reduce(const float *partial, int n_partial, void *y, int hidden, int act_fmt,
                                  hipStream_t s);
 hipError_t launch_pack(int fmt, int hidden, int inter, const void *gate, const void *up, const void *down,
@@ -62,6 +73,9 @@ hipError_t launch_residual_rmsnorm(float *h, const void *y, const float *a, floa
 hipError_t launch_state_init(LayerState *state, int n_layers, const int32_t *initial_dev, int n_initial,
                              hipStream_t s);
 bool gemv_shape_supported(int weight_fmt, int hidden);
+bool gemv_inter_supported(int weight_fmt, int inter);
+hipError_t launch_expert_gemv_quant(const GemvParams &p, int weight_fmt, const GemvPlan &plan, hipStream_t s,
+                                    hipEvent_t start, hipEvent_t stop);
 
 // ---- device helpers -------------------------------------------------------------------------
 #if defined(__HIPCC__)

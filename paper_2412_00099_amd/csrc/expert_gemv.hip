@@ -9,99 +9,104 @@
 // into its private d/64 outputs: no barrier between the up and the down projection.  Records of all
 // selected experts and of the shared expert form one index space that is split evenly over the workgroups;
 // inside a workgroup records are interleaved over the wavefronts, so a workgroup streams one contiguous span.
-// The wavefronts' private outputs are tree-reduced through LDS, each workgroup writes one fp32 partial row,
-// and a second small kernel adds the partial rows in a fixed order (deterministic result).
+// Each wavefront keeps DEPTH records' loads in flight in a register ring.  The wavefronts' private outputs
+// are tree-reduced through LDS, each workgroup writes one fp32 partial row, and a second small kernel adds
+// the partial rows in a fixed order (deterministic result).
+#include <cstdlib>
+
 #include "common.h"
+#include "gemv_common.h"
 
 namespace moe {
 namespace {
 
-constexpr int kGemvWaves = 8;
-constexpr int kRedCols = 2048;  // columns reduced per LDS pass
+// ---- per-format arithmetic on one 16-byte chunk --------------------------------------------------
+// X holds the lane's activations for one chunk: XW registers.  dot() accumulates the chunk's partial
+// dot product into two chains; axpy() adds h * chunk to the VEC outputs.
+template <int FMT, bool DOT2>
+struct Chunk;
 
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-
-template <int FMT>
-struct WFmt;
 template <>
-struct WFmt<MOE_W_FP32> {
-  static constexpr int VEC = 4;
-  static __device__ __forceinline__ void decode(const u32x4 &v, float (&f)[4]) {
-    f[0] = __uint_as_float(v.x);
-    f[1] = __uint_as_float(v.y);
-    f[2] = __uint_as_float(v.z);
-    f[3] = __uint_as_float(v.w);
-  }
-};
-template <>
-struct WFmt<MOE_W_BF16> {
-  static constexpr int VEC = 8;
-  static __device__ __forceinline__ void decode(const u32x4 &v, float (&f)[8]) {
-    f[0] = bf16_lo(v.x);
-    f[1] = bf16_hi(v.x);
-    f[2] = bf16_lo(v.y);
-    f[3] = bf16_hi(v.y);
-    f[4] = bf16_lo(v.z);
-    f[5] = bf16_hi(v.z);
-    f[6] = bf16_lo(v.w);
-    f[7] = bf16_hi(v.w);
-  }
-};
-
-
-// weights are read once: mark the loads non-temporal so they do not displace x and the partial rows in L2
-__device__ __forceinline__ u32x4 stream_load(const u32x4 *p) { return __builtin_nontemporal_load(p); }
-
-// VEC consecutive activations starting at element `col`, widened to fp32
-template <int VEC>
-__device__ __forceinline__ void load_x(const void *x, int act_fmt, int col, float *out) {
-  if (act_fmt == MOE_A_BF16) {
-    const uint16_t *xb = static_cast<const uint16_t *>(x) + col;
-    if constexpr (VEC == 4) {
-      const u32x2 v = *reinterpret_cast<const u32x2 *>(xb);
-      out[0] = bf16_lo(v.x); out[1] = bf16_hi(v.x); out[2] = bf16_lo(v.y); out[3] = bf16_hi(v.y);
+struct Chunk<MOE_W_FP32, false> {
+  static constexpr int VEC = 4, XW = 4;
+  static __device__ __forceinline__ void load_x(const void *x, int act_fmt, int col, float *xr) {
+    if (act_fmt == MOE_A_BF16) {
+      const u32x2 v = *reinterpret_cast<const u32x2 *>(static_cast<const uint16_t *>(x) + col);
+      xr[0] = bf16_lo(v.x); xr[1] = bf16_hi(v.x); xr[2] = bf16_lo(v.y); xr[3] = bf16_hi(v.y);
     } else {
-#pragma unroll
-      for (int i = 0; i < VEC / 8; ++i) {
-        const u32x4 v = reinterpret_cast<const u32x4 *>(xb)[i];
-        out[i * 8 + 0] = bf16_lo(v.x); out[i * 8 + 1] = bf16_hi(v.x);
-        out[i * 8 + 2] = bf16_lo(v.y); out[i * 8 + 3] = bf16_hi(v.y);
-        out[i * 8 + 4] = bf16_lo(v.z); out[i * 8 + 5] = bf16_hi(v.z);
-        out[i * 8 + 6] = bf16_lo(v.w); out[i * 8 + 7] = bf16_hi(v.w);
-      }
-    }
-  } else {
-    const float4 *xf = reinterpret_cast<const float4 *>(static_cast<const float *>(x) + col);
-#pragma unroll
-    for (int i = 0; i < VEC / 4; ++i) {
-      const float4 v = xf[i];
-      out[i * 4 + 0] = v.x; out[i * 4 + 1] = v.y; out[i * 4 + 2] = v.z; out[i * 4 + 3] = v.w;
+      const float4 v = *reinterpret_cast<const float4 *>(static_cast<const float *>(x) + col);
+      xr[0] = v.x; xr[1] = v.y; xr[2] = v.z; xr[3] = v.w;
     }
   }
-}
+  static __device__ __forceinline__ void dot(const u32x4 &w, const float *xr, float &a0, float &a1) {
+    a0 = __builtin_fmaf(__uint_as_float(w.x), xr[0], a0);
+    a1 = __builtin_fmaf(__uint_as_float(w.y), xr[1], a1);
+    a0 = __builtin_fmaf(__uint_as_float(w.z), xr[2], a0);
+    a1 = __builtin_fmaf(__uint_as_float(w.w), xr[3], a1);
+  }
+  static __device__ __forceinline__ void axpy(float h, const u32x4 &w, float *y) {
+    y[0] = __builtin_fmaf(h, __uint_as_float(w.x), y[0]);
+    y[1] = __builtin_fmaf(h, __uint_as_float(w.y), y[1]);
+    y[2] = __builtin_fmaf(h, __uint_as_float(w.z), y[2]);
+    y[3] = __builtin_fmaf(h, __uint_as_float(w.w), y[3]);
+  }
+};
 
-// sums a and b over the wavefront (both results in every lane), the two chains interleaved
-__device__ __forceinline__ void wave_sum2(float &a, float &b) {
-  a += dpp_f32<0x128>(a);
-  b += dpp_f32<0x128>(b);
-  a += dpp_f32<0x124>(a);
-  b += dpp_f32<0x124>(b);
-  a += dpp_f32<0x122>(a);
-  b += dpp_f32<0x122>(b);
-  a += dpp_f32<0x121>(a);
-  b += dpp_f32<0x121>(b);
-  float a0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a), 0));
-  float a1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a), 16));
-  float a2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a), 32));
-  float a3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a), 48));
-  float b0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(b), 0));
-  float b1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(b), 16));
-  float b2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(b), 32));
-  float b3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(b), 48));
-  a = (a0 + a1) + (a2 + a3);
-  b = (b0 + b1) + (b2 + b3);
-}
+template <>
+struct Chunk<MOE_W_BF16, false> {
+  static constexpr int VEC = 8, XW = 8;
+  static __device__ __forceinline__ void load_x(const void *x, int act_fmt, int col, float *xr) {
+    if (act_fmt == MOE_A_BF16) {
+      const u32x4 v = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(x) + col);
+      xr[0] = bf16_lo(v.x); xr[1] = bf16_hi(v.x); xr[2] = bf16_lo(v.y); xr[3] = bf16_hi(v.y);
+      xr[4] = bf16_lo(v.z); xr[5] = bf16_hi(v.z); xr[6] = bf16_lo(v.w); xr[7] = bf16_hi(v.w);
+    } else {
+      const float4 *p = reinterpret_cast<const float4 *>(static_cast<const float *>(x) + col);
+      const float4 a = p[0], b = p[1];
+      xr[0] = a.x; xr[1] = a.y; xr[2] = a.z; xr[3] = a.w; xr[4] = b.x; xr[5] = b.y; xr[6] = b.z; xr[7] = b.w;
+    }
+  }
+  static __device__ __forceinline__ void dot(const u32x4 &w, const float *xr, float &a0, float &a1) {
+    a0 = __builtin_fmaf(bf16_lo(w.x), xr[0], a0);
+    a1 = __builtin_fmaf(bf16_hi(w.x), xr[1], a1);
+    a0 = __builtin_fmaf(bf16_lo(w.y), xr[2], a0);
+    a1 = __builtin_fmaf(bf16_hi(w.y), xr[3], a1);
+    a0 = __builtin_fmaf(bf16_lo(w.z), xr[4], a0);
+    a1 = __builtin_fmaf(bf16_hi(w.z), xr[5], a1);
+    a0 = __builtin_fmaf(bf16_lo(w.w), xr[6], a0);
+    a1 = __builtin_fmaf(bf16_hi(w.w), xr[7], a1);
+  }
+  static __device__ __forceinline__ void axpy(float h, const u32x4 &w, float *y) {
+    y[0] = __builtin_fmaf(h, bf16_lo(w.x), y[0]);
+    y[1] = __builtin_fmaf(h, bf16_hi(w.x), y[1]);
+    y[2] = __builtin_fmaf(h, bf16_lo(w.y), y[2]);
+    y[3] = __builtin_fmaf(h, bf16_hi(w.y), y[3]);
+    y[4] = __builtin_fmaf(h, bf16_lo(w.z), y[4]);
+    y[5] = __builtin_fmaf(h, bf16_hi(w.z), y[5]);
+    y[6] = __builtin_fmaf(h, bf16_lo(w.w), y[6]);
+    y[7] = __builtin_fmaf(h, bf16_hi(w.w), y[7]);
+  }
+};
+
+// bf16 weights with bf16 activations: the activations stay packed (two per register) and the dot products
+// use the two-way bf16 dot instruction with fp32 accumulation (products of bf16 values are exact in fp32).
+template <>
+struct Chunk<MOE_W_BF16, true> {
+  static constexpr int VEC = 8, XW = 4;
+  static __device__ __forceinline__ void load_x(const void *x, int, int col, float *xr) {
+    const u32x4 v = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(x) + col);
+    xr[0] = __uint_as_float(v.x); xr[1] = __uint_as_float(v.y); xr[2] = __uint_as_float(v.z); xr[3] = __uint_as_float(v.w);
+  }
+  static __device__ __forceinline__ void dot(const u32x4 &w, const float *xr, float &a0, float &a1) {
+    a0 = dot2_bf16(w.x, __float_as_uint(xr[0]), a0);
+    a1 = dot2_bf16(w.y, __float_as_uint(xr[1]), a1);
+    a0 = dot2_bf16(w.z, __float_as_uint(xr[2]), a0);
+    a1 = dot2_bf16(w.w, __float_as_uint(xr[3]), a1);
+  }
+  static __device__ __forceinline__ void axpy(float h, const u32x4 &w, float *y) {
+    Chunk<MOE_W_BF16, false>::axpy(h, w, y);
+  }
+};
 
 template <int LPR>
 struct RecRegs {
@@ -109,61 +114,61 @@ struct RecRegs {
   float wt;
 };
 
-// FMT: weight format, LPR: 16-byte loads per row per lane (d = LPR * 64 * VEC)
-template <int FMT, int LPR>
-__global__ __launch_bounds__(kGemvWaves * kWave) void expert_gemv_kernel(GemvParams p) {
-  using F = WFmt<FMT>;
-  constexpr int VEC = F::VEC;
+// FMT: weight format; LPR: 16-byte loads per row per lane (d = LPR*64*VEC); NW: wavefronts per workgroup;
+// DEPTH: records in flight per wavefront; DOT2: packed bf16 dot products.
+template <int FMT, int LPR, int NW, int DEPTH, bool DOT2>
+__global__ __launch_bounds__(NW *kWave) void expert_gemv_kernel(GemvParams p) {
+  using F = Chunk<FMT, DOT2>;
+  constexpr int VEC = F::VEC, XW = F::XW;
   constexpr int CPL = LPR * VEC;  // columns per lane
-  constexpr int NW = kGemvWaves;
-  __shared__ float red[(NW / 2) * kRedCols];
-  __shared__ int64_t seg_off[MOE_MAX_TOPK];
-  __shared__ float seg_w[MOE_MAX_TOPK];
+  __shared__ float red[kRedFloats];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform: keeps record addressing scalar
   const int d = p.hidden, I = p.inter, K = p.top_k;
-  const int64_t row_bytes = (int64_t)d * 16 / VEC;
-  const int64_t rec_bytes = 3 * row_bytes;
+  const int64_t row16 = (int64_t)d / VEC;  // 16-byte chunks per row
+  const int64_t rec_bytes = 3 * row16 * 16;
   const int routed = K * I;
   const int total = routed + p.shared_inter;
   const int r0 = (int)((int64_t)blockIdx.x * total / gridDim.x);
   const int r1 = (int)((int64_t)(blockIdx.x + 1) * total / gridDim.x);
 
-  if (tid < K) {
-    seg_off[tid] = (int64_t)p.route->sel_slot[tid] * p.slot_bytes;
-    seg_w[tid] = p.route->sel_weight[tid];
-  }
-  __syncthreads();
+  // this wavefront's records: first + j*NW, j = 0 .. n-1, walked as (segment, row) without divisions:
+  // segments 0..K-1 are the selected slots (I rows each), segment K is the shared expert
+  const int first = r0 + wave;
+  const int n = first < r1 ? (r1 - first + NW - 1) / NW : 0;
+  int seg = first < routed ? first / I : K;
+  int row = first < routed ? first - seg * I : first - routed;
 
-  auto issue = [&](int r, RecRegs<LPR> &R) {
-    const uint8_t *rec;
-    if (r < routed) {
-      const int k = r / I, i = r - k * I;
-      rec = p.slot_pool + seg_off[k] + (int64_t)i * rec_bytes;
-      R.wt = seg_w[k];
-    } else {
-      rec = p.shared_blob + (int64_t)(r - routed) * rec_bytes;
-      R.wt = 1.f;
-    }
-    const u32x4 *q = reinterpret_cast<const u32x4 *>(rec) + lane;
+  auto issue = [&](RecRegs<LPR> &R) {
+    const uint8_t *base = seg < K ? p.slot_pool + p.seg_off[seg] : p.shared_blob;
+    R.wt = seg < K ? p.seg_w[seg] : 1.f;
+    const u32x4 *q = reinterpret_cast<const u32x4 *>(base + (int64_t)row * rec_bytes) + lane;
 #pragma unroll
     for (int c = 0; c < LPR; ++c) R.g[c] = stream_load(q + c * kWave);
-    q += row_bytes / 16;
+    q += row16;
 #pragma unroll
     for (int c = 0; c < LPR; ++c) R.u[c] = stream_load(q + c * kWave);
-    q += row_bytes / 16;
+    q += row16;
 #pragma unroll
     for (int c = 0; c < LPR; ++c) R.dn[c] = stream_load(q + c * kWave);
+    // advance to this wavefront's next record
+    row += NW;
+    while (seg < K && row >= I) {
+      row -= I;
+      ++seg;
+    }
   };
 
-  int r = r0 + wave;
-  RecRegs<LPR> A, B;
-  if (r < r1) issue(r, A);  // weights first: they do not depend on x
-
-  // activations: lane keeps the x entries of its own columns in registers
-  float xr[CPL];
+  RecRegs<LPR> ring[DEPTH];
 #pragma unroll
-  for (int c = 0; c < LPR; ++c) load_x<VEC>(p.x, p.act_fmt, (c * kWave + lane) * VEC, &xr[c * VEC]);
+  for (int j = 0; j < DEPTH; ++j)
+    if (j < n) issue(ring[j]);  // weights first: they do not depend on x
+
+  // activations: the lane keeps the x entries of its own columns in registers
+  float xr[LPR * XW];
+#pragma unroll
+  for (int c = 0; c < LPR; ++c) F::load_x(p.x, p.act_fmt, (c * kWave + lane) * VEC, &xr[c * XW]);
 
   float y[CPL];
 #pragma unroll
@@ -173,87 +178,27 @@ __global__ __launch_bounds__(kGemvWaves * kWave) void expert_gemv_kernel(GemvPar
     float g0 = 0.f, g1 = 0.f, u0 = 0.f, u1 = 0.f;
 #pragma unroll
     for (int c = 0; c < LPR; ++c) {
-      float gw[VEC], uw[VEC];
-      F::decode(R.g[c], gw);
-      F::decode(R.u[c], uw);
-#pragma unroll
-      for (int v = 0; v < VEC; v += 2) {
-        g0 = __builtin_fmaf(gw[v], xr[c * VEC + v], g0);
-        g1 = __builtin_fmaf(gw[v + 1], xr[c * VEC + v + 1], g1);
-        u0 = __builtin_fmaf(uw[v], xr[c * VEC + v], u0);
-        u1 = __builtin_fmaf(uw[v + 1], xr[c * VEC + v + 1], u1);
-      }
+      F::dot(R.g[c], &xr[c * XW], g0, g1);
+      F::dot(R.u[c], &xr[c * XW], u0, u1);
     }
     float g = g0 + g1, u = u0 + u1;
     wave_sum2(g, u);
     const float h = g / (1.f + __expf(-g)) * u * R.wt;
 #pragma unroll
-    for (int c = 0; c < LPR; ++c) {
-      float dw[VEC];
-      F::decode(R.dn[c], dw);
-#pragma unroll
-      for (int v = 0; v < VEC; ++v) y[c * VEC + v] = __builtin_fmaf(h, dw[v], y[c * VEC + v]);
-    }
+    for (int c = 0; c < LPR; ++c) F::axpy(h, R.dn[c], &y[c * VEC]);
   };
 
-  for (; r < r1; r += 2 * NW) {
-    const bool has_b = r + NW < r1;
-    if (has_b) issue(r + NW, B);
-    consume(A);
-    if (has_b) {
-      if (r + 2 * NW < r1) issue(r + 2 * NW, A);
-      consume(B);
+  for (int k = 0; k < n; k += DEPTH) {
+#pragma unroll
+    for (int j = 0; j < DEPTH; ++j) {
+      if (k + j < n) {
+        consume(ring[j]);
+        if (k + j + DEPTH < n) issue(ring[j]);
+      }
     }
   }
 
-  // ---- tree reduction of the wavefronts' outputs through LDS, kRedCols columns per pass ----------
-  constexpr int CB = kRedCols / (kWave * VEC);            // load indices c per pass
-  constexpr int PASSES = (LPR + CB - 1) / CB;
-  constexpr int CPP = (LPR < CB ? LPR : CB);              // c per pass actually present
-  float4 *red4 = reinterpret_cast<float4 *>(red);
-  float *out = p.partial + (int64_t)blockIdx.x * d;
-#pragma unroll
-  for (int ps = 0; ps < PASSES; ++ps) {
-#pragma unroll
-    for (int s = NW / 2; s >= 1; s >>= 1) {
-      if (wave >= s && wave < 2 * s) {
-        float4 *dst = red4 + (int64_t)(wave - s) * (kRedCols / 4);
-#pragma unroll
-        for (int cc = 0; cc < CPP; ++cc)
-#pragma unroll
-          for (int v4 = 0; v4 < VEC / 4; ++v4) {
-            const int j = (ps * CB + cc) * VEC + v4 * 4;
-            dst[(cc * (VEC / 4) + v4) * kWave + lane] = make_float4(y[j], y[j + 1], y[j + 2], y[j + 3]);
-          }
-      }
-      __syncthreads();
-      if (wave < s) {
-        const float4 *src = red4 + (int64_t)wave * (kRedCols / 4);
-#pragma unroll
-        for (int cc = 0; cc < CPP; ++cc)
-#pragma unroll
-          for (int v4 = 0; v4 < VEC / 4; ++v4) {
-            const int j = (ps * CB + cc) * VEC + v4 * 4;
-            const float4 t = src[(cc * (VEC / 4) + v4) * kWave + lane];
-            y[j] += t.x;
-            y[j + 1] += t.y;
-            y[j + 2] += t.z;
-            y[j + 3] += t.w;
-          }
-      }
-      __syncthreads();
-    }
-  }
-  if (wave == 0) {
-#pragma unroll
-    for (int c = 0; c < LPR; ++c)
-#pragma unroll
-      for (int v4 = 0; v4 < VEC / 4; ++v4) {
-        const int j = c * VEC + v4 * 4;
-        float4 *o = reinterpret_cast<float4 *>(out + (c * kWave + lane) * VEC + v4 * 4);
-        *o = make_float4(y[j], y[j + 1], y[j + 2], y[j + 3]);
-      }
-  }
+  reduce_and_store<NW, VEC, LPR>(y, red, p.partial + (int64_t)blockIdx.x * d, tid, lane, wave);
 }
 
 // y[j] = sum over partial rows in index order, rounded to the activation type.
@@ -298,40 +243,92 @@ __global__ __launch_bounds__(256) void partial_reduce_kernel(const float *partia
   }
 }
 
-template <int FMT>
-hipError_t launch_fmt(const GemvParams &p, int grid, hipStream_t s) {
-  constexpr int VEC = WFmt<FMT>::VEC;
-  const int lpr = p.hidden / (kWave * VEC);
-  dim3 g(grid), b(kGemvWaves * kWave);
-  switch (lpr) {
-    case 1: hipLaunchKernelGGL((expert_gemv_kernel<FMT, 1>), g, b, 0, s, p); break;
-    case 2: hipLaunchKernelGGL((expert_gemv_kernel<FMT, 2>), g, b, 0, s, p); break;
-    case 4: hipLaunchKernelGGL((expert_gemv_kernel<FMT, 4>), g, b, 0, s, p); break;
-    case 8: hipLaunchKernelGGL((expert_gemv_kernel<FMT, 8>), g, b, 0, s, p); break;
+template <int FMT, int LPR, int NW, int DEPTH, bool DOT2>
+void launch_one(const GemvParams &p, int grid, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
+  hipExtLaunchKernelGGL((expert_gemv_kernel<FMT, LPR, NW, DEPTH, DOT2>), dim3(grid), dim3(NW * kWave), 0, s, e0, e1,
+                        0, p);
+}
+
+template <int FMT, int LPR, bool DOT2>
+hipError_t launch_plan(const GemvParams &p, const GemvPlan &plan, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
+  const int key = plan.waves * 10 + plan.depth;
+  switch (key) {
+    case 42: launch_one<FMT, LPR, 4, 2, DOT2>(p, plan.grid, s, e0, e1); break;
+    case 43: launch_one<FMT, LPR, 4, 3, DOT2>(p, plan.grid, s, e0, e1); break;
+    case 82: launch_one<FMT, LPR, 8, 2, DOT2>(p, plan.grid, s, e0, e1); break;
+    case 161: launch_one<FMT, LPR, 16, 1, DOT2>(p, plan.grid, s, e0, e1); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
 }
 
+// start/stop, when given, receive the kernel's own begin and end timestamps
+template <int FMT, bool DOT2>
+hipError_t launch_fmt(const GemvParams &p, const GemvPlan &plan, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
+  constexpr int VEC = Chunk<FMT, DOT2>::VEC;
+  const int lpr = p.hidden / (kWave * VEC);
+  switch (lpr) {
+    case 1: return launch_plan<FMT, 1, DOT2>(p, plan, s, e0, e1);
+    case 2: return launch_plan<FMT, 2, DOT2>(p, plan, s, e0, e1);
+    case 4: return launch_plan<FMT, 4, DOT2>(p, plan, s, e0, e1);
+    case 8: return launch_plan<FMT, 8, DOT2>(p, plan, s, e0, e1);
+    default: return hipErrorInvalidValue;
+  }
+}
+
 }  // namespace
 
 bool gemv_shape_supported(int weight_fmt, int hidden) {
-  int vec;
+  int vec, max_lpr;
   switch (weight_fmt) {
-    case MOE_W_FP32: vec = 4; break;
-    case MOE_W_BF16: vec = 8; break;
+    case MOE_W_FP32: vec = 4; max_lpr = 8; break;
+    case MOE_W_BF16: vec = 8; max_lpr = 8; break;
+    case MOE_W_INT8_PC: vec = 16; max_lpr = 4; break;
+    case MOE_W_INT4_G128: vec = 32; max_lpr = 2; break;
     default: return false;
   }
   if (hidden <= 0 || hidden % (kWave * vec) != 0) return false;
   const int lpr = hidden / (kWave * vec);
-  return lpr == 1 || lpr == 2 || lpr == 4 || lpr == 8;
+  return (lpr == 1 || lpr == 2 || lpr == 4 || lpr == 8) && lpr <= max_lpr;
 }
 
-hipError_t launch_expert_gemv(const GemvParams &p, int weight_fmt, int grid, hipStream_t s) {
+// int8 keeps 16-byte alignment of its scale tail with rows % 8 == 0; int4 groups 128 rows of W_down
+bool gemv_inter_supported(int weight_fmt, int inter) {
+  if (inter <= 0) return false;
+  if (weight_fmt == MOE_W_INT8_PC) return inter % 8 == 0;
+  if (weight_fmt == MOE_W_INT4_G128) return inter % 128 == 0;
+  return true;
+}
+
+// Launch shape: one workgroup of 8 wavefronts per compute unit, two records in flight per wavefront
+// (measured best on MI355X among 4/8/16 wavefronts and depths 1-3; the environment variables below
+// exist for such sweeps).
+GemvPlan gemv_plan(int n_cus, int total_records, int weight_fmt, int act_fmt) {
+  GemvPlan pl{};
+  pl.grid = n_cus < total_records ? n_cus : total_records;
+  if (pl.grid < 1) pl.grid = 1;
+  pl.waves = 8;
+  pl.depth = 2;
+  pl.dot2 = weight_fmt == MOE_W_BF16 && act_fmt == MOE_A_BF16;
+  if (const char *s = getenv("MOE_GEMV_GRID")) if (atoi(s) > 0) pl.grid = atoi(s) < total_records ? atoi(s) : total_records;
+  if (const char *s = getenv("MOE_GEMV_WAVES")) if (atoi(s) == 4 || atoi(s) == 8 || atoi(s) == 16) pl.waves = atoi(s);
+  if (const char *s = getenv("MOE_GEMV_DEPTH")) if (atoi(s) == 2 || atoi(s) == 3) pl.depth = atoi(s);
+  if (const char *s = getenv("MOE_GEMV_DOT2")) pl.dot2 = pl.dot2 && atoi(s) != 0;
+  if (pl.waves == 8) pl.depth = 2;
+  if (pl.waves == 16) pl.depth = 1;
+  return pl;
+}
+
+hipError_t launch_expert_gemv(const GemvParams &p, int weight_fmt, const GemvPlan &plan, hipStream_t s,
+                              hipEvent_t e0, hipEvent_t e1) {
   if (!gemv_shape_supported(weight_fmt, p.hidden)) return hipErrorInvalidValue;
   switch (weight_fmt) {
-    case MOE_W_FP32: return launch_fmt<MOE_W_FP32>(p, grid, s);
-    case MOE_W_BF16: return launch_fmt<MOE_W_BF16>(p, grid, s);
+    case MOE_W_FP32: return launch_fmt<MOE_W_FP32, false>(p, plan, s, e0, e1);
+    case MOE_W_BF16:
+      return plan.dot2 ? launch_fmt<MOE_W_BF16, true>(p, plan, s, e0, e1)
+                       : launch_fmt<MOE_W_BF16, false>(p, plan, s, e0, e1);
+    case MOE_W_INT8_PC:
+    case MOE_W_INT4_G128: return launch_expert_gemv_quant(p, weight_fmt, plan, s, e0, e1);
     default: return hipErrorInvalidValue;
   }
 }

@@ -1,0 +1,399 @@
+// Weight-only quantised variants of the expert SwiGLU GEMV (paper Eq. 1; Sec. 4.5 deploys 4- and 8-bit
+// experts).  Same decomposition as the bf16 kernel - one wavefront per record [gate row | up row | column of
+// W_down], DPP reduction of the two dot products, private output accumulators, LDS sum, one fp32 partial
+// row per workgroup - with the dequantisation folded into the arithmetic:
+//
+//  int8 (per output channel fp16 scales).  Bytes are stored offset-binary (u = q + 128).  Two bytes become a
+//  packed fp16 pair (1024 + u) with one byte permute; the dot products use the two-way fp16 dot instruction
+//  with fp32 accumulation against fp16-packed activations, and the constant (1024 + 128) * sum(x) is removed
+//  once per row.  The row scale multiplies the reduced dot product.  For the down projection each byte is
+//  converted to fp32 and accumulated unscaled; the per-column scale is applied when the wavefront leaves
+//  an expert (scales differ per expert) and at the end.
+//
+//  int4 (group-128 symmetric, fp16 scales, nibble = q + 8).  A lane's 32 columns of a row lie in one
+//  group.  Nibble pairs (t, t+4) of a dword become packed bf16 (128 + n) with one and-or (plus a shift);
+//  dot products use the two-way bf16 dot instruction against bf16-packed activations arranged in the same
+//  pair order, the constant (128 + 8) * sum(x) is removed per lane, then the lane's group scale is applied
+//  before the wavefront reduction.  For the down projection the pairs are formed as fp16 (1024 + n) and
+//  consumed by mixed-precision FMAs; accumulators are unscaled within a group of 128 records and flushed with
+//  the group's per-column scales (and the constant (1024 + 8) * sum(h) removed) when the group or expert
+//  changes and at the end.
+#include <cstdlib>
+
+#include "common.h"
+#include "gemv_common.h"
+
+namespace moe {
+namespace {
+
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float dot2_f16(uint32_t a, uint32_t b, float acc) {
+  return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, a), __builtin_bit_cast(f16x2, b), acc, false);
+}
+__device__ __forceinline__ float f16_lo(uint32_t v) { return (float)__builtin_bit_cast(f16x2, v).x; }
+__device__ __forceinline__ float f16_hi(uint32_t v) { return (float)__builtin_bit_cast(f16x2, v).y; }
+__device__ __forceinline__ float f16_bits(uint16_t v) { return (float)__builtin_bit_cast(_Float16, v); }
+__device__ __forceinline__ uint32_t pack_f16(float a, float b) {
+  // saturate: activations beyond the fp16 range would turn into infinities
+  a = fminf(fmaxf(a, -65504.f), 65504.f);
+  b = fminf(fmaxf(b, -65504.f), 65504.f);
+  f16x2 v = {(_Float16)a, (_Float16)b};
+  return __builtin_bit_cast(uint32_t, v);
+}
+__device__ __forceinline__ float x_at(const void *x, int act_fmt, int col) {
+  return act_fmt == MOE_A_BF16 ? __uint_as_float((uint32_t) static_cast<const uint16_t *>(x)[col] << 16)
+                               : static_cast<const float *>(x)[col];
+}
+
+// =================================================================================================
+// int8
+// =================================================================================================
+template <int LPR>
+struct RecI8 {
+  u32x4 g[LPR], u[LPR], dn[LPR];
+  float sg, su, wt;
+  int seg;
+};
+
+template <int LPR, int NW, int DEPTH>
+__global__ __launch_bounds__(NW *kWave) void expert_gemv_int8_kernel(GemvParams p) {
+  constexpr int VEC = 16, CPL = LPR * VEC;
+  __shared__ float red[kRedFloats];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int d = p.hidden, I = p.inter, K = p.top_k;
+  const int64_t row16 = d / VEC;
+  const int64_t rec_bytes = 3 * row16 * 16;
+  const int routed = K * I;
+  const int total = routed + p.shared_inter;
+  const int r0 = (int)((int64_t)blockIdx.x * total / gridDim.x);
+  const int r1 = (int)((int64_t)(blockIdx.x + 1) * total / gridDim.x);
+  const int first = r0 + wave;
+  const int n = first < r1 ? (r1 - first + NW - 1) / NW : 0;
+  int seg = first < routed ? first / I : K;
+  int row = first < routed ? first - seg * I : first - routed;
+
+  auto seg_base = [&](int s) -> const uint8_t * { return s < K ? p.slot_pool + p.seg_off[s] : p.shared_blob; };
+  auto seg_rows = [&](int s) -> int { return s < K ? I : p.shared_inter; };
+
+  auto issue = [&](RecI8<LPR> &R) {
+    const uint8_t *base = seg_base(seg);
+    const uint16_t *tail = reinterpret_cast<const uint16_t *>(base + (int64_t)seg_rows(seg) * rec_bytes);
+    R.wt = seg < K ? p.seg_w[seg] : 1.f;
+    R.seg = seg;
+    const u32x4 *q = reinterpret_cast<const u32x4 *>(base + (int64_t)row * rec_bytes) + lane;
+#pragma unroll
+    for (int c = 0; c < LPR; ++c) R.g[c] = stream_load(q + c * kWave);
+    q += row16;
+#pragma unroll
+    for (int c = 0; c < LPR; ++c) R.u[c] = stream_load(q + c * kWave);
+    q += row16;
+#pragma unroll
+    for (int c = 0; c < LPR; ++c) R.dn[c] = stream_load(q + c * kWave);
+    R.sg = f16_bits(tail[row]);                 // gate scales [rows]
+    R.su = f16_bits(tail[seg_rows(seg) + row]);  // up scales [rows]
+    row += NW;
+    while (seg < K && row >= I) {
+      row -= I;
+      ++seg;
+    }
+  };
+
+  RecI8<LPR> ring[DEPTH];
+#pragma unroll
+  for (int j = 0; j < DEPTH; ++j)
+    if (j < n) issue(ring[j]);
+
+  // activations as packed fp16 pairs in column order, and their sum over this lane's columns
+  uint32_t xh[CPL / 2];
+  float xsum = 0.f;
+#pragma unroll
+  for (int c = 0; c < LPR; ++c)
+#pragma unroll
+    for (int v = 0; v < VEC; v += 2) {
+      const int col = (c * kWave + lane) * VEC + v;
+      const uint32_t pr = pack_f16(x_at(p.x, p.act_fmt, col), x_at(p.x, p.act_fmt, col + 1));
+      xh[(c * VEC + v) / 2] = pr;
+      xsum += f16_lo(pr) + f16_hi(pr);
+    }
+  const float xoff = -(1024.f + 128.f) * xsum;
+
+  float y[CPL], acc[CPL];
+#pragma unroll
+  for (int j = 0; j < CPL; ++j) y[j] = acc[j] = 0.f;
+  float hsum = 0.f;
+  int cur_seg = -1;
+
+  // y += scale_col * (acc - 128*hsum) with the per-column scales of expert `s`
+  auto flush = [&](int s) {
+    const uint16_t *sd = reinterpret_cast<const uint16_t *>(seg_base(s) + (int64_t)seg_rows(s) * rec_bytes) +
+                         2 * seg_rows(s);
+    const float off = 128.f * hsum;
+#pragma unroll
+    for (int c = 0; c < LPR; ++c) {
+      const u32x4 *sp = reinterpret_cast<const u32x4 *>(sd + (c * kWave + lane) * VEC);
+      const u32x4 s0 = sp[0], s1 = sp[1];
+      const uint32_t sw[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+#pragma unroll
+      for (int v = 0; v < VEC; v += 2) {
+        const int j = c * VEC + v;
+        y[j] = __builtin_fmaf(f16_lo(sw[v / 2]), acc[j] - off, y[j]);
+        y[j + 1] = __builtin_fmaf(f16_hi(sw[v / 2]), acc[j + 1] - off, y[j + 1]);
+        acc[j] = acc[j + 1] = 0.f;
+      }
+    }
+    hsum = 0.f;
+  };
+
+  auto consume = [&](const RecI8<LPR> &R) {
+    if (R.seg != cur_seg) {
+      if (cur_seg >= 0) flush(cur_seg);
+      cur_seg = R.seg;
+    }
+    float g0 = 0.f, g1 = 0.f, u0 = 0.f, u1 = 0.f;
+#pragma unroll
+    for (int c = 0; c < LPR; ++c) {
+      const uint32_t gw[4] = {R.g[c].x, R.g[c].y, R.g[c].z, R.g[c].w};
+      const uint32_t uw[4] = {R.u[c].x, R.u[c].y, R.u[c].z, R.u[c].w};
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        // bytes (b0,b1) and (b2,b3) of the dword -> fp16 pairs (1024+b)
+        const uint32_t glo = __builtin_amdgcn_perm(gw[w], 0x64646464u, 0x00050004u);
+        const uint32_t ghi = __builtin_amdgcn_perm(gw[w], 0x64646464u, 0x00070006u);
+        const uint32_t ulo = __builtin_amdgcn_perm(uw[w], 0x64646464u, 0x00050004u);
+        const uint32_t uhi = __builtin_amdgcn_perm(uw[w], 0x64646464u, 0x00070006u);
+        g0 = dot2_f16(glo, xh[c * 8 + w * 2], g0);
+        g1 = dot2_f16(ghi, xh[c * 8 + w * 2 + 1], g1);
+        u0 = dot2_f16(ulo, xh[c * 8 + w * 2], u0);
+        u1 = dot2_f16(uhi, xh[c * 8 + w * 2 + 1], u1);
+      }
+    }
+    float g = (g0 + g1) + xoff, u = (u0 + u1) + xoff;
+    wave_sum2(g, u);
+    g *= R.sg;
+    u *= R.su;
+    const float h = g / (1.f + __expf(-g)) * u * R.wt;
+    hsum += h;
+#pragma unroll
+    for (int c = 0; c < LPR; ++c) {
+      const uint32_t dw[4] = {R.dn[c].x, R.dn[c].y, R.dn[c].z, R.dn[c].w};
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const int j = c * VEC + w * 4;
+        acc[j] = __builtin_fmaf(h, (float)(dw[w] & 0xffu), acc[j]);
+        acc[j + 1] = __builtin_fmaf(h, (float)((dw[w] >> 8) & 0xffu), acc[j + 1]);
+        acc[j + 2] = __builtin_fmaf(h, (float)((dw[w] >> 16) & 0xffu), acc[j + 2]);
+        acc[j + 3] = __builtin_fmaf(h, (float)(dw[w] >> 24), acc[j + 3]);
+      }
+    }
+  };
+
+  for (int k = 0; k < n; k += DEPTH) {
+#pragma unroll
+    for (int j = 0; j < DEPTH; ++j) {
+      if (k + j < n) {
+        consume(ring[j]);
+        if (k + j + DEPTH < n) issue(ring[j]);
+      }
+    }
+  }
+  if (cur_seg >= 0) flush(cur_seg);
+  reduce_and_store<NW, VEC, LPR>(y, red, p.partial + (int64_t)blockIdx.x * d, tid, lane, wave);
+}
+
+// =================================================================================================
+// int4, group 128
+// =================================================================================================
+template <int LPR>
+struct RecI4 {
+  u32x4 g[LPR], u[LPR], dn[LPR];
+  uint32_t sc[LPR];  // (gate scale, up scale) fp16 pair of this lane's group, per chunk
+  float wt;
+  int seg, grp;
+};
+
+template <int LPR, int NW, int DEPTH>
+__global__ __launch_bounds__(NW *kWave) void expert_gemv_int4_kernel(GemvParams p) {
+  constexpr int VEC = 32, CPL = LPR * VEC;
+  __shared__ float red[kRedFloats];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int d = p.hidden, I = p.inter, K = p.top_k;
+  const int64_t row16 = d / VEC;                          // 16-byte chunks per row of nibbles
+  const int64_t rec_bytes = 3 * row16 * 16 + (d / 128) * 4;  // three rows + (gate, up) scale pairs
+  const int routed = K * I;
+  const int total = routed + p.shared_inter;
+  const int r0 = (int)((int64_t)blockIdx.x * total / gridDim.x);
+  const int r1 = (int)((int64_t)(blockIdx.x + 1) * total / gridDim.x);
+  const int first = r0 + wave;
+  const int n = first < r1 ? (r1 - first + NW - 1) / NW : 0;
+  int seg = first < routed ? first / I : K;
+  int row = first < routed ? first - seg * I : first - routed;
+
+  auto seg_base = [&](int s) -> const uint8_t * { return s < K ? p.slot_pool + p.seg_off[s] : p.shared_blob; };
+  auto seg_rows = [&](int s) -> int { return s < K ? I : p.shared_inter; };
+
+  auto issue = [&](RecI4<LPR> &R) {
+    const uint8_t *rec = seg_base(seg) + (int64_t)row * rec_bytes;
+    R.wt = seg < K ? p.seg_w[seg] : 1.f;
+    R.seg = seg;
+    R.grp = row >> 7;
+    const u32x4 *q = reinterpret_cast<const u32x4 *>(rec) + lane;
+#pragma unroll
+    for (int c = 0; c < LPR; ++c) R.g[c] = stream_load(q + c * kWave);
+    q += row16;
+#pragma unroll
+    for (int c = 0; c < LPR; ++c) R.u[c] = stream_load(q + c * kWave);
+    q += row16;
+#pragma unroll
+    for (int c = 0; c < LPR; ++c) R.dn[c] = stream_load(q + c * kWave);
+    const uint32_t *sc = reinterpret_cast<const uint32_t *>(rec + 3 * row16 * 16);
+#pragma unroll
+    for (int c = 0; c < LPR; ++c) R.sc[c] = sc[(c * kWave + lane) >> 2];  // 4 lanes (128 columns) per group
+    row += NW;
+    while (seg < K && row >= I) {
+      row -= I;
+      ++seg;
+    }
+  };
+
+  RecI4<LPR> ring[DEPTH];
+#pragma unroll
+  for (int j = 0; j < DEPTH; ++j)
+    if (j < n) issue(ring[j]);
+
+  // activations as packed bf16 pairs (column t, column t+4) per dword of 8 nibbles, and per-chunk sums
+  uint32_t xp[CPL / 2];
+  float xoff[LPR];
+#pragma unroll
+  for (int c = 0; c < LPR; ++c) {
+    float s = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const int col = (c * kWave + lane) * VEC + w * 8 + t;
+        const float a = x_at(p.x, p.act_fmt, col), b = x_at(p.x, p.act_fmt, col + 4);
+        const uint32_t pa = f32_to_bf16_rne(a), pb = f32_to_bf16_rne(b);
+        xp[c * 16 + w * 4 + t] = pa | (pb << 16);
+        s += __uint_as_float(pa << 16) + __uint_as_float(pb << 16);
+      }
+    xoff[c] = -(128.f + 8.f) * s;
+  }
+
+  float y[CPL], acc[CPL];
+#pragma unroll
+  for (int j = 0; j < CPL; ++j) y[j] = acc[j] = 0.f;
+  float hsum = 0.f;
+  int cur_seg = -1, cur_grp = -1;
+
+  // y += scale[group][col] * (acc - 1032*hsum)
+  auto flush = [&](int s, int grp) {
+    const uint16_t *sd = reinterpret_cast<const uint16_t *>(seg_base(s) + (int64_t)seg_rows(s) * rec_bytes) +
+                         (int64_t)grp * d;
+    const float off = (1024.f + 8.f) * hsum;
+#pragma unroll
+    for (int c = 0; c < LPR; ++c) {
+      const u32x4 *sp = reinterpret_cast<const u32x4 *>(sd + (c * kWave + lane) * VEC);
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const u32x4 sv = sp[q4];
+        const uint32_t sw[4] = {sv.x, sv.y, sv.z, sv.w};
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const int j = c * VEC + q4 * 8 + t * 2;
+          y[j] = __builtin_fmaf(f16_lo(sw[t]), acc[j] - off, y[j]);
+          y[j + 1] = __builtin_fmaf(f16_hi(sw[t]), acc[j + 1] - off, y[j + 1]);
+          acc[j] = acc[j + 1] = 0.f;
+        }
+      }
+    }
+    hsum = 0.f;
+  };
+
+  auto consume = [&](const RecI4<LPR> &R) {
+    if (R.seg != cur_seg || R.grp != cur_grp) {
+      if (cur_seg >= 0) flush(cur_seg, cur_grp);
+      cur_seg = R.seg;
+      cur_grp = R.grp;
+    }
+    float g = 0.f, u = 0.f;
+#pragma unroll
+    for (int c = 0; c < LPR; ++c) {
+      const uint32_t gw[4] = {R.g[c].x, R.g[c].y, R.g[c].z, R.g[c].w};
+      const uint32_t uw[4] = {R.u[c].x, R.u[c].y, R.u[c].z, R.u[c].w};
+      float g0 = 0.f, g1 = 0.f, u0 = 0.f, u1 = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const uint32_t *xw = &xp[c * 16 + w * 4];
+        // nibble pairs (t, t+4) -> packed bf16 (128 + n)
+        g0 = dot2_bf16((gw[w] & 0x000f000fu) | 0x43004300u, xw[0], g0);
+        g1 = dot2_bf16(((gw[w] >> 4) & 0x000f000fu) | 0x43004300u, xw[1], g1);
+        g0 = dot2_bf16(((gw[w] >> 8) & 0x000f000fu) | 0x43004300u, xw[2], g0);
+        g1 = dot2_bf16(((gw[w] >> 12) & 0x000f000fu) | 0x43004300u, xw[3], g1);
+        u0 = dot2_bf16((uw[w] & 0x000f000fu) | 0x43004300u, xw[0], u0);
+        u1 = dot2_bf16(((uw[w] >> 4) & 0x000f000fu) | 0x43004300u, xw[1], u1);
+        u0 = dot2_bf16(((uw[w] >> 8) & 0x000f000fu) | 0x43004300u, xw[2], u0);
+        u1 = dot2_bf16(((uw[w] >> 12) & 0x000f000fu) | 0x43004300u, xw[3], u1);
+      }
+      g = __builtin_fmaf((g0 + g1) + xoff[c], f16_lo(R.sc[c]), g);
+      u = __builtin_fmaf((u0 + u1) + xoff[c], f16_hi(R.sc[c]), u);
+    }
+    wave_sum2(g, u);
+    const float h = g / (1.f + __expf(-g)) * u * R.wt;
+    hsum += h;
+#pragma unroll
+    for (int c = 0; c < LPR; ++c) {
+      const uint32_t dw[4] = {R.dn[c].x, R.dn[c].y, R.dn[c].z, R.dn[c].w};
+#pragma unroll
+      for (int w = 0; w < 4; ++w)
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          // nibbles t and t+4 of the dword -> fp16 pair (1024 + n), consumed by mixed-precision FMAs
+          const uint32_t pr = ((dw[w] >> (4 * t)) & 0x000f000fu) | 0x64006400u;
+          const int j = c * VEC + w * 8 + t;
+          acc[j] = __builtin_fmaf(f16_lo(pr), h, acc[j]);
+          acc[j + 4] = __builtin_fmaf(f16_hi(pr), h, acc[j + 4]);
+        }
+    }
+  };
+
+  for (int k = 0; k < n; k += DEPTH) {
+#pragma unroll
+    for (int j = 0; j < DEPTH; ++j) {
+      if (k + j < n) {
+        consume(ring[j]);
+        if (k + j + DEPTH < n) issue(ring[j]);
+      }
+    }
+  }
+  if (cur_seg >= 0) flush(cur_seg, cur_grp);
+  reduce_and_store<NW, VEC, LPR>(y, red, p.partial + (int64_t)blockIdx.x * d, tid, lane, wave);
+}
+
+}  // namespace
+
+hipError_t launch_expert_gemv_quant(const GemvParams &p, int weight_fmt, const GemvPlan &plan, hipStream_t s,
+                                    hipEvent_t e0, hipEvent_t e1) {
+  const dim3 g(plan.grid), b(8 * kWave);
+  if (weight_fmt == MOE_W_INT8_PC) {
+    switch (p.hidden / (kWave * 16)) {
+      case 1: hipExtLaunchKernelGGL((expert_gemv_int8_kernel<1, 8, 2>), g, b, 0, s, e0, e1, 0, p); break;
+      case 2: hipExtLaunchKernelGGL((expert_gemv_int8_kernel<2, 8, 2>), g, b, 0, s, e0, e1, 0, p); break;
+      case 4: hipExtLaunchKernelGGL((expert_gemv_int8_kernel<4, 8, 1>), g, b, 0, s, e0, e1, 0, p); break;
+      default: return hipErrorInvalidValue;
+    }
+  } else if (weight_fmt == MOE_W_INT4_G128) {
+    switch (p.hidden / (kWave * 32)) {
+      case 1: hipExtLaunchKernelGGL((expert_gemv_int4_kernel<1, 8, 4>), g, b, 0, s, e0, e1, 0, p); break;
+      case 2: hipExtLaunchKernelGGL((expert_gemv_int4_kernel<2, 8, 2>), g, b, 0, s, e0, e1, 0, p); break;
+      default: return hipErrorInvalidValue;
+    }
+  } else {
+    return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace moe

@@ -1,0 +1,87 @@
+// Device helpers shared by the expert GEMV kernels (all weight formats).
+#pragma once
+
+#include "common.h"
+
+namespace moe {
+
+constexpr int kRedFloats = 16384;  // LDS floats (64 KB) shared by the wavefronts' rows in the final reduction
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// weights are read once: mark the loads non-temporal so they do not displace x and the partial rows in L2
+__device__ __forceinline__ u32x4 stream_load(const u32x4 *p) { return __builtin_nontemporal_load(p); }
+
+__device__ __forceinline__ float dot2_bf16(uint32_t w, uint32_t x, float acc) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), __builtin_bit_cast(bf16x2, x), acc, false);
+}
+
+// sums a and b over the wavefront (both results in every lane), the two chains interleaved
+__device__ __forceinline__ void wave_sum2(float &a, float &b) {
+  a += dpp_f32<0x128>(a);
+  b += dpp_f32<0x128>(b);
+  a += dpp_f32<0x124>(a);
+  b += dpp_f32<0x124>(b);
+  a += dpp_f32<0x122>(a);
+  b += dpp_f32<0x122>(b);
+  a += dpp_f32<0x121>(a);
+  b += dpp_f32<0x121>(b);
+  float a0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a), 0));
+  float a1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a), 16));
+  float a2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a), 32));
+  float a3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a), 48));
+  float b0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(b), 0));
+  float b1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(b), 16));
+  float b2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(b), 32));
+  float b3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(b), 48));
+  a = (a0 + a1) + (a2 + a3);
+  b = (b0 + b1) + (b2 + b3);
+}
+
+
+// Sum the wavefronts' private outputs through LDS (one barrier per pass) and write the workgroup's fp32
+// partial row.  y holds, for load index c and v < VEC, column (c*64 + lane)*VEC + v at y[c*VEC + v].
+// Slot (cv*64 + lane) of a wavefront's LDS row holds 4 columns with cv = c_in_pass*(VEC/4) + v4, so
+// consecutive lanes hit consecutive 16-byte slots.  Wavefronts are added in index order (deterministic).
+template <int NW, int VEC, int LPR>
+__device__ __forceinline__ void reduce_and_store(const float *y, float *red, float *out, int tid, int lane, int wave) {
+  constexpr int kRedCols = kRedFloats / NW;      // columns per LDS pass
+  constexpr int CBF = kRedCols / (kWave * VEC);  // load indices c per pass (0 if a chunk exceeds a pass)
+  constexpr int CB = CBF > 0 ? CBF : 1;
+  static_assert(CBF > 0, "one 16-byte chunk per lane must fit an LDS pass");
+  constexpr int PASSES = (LPR + CB - 1) / CB;
+  constexpr int CPP = (LPR < CB ? LPR : CB);  // c per pass actually present
+  constexpr int SLOTS = kRedCols / 4;         // float4 slots per wavefront row
+  float4 *red4 = reinterpret_cast<float4 *>(red);
+#pragma unroll
+  for (int ps = 0; ps < PASSES; ++ps) {
+    if (ps > 0) __syncthreads();
+    float4 *dst = red4 + wave * SLOTS;
+#pragma unroll
+    for (int cc = 0; cc < CPP; ++cc)
+#pragma unroll
+      for (int v4 = 0; v4 < VEC / 4; ++v4) {
+        const int j = (ps * CB + cc) * VEC + v4 * 4;
+        dst[(cc * (VEC / 4) + v4) * kWave + lane] = make_float4(y[j], y[j + 1], y[j + 2], y[j + 3]);
+      }
+    __syncthreads();
+    for (int sl = tid; sl < CPP * (VEC / 4) * kWave; sl += NW * kWave) {
+      float4 acc = red4[sl];
+#pragma unroll
+      for (int w = 1; w < NW; ++w) {
+        const float4 t = red4[w * SLOTS + sl];
+        acc.x += t.x;
+        acc.y += t.y;
+        acc.z += t.z;
+        acc.w += t.w;
+      }
+      const int cv = sl / kWave, ln = sl % kWave;
+      const int c = ps * CB + cv / (VEC / 4), v4 = cv % (VEC / 4);
+      *reinterpret_cast<float4 *>(out + (c * kWave + ln) * VEC + v4 * 4) = acc;
+    }
+  }
+}
+
+}  // namespace moe

@@ -56,7 +56,7 @@ struct moe_cache {
   moe_route_out_t *h_route_dev = nullptr;  // device view of h_route
   int32_t *d_initial = nullptr;
   float *d_partial = nullptr;
-  int gemv_grid = 0;
+  GemvPlan plan{};
   hipEvent_t ev_route = nullptr;
   std::vector<hipEvent_t> ev_copy;
   std::vector<uint8_t> routed;        // per layer: a route step awaits its expert_forward
@@ -108,7 +108,7 @@ const char *moe_last_error(void) { return g_err.c_str(); }
 
 size_t moe_blob_bytes(int32_t weight_fmt, int32_t hidden, int32_t inter) {
   if (!valid_wfmt(weight_fmt) || hidden <= 0 || inter <= 0) return 0;
-  if (!gemv_shape_supported(weight_fmt, hidden)) return 0;
+  if (!gemv_shape_supported(weight_fmt, hidden) || !gemv_inter_supported(weight_fmt, inter)) return 0;
   return (size_t)blob_layout(weight_fmt, hidden, inter).total;
 }
 
@@ -116,7 +116,8 @@ int moe_pack_expert(int32_t weight_fmt, int32_t hidden, int32_t inter, const voi
                     const void *down, const void *gate_s, const void *up_s, const void *down_s, void *blob_dev,
                     void *stream) {
   if (!valid_wfmt(weight_fmt)) return fail(MOE_EINVAL, "unknown weight format %d", weight_fmt);
-  if (hidden <= 0 || inter <= 0 || !gemv_shape_supported(weight_fmt, hidden))
+  if (hidden <= 0 || inter <= 0 || !gemv_shape_supported(weight_fmt, hidden) ||
+      !gemv_inter_supported(weight_fmt, inter))
     return fail(MOE_EINVAL, "unsupported shape hidden=%d inter=%d for weight format %d", hidden, inter, weight_fmt);
   if (!gate || !up || !down || !blob_dev) return fail(MOE_EINVAL, "NULL weight or blob pointer");
   const bool quant = weight_fmt == MOE_W_INT8_PC || weight_fmt == MOE_W_INT4_G128;
@@ -142,7 +143,9 @@ int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, 
   if (cfg->inter <= 0 || cfg->shared_inter < 0) return fail(MOE_EINVAL, "bad intermediate size");
   if (!gemv_shape_supported(cfg->weight_fmt, cfg->hidden))
     return fail(MOE_EINVAL, "hidden=%d unsupported for weight format %d (needs 64*{1,2,4,8} 16-byte loads per row)", cfg->hidden, cfg->weight_fmt);
-  if (cfg->hidden % 8 != 0) return fail(MOE_EINVAL, "hidden must be a multiple of 8");
+  if (!gemv_inter_supported(cfg->weight_fmt, cfg->inter) ||
+      (cfg->shared_inter > 0 && !gemv_inter_supported(cfg->weight_fmt, cfg->shared_inter)))
+    return fail(MOE_EINVAL, "intermediate size unsupported for this weight format (int8: multiple of 8, int4: multiple of 128)");
   if (!(cfg->lambda >= 0.f) || !std::isfinite(cfg->lambda)) return fail(MOE_EINVAL, "lambda must be finite and >= 0");
   if (cfg->delta_mode != MOE_DELTA_RUNNING_MEAN && cfg->delta_mode != MOE_DELTA_FIXED) return fail(MOE_EINVAL, "bad delta_mode");
   if (cfg->delta_mode == MOE_DELTA_FIXED && !std::isfinite(cfg->delta_fixed)) return fail(MOE_EINVAL, "delta_fixed must be finite");
@@ -205,14 +208,7 @@ int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, 
   HIP_INIT(hipGetDevice(&dev));
   int cus = 0;
   HIP_INIT(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-  int per_cu = 1;
-  if (const char *s = getenv("MOE_GEMV_WGS_PER_CU")) per_cu = atoi(s) > 0 ? atoi(s) : 1;
-  c->gemv_grid = cus * per_cu;
-  if (const char *s = getenv("MOE_GEMV_GRID")) {
-    if (atoi(s) > 0) c->gemv_grid = atoi(s);
-  }
-  const int total_rec = cfg->top_k * cfg->inter + cfg->shared_inter;
-  if (c->gemv_grid > total_rec) c->gemv_grid = total_rec;
+  c->plan = gemv_plan(cus, cfg->top_k * cfg->inter + cfg->shared_inter, cfg->weight_fmt, cfg->act_fmt);
   if (const char *s = getenv("MOE_HOST_SYNC")) c->poll = strcmp(s, "poll") == 0;
 
   HIP_INIT(hipMalloc(&c->d_state, sizeof(LayerState) * L));
@@ -223,7 +219,7 @@ int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, 
   memset(c->h_route, 0, sizeof(moe_route_out_t) * L);
   HIP_INIT(hipHostGetDevicePointer(reinterpret_cast<void **>(&c->h_route_dev), c->h_route, 0));
   HIP_INIT(hipMalloc(&c->d_initial, sizeof(int32_t) * (size_t)L * (b->n_initial > 0 ? b->n_initial : 1)));
-  HIP_INIT(hipMalloc(&c->d_partial, sizeof(float) * (size_t)c->gemv_grid * cfg->hidden));
+  HIP_INIT(hipMalloc(&c->d_partial, sizeof(float) * (size_t)c->plan.grid * cfg->hidden));
   HIP_INIT(hipEventCreateWithFlags(&c->ev_route, hipEventDisableTiming));
   for (int l = 0; l < L; ++l) HIP_INIT(hipEventCreateWithFlags(&c->ev_copy[l], hipEventDisableTiming));
 #undef HIP_INIT
@@ -329,7 +325,10 @@ int moe_expert_forward(moe_cache_t *c, int32_t layer, const void *x_dev, void *y
   GemvParams p{};
   p.slot_pool = static_cast<const uint8_t *>(c->slot_pool[layer]);
   p.shared_blob = g.shared_inter > 0 ? static_cast<const uint8_t *>(c->shared_blob[layer]) : nullptr;
-  p.route = c->d_route + layer;
+  for (int k = 0; k < g.top_k; ++k) {
+    p.seg_off[k] = (int64_t)c->h_route[layer].sel_slot[k] * c->slot_layout.total;
+    p.seg_w[k] = c->h_route[layer].sel_weight[k];
+  }
   p.x = x_dev;
   p.partial = c->d_partial;
   p.hidden = g.hidden;
@@ -346,14 +345,13 @@ int moe_expert_forward(moe_cache_t *c, int32_t layer, const void *x_dev, void *y
       HIP_TRY(hipEventCreate(&b));
       c->prof_events.emplace_back(a, b);
     }
-    HIP_TRY(hipEventRecord(c->prof_events[c->prof_used].first, c->compute));
-  }
-  HIP_TRY(launch_expert_gemv(p, g.weight_fmt, c->gemv_grid, c->compute));
-  if (prof) {
-    HIP_TRY(hipEventRecord(c->prof_events[c->prof_used].second, c->compute));
+    HIP_TRY(launch_expert_gemv(p, g.weight_fmt, c->plan, c->compute, c->prof_events[c->prof_used].first,
+                               c->prof_events[c->prof_used].second));
     ++c->prof_used;
+  } else {
+    HIP_TRY(launch_expert_gemv(p, g.weight_fmt, c->plan, c->compute));
   }
-  HIP_TRY(launch_partial_reduce(c->d_partial, c->gemv_grid, y_dev, g.hidden, g.act_fmt, c->compute));
+  HIP_TRY(launch_partial_reduce(c->d_partial, c->plan.grid, y_dev, g.hidden, g.act_fmt, c->compute));
   c->routed[layer] = 0;
   return MOE_OK;
 }

@@ -6,14 +6,30 @@ namespace moe {
 BlobLayout blob_layout(int fmt, int hidden, int inter) {
   BlobLayout L{};
   const int64_t d = hidden, I = inter;
+  int64_t tail_bytes = 0;
   switch (fmt) {
-    case MOE_W_FP32: L.row_bytes = d * 4; break;
-    case MOE_W_BF16: L.row_bytes = d * 2; break;
+    case MOE_W_FP32:
+      L.row_bytes = d * 4;
+      L.rec_bytes = 3 * L.row_bytes;
+      break;
+    case MOE_W_BF16:
+      L.row_bytes = d * 2;
+      L.rec_bytes = 3 * L.row_bytes;
+      break;
+    case MOE_W_INT8_PC:  // tail: gate scales [I], up scales [I], down scales [d], fp16
+      L.row_bytes = d;
+      L.rec_bytes = 3 * L.row_bytes;
+      tail_bytes = (2 * I + d) * 2;
+      break;
+    case MOE_W_INT4_G128:  // record carries its (gate, up) group scales; tail: down scales [I/128][d], fp16
+      L.row_bytes = d / 2;
+      L.rec_bytes = 3 * L.row_bytes + (d / 128) * 4;
+      tail_bytes = (I / 128) * d * 2;
+      break;
     default: return L;
   }
-  L.rec_bytes = 3 * L.row_bytes;
   L.tail_offset = I * L.rec_bytes;
-  L.total = (L.tail_offset + 255) / 256 * 256;
+  L.total = (L.tail_offset + tail_bytes + 255) / 256 * 256;
   return L;
 }
 
@@ -46,6 +62,74 @@ __global__ void pack_plain_kernel(const T *gate, const T *up, const T *down, T *
     T *o = blob + (rec * 3 + sec) * d + col;
 #pragma unroll
     for (int j = 0; j < VEC; ++j) o[j] = v[j];
+  }
+}
+
+// int8: values become offset-binary bytes (q + 128); scales go to the tail.
+__global__ void pack_int8_kernel(const int8_t *gate, const int8_t *up, const int8_t *down, const uint16_t *gs,
+                                 const uint16_t *us, const uint16_t *ds, uint8_t *blob, int d, int I) {
+  const int64_t chunks_per_row = d / 16;
+  const int64_t n_chunks = (int64_t)I * 3 * chunks_per_row;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (int64_t c = gid; c < n_chunks; c += stride) {
+    const int64_t rec = c / (3 * chunks_per_row);
+    const int64_t rem = c - rec * 3 * chunks_per_row;
+    const int sec = (int)(rem / chunks_per_row);
+    const int64_t col = (rem - sec * chunks_per_row) * 16;
+    uint8_t *o = blob + (rec * 3 + sec) * d + col;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) {
+      const int8_t q = sec == 0 ? gate[rec * d + col + j] : sec == 1 ? up[rec * d + col + j] : down[(col + j) * I + rec];
+      o[j] = (uint8_t)q ^ 0x80u;
+    }
+  }
+  uint16_t *tail = reinterpret_cast<uint16_t *>(blob + (int64_t)I * 3 * d);
+  for (int64_t i = gid; i < 2 * (int64_t)I + d; i += stride)
+    tail[i] = i < I ? gs[i] : i < 2 * (int64_t)I ? us[i - I] : ds[i - 2 * I];
+}
+
+// int4: canonical bytes hold two nibbles (even column low); gate/up rows are copied, the down column is
+// gathered nibble by nibble; the record ends with its (gate, up) scale pairs, the down scales form the tail.
+__global__ void pack_int4_kernel(const uint8_t *gate, const uint8_t *up, const uint8_t *down, const uint16_t *gs,
+                                 const uint16_t *us, const uint16_t *ds, uint8_t *blob, int d, int I) {
+  const int64_t row_bytes = d / 2, groups = d / 128, rec_bytes = 3 * row_bytes + groups * 4;
+  const int64_t chunks_per_row = row_bytes / 16;
+  const int64_t n_chunks = (int64_t)I * 3 * chunks_per_row;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (int64_t c = gid; c < n_chunks; c += stride) {
+    const int64_t rec = c / (3 * chunks_per_row);
+    const int64_t rem = c - rec * 3 * chunks_per_row;
+    const int sec = (int)(rem / chunks_per_row);
+    const int64_t b0 = (rem - sec * chunks_per_row) * 16;  // first byte of the chunk inside the row
+    uint8_t *o = blob + rec * rec_bytes + sec * row_bytes + b0;
+    if (sec < 2) {
+      const uint8_t *src = (sec == 0 ? gate : up) + rec * row_bytes + b0;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) o[j] = src[j];
+    } else {
+      const int64_t in_row = I / 2;  // bytes per row of the canonical [d, I/2] matrix
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int64_t c0 = (b0 + j) * 2;  // two output columns share a byte
+        const uint8_t a = down[c0 * in_row + rec / 2], b = down[(c0 + 1) * in_row + rec / 2];
+        const int sh = (rec & 1) * 4;
+        o[j] = (uint8_t)(((a >> sh) & 0xf) | (((b >> sh) & 0xf) << 4));
+      }
+    }
+  }
+  for (int64_t i = gid; i < (int64_t)I * groups; i += stride) {
+    const int64_t rec = i / groups, g = i - rec * groups;
+    uint16_t *o = reinterpret_cast<uint16_t *>(blob + rec * rec_bytes + 3 * row_bytes + g * 4);
+    o[0] = gs[rec * groups + g];
+    o[1] = us[rec * groups + g];
+  }
+  uint16_t *tail = reinterpret_cast<uint16_t *>(blob + (int64_t)I * rec_bytes);
+  const int64_t rgroups = I / 128;
+  for (int64_t i = gid; i < rgroups * d; i += stride) {
+    const int64_t g = i / d, col = i - g * d;
+    tail[i] = ds[col * rgroups + g];
   }
 }
 
@@ -83,10 +167,8 @@ __global__ __launch_bounds__(1024) void residual_rmsnorm_kernel(float *h, const 
 
 hipError_t launch_pack(int fmt, int hidden, int inter, const void *gate, const void *up, const void *down,
                        const void *gs, const void *us, const void *ds, void *blob, hipStream_t s) {
-  (void)gs;
-  (void)us;
-  (void)ds;
-  const int64_t chunks = (int64_t)inter * 3 * hidden / (fmt == MOE_W_FP32 ? 4 : 8);
+  const int per16 = fmt == MOE_W_FP32 ? 4 : fmt == MOE_W_BF16 ? 8 : fmt == MOE_W_INT8_PC ? 16 : 32;
+  const int64_t chunks = (int64_t)inter * 3 * hidden / per16;
   int grid = (int)((chunks + 255) / 256);
   if (grid > 65535) grid = 65535;
   if (fmt == MOE_W_FP32) {
@@ -97,6 +179,16 @@ hipError_t launch_pack(int fmt, int hidden, int inter, const void *gate, const v
     hipLaunchKernelGGL(pack_plain_kernel<uint16_t>, dim3(grid), dim3(256), 0, s,
                        static_cast<const uint16_t *>(gate), static_cast<const uint16_t *>(up),
                        static_cast<const uint16_t *>(down), static_cast<uint16_t *>(blob), hidden, inter);
+  } else if (fmt == MOE_W_INT8_PC) {
+    hipLaunchKernelGGL(pack_int8_kernel, dim3(grid), dim3(256), 0, s, static_cast<const int8_t *>(gate),
+                       static_cast<const int8_t *>(up), static_cast<const int8_t *>(down),
+                       static_cast<const uint16_t *>(gs), static_cast<const uint16_t *>(us),
+                       static_cast<const uint16_t *>(ds), static_cast<uint8_t *>(blob), hidden, inter);
+  } else if (fmt == MOE_W_INT4_G128) {
+    hipLaunchKernelGGL(pack_int4_kernel, dim3(grid), dim3(256), 0, s, static_cast<const uint8_t *>(gate),
+                       static_cast<const uint8_t *>(up), static_cast<const uint8_t *>(down),
+                       static_cast<const uint16_t *>(gs), static_cast<const uint16_t *>(us),
+                       static_cast<const uint16_t *>(ds), static_cast<uint8_t *>(blob), hidden, inter);
   } else {
     return hipErrorInvalidValue;
   }

@@ -75,25 +75,44 @@ def gate_weight(cfg: MoEWorkload, layer: int, device="cpu") -> torch.Tensor:
     return w.view(cfg.n_experts, cfg.hidden).to(cfg.act_dtype)
 
 
+def _nearest_code(w: torch.Tensor, s: torch.Tensor, lo: int, hi: int) -> torch.Tensor:
+    """Integer code q in [lo, hi] minimising |w - q*s| (ties -> smaller q), as an int16 tensor.
+
+    A first guess comes from a division, whose last bit may depend on the device; the decision among the
+    guess and its two neighbours is then taken on |w - q*s| evaluated in fp64, where the product and the
+    difference are exact, so every device returns the same codes.
+    """
+    q = torch.clamp(torch.round(w / s), lo, hi)
+    w64, s64 = w.double(), s.double()
+    err = (w64 - q.double() * s64).abs()
+    for dq in (-1.0, 1.0):
+        q1 = torch.clamp(q + dq, lo, hi)
+        e1 = (w64 - q1.double() * s64).abs()
+        better = (e1 < err) | ((e1 == err) & (q1 < q))
+        q = torch.where(better, q1, q)
+        err = torch.where(better, e1, err)
+    return q.to(torch.int16)
+
+
 def quantize_int8(w: torch.Tensor):
-    """Per output row symmetric int8: s = max|w|/127 (stored fp16), q = clamp(rint(w/s), -127, 127)."""
-    s = (w.abs().amax(dim=1) / 127.0).to(torch.float16)
+    """Per output row symmetric int8: s = max|w|/127 (stored fp16), q = nearest code in [-127, 127]."""
+    s = (w.abs().amax(dim=1) * (1.0 / 127.0)).to(torch.float16)
     s = torch.where(s == 0, torch.ones_like(s), s)
-    q = torch.clamp(torch.round(w / s.float()[:, None]), -127, 127).to(torch.int8)
+    q = _nearest_code(w, s.float()[:, None], -127, 127).to(torch.int8)
     return q, s
 
 
 def quantize_int4(w: torch.Tensor):
-    """Group-128 symmetric int4 along each row: s = max|w|/7 (fp16), q = clamp(rint(w/s), -8, 7).
+    """Group-128 symmetric int4 along each row: s = max|w|/7 (fp16), q = nearest code in [-8, 7].
 
     Stored as one byte per two weights: nibble = q + 8, even column in the low nibble.
     """
     rows, cols = w.shape
     assert cols % INT4_GROUP == 0
     g = w.view(rows, cols // INT4_GROUP, INT4_GROUP)
-    s = (g.abs().amax(dim=2) / 7.0).to(torch.float16)
+    s = (g.abs().amax(dim=2) * (1.0 / 7.0)).to(torch.float16)
     s = torch.where(s == 0, torch.ones_like(s), s)
-    q = torch.clamp(torch.round(g / s.float()[:, :, None]), -8, 7).to(torch.int16) + 8
+    q = _nearest_code(g, s.float()[:, :, None], -8, 7) + 8
     q = q.view(rows, cols)
     packed = (q[:, 0::2] | (q[:, 1::2] << 4)).to(torch.uint8)
     return packed, s

@@ -104,3 +104,89 @@ def test_stack_glue_kernel(fmt):
     assert oexp.rel_err(hd.cpu().numpy(), h_ref) <= 1e-6
     assert oexp.rel_err(xd.float().cpu().numpy(), x_ref) <= (1e-6 if fmt == "fp32" else 4e-3)
     dec.close()
+
+
+# ---------------------------------------------------------------- weight-only int8 / int4
+
+
+@pytest.mark.parametrize("hidden,inter", [(4096, 160), (2048, 104), (1024, 64)])
+def test_int8_reduced(hidden, inter):
+    cfg = CONFIGS["c5_mixtral_int8"].with_(n_layers=2, hidden=hidden, inter=inter, seed=400 + hidden)
+    print(f"case int8 hidden={hidden}", flush=True)
+    free_run(cfg, 0.5, 32, top_j=1)
+
+
+@pytest.mark.parametrize("hidden,inter,shared", [(2048, 256, 384), (4096, 128, 0)])
+def test_int4_reduced(hidden, inter, shared):
+    cfg = CONFIGS["c4_dsv2lite_int4"].with_(n_layers=2, hidden=hidden, inter=inter, shared_inter=shared,
+                                            n_experts=16, capacity=8, seed=500 + hidden)
+    print(f"case int4 hidden={hidden}", flush=True)
+    free_run(cfg, 0.5, 32, top_j=2)
+
+
+@pytest.mark.parametrize("fmt", ["int8", "int4"])
+def test_quantised_layout_closed_form(fmt):
+    """Single non-zero code per matrix: exposes byte/nibble order, scale indexing and the packer's transpose."""
+    import torch
+
+    d, I = 2048, 256
+    cfg = CONFIGS["c4_dsv2lite_int4"].with_(n_layers=1, hidden=d, inter=I, shared_inter=0, n_experts=2, capacity=2,
+                                            top_k=1, weight_fmt=fmt)
+    store, dec = build(cfg)
+    i, j1, j2, j3 = 133, 5, 1990, 1029
+    if fmt == "int8":
+        gq = torch.zeros(I, d, dtype=torch.int8); uq = torch.zeros(I, d, dtype=torch.int8)
+        dq = torch.zeros(d, I, dtype=torch.int8)
+        gq[i, j1], uq[i, j2], dq[j3, i] = 100, -50, 77
+        gs = torch.ones(I, dtype=torch.float16); us = torch.ones(I, dtype=torch.float16)
+        ds = torch.ones(d, dtype=torch.float16)
+        gs[i], us[i], ds[j3] = 0.25, 0.5, 0.125
+        wg, wu, wd = 100 * 0.25, -50 * 0.5, 77 * 0.125
+    else:
+        def codes(rows, cols):
+            return torch.full((rows, cols // 2), 0x88, dtype=torch.uint8)  # all q = 0
+
+        gq, uq, dq = codes(I, d), codes(I, d), codes(d, I)
+        def put(m, r, c, q):
+            b = int(m[r, c // 2])
+            m[r, c // 2] = (b & 0xF0) | (q + 8) if c % 2 == 0 else (b & 0x0F) | ((q + 8) << 4)
+        put(gq, i, j1, 7); put(uq, i, j2, -8); put(dq, j3, i, 5)
+        gs = torch.ones(I, d // 128, dtype=torch.float16); us = torch.ones(I, d // 128, dtype=torch.float16)
+        ds = torch.ones(d, I // 128, dtype=torch.float16)
+        gs[i, j1 // 128], us[i, j2 // 128], ds[j3, i // 128] = 0.25, 0.5, 0.125
+        wg, wu, wd = 7 * 0.25, -8 * 0.5, 5 * 0.125
+    store.put_expert(0, 1, {"gate": (gq, gs), "up": (uq, us), "down": (dq, ds)})
+    x = torch.zeros(d); x[j1], x[j2] = 0.75, 2.0
+    xd, yd = x.to(torch.bfloat16).to(DEV), torch.zeros(d, dtype=torch.bfloat16, device=DEV)
+    z = torch.tensor([0.0, 5.0], device=DEV)
+    torch.cuda.synchronize()
+    out = dec.route_step(0, logits=z)
+    assert list(out.sel_expert[:1]) == [1]
+    dec.expert_forward(0, xd, yd)
+    dec.compute_stream.synchronize()
+    a = wg * 0.75
+    w = math.exp(5.0) / (1.0 + math.exp(5.0))
+    expect = wd * (a / (1 + math.exp(-a))) * (wu * 2.0) * w
+    y = yd.float().cpu().numpy()
+    assert abs(y[j3] - expect) <= 5e-3 * abs(expect), (y[j3], expect)
+    y[j3] = 0
+    assert np.abs(y).max() <= 1e-3 * abs(expect), np.abs(y).max()
+    dec.close()
+
+
+def test_generators_are_device_independent():
+    """The oracle regenerates weights on the CPU; the store is filled from the device: same bits."""
+    import torch
+    from synth import workloads
+
+    for fmt in ("fp32", "bf16", "int8", "int4"):
+        cfg = CONFIGS["c4_dsv2lite_int4"].with_(hidden=2048, inter=256, weight_fmt=fmt, seed=31)
+        a, b = workloads.expert_weights(cfg, 1, 3, "cpu"), workloads.expert_weights(cfg, 1, 3, DEV)
+        for k in ("gate", "up", "down"):
+            ta = a[k] if isinstance(a[k], tuple) else (a[k],)
+            tb = b[k] if isinstance(b[k], tuple) else (b[k],)
+            for u, v in zip(ta, tb):
+                assert torch.equal(u, v.cpu()), (fmt, k)
+    cfg = CONFIGS["c2_qwen_bf16"].with_(n_layers=2)
+    assert torch.equal(workloads.ar1_stream(cfg, 16), workloads.ar1_stream(cfg, 16, device=DEV).cpu())
+    assert torch.equal(workloads.gate_weight(cfg, 1), workloads.gate_weight(cfg, 1, DEV).cpu())
