@@ -209,7 +209,10 @@ int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, 
   int cus = 0;
   HIP_INIT(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
   c->plan = gemv_plan(cus, cfg->top_k * cfg->inter + cfg->shared_inter, cfg->weight_fmt, cfg->act_fmt);
-  if (const char *s = getenv("MOE_HOST_SYNC")) c->poll = strcmp(s, "poll") == 0;
+  // the host learns a routing decision by polling the tag the kernel releases into mapped host memory;
+  // MOE_HOST_SYNC=event waits on a stream event instead
+  c->poll = true;
+  if (const char *s = getenv("MOE_HOST_SYNC")) c->poll = strcmp(s, "event") != 0;
 
   HIP_INIT(hipMalloc(&c->d_state, sizeof(LayerState) * L));
   HIP_INIT(hipMalloc(&c->d_route, sizeof(moe_route_out_t) * L));

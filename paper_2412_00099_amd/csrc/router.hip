@@ -5,24 +5,38 @@
 // selected are single fp32 operations in a fixed order (subtract, add, divide, multiply, add), so the
 // decisions are reproducible bit for bit from the same fp32 logits.
 //
-// Layout of the work: one workgroup.  All its wavefronts compute rows of z = W_gate x (128-bit loads,
-// fp32 accumulation, wavefront reduction); wavefront 0 then does the routing with lane e <-> expert e
-// and lane s <-> slot s (N <= 64, C <= 64), entirely in registers, and writes the decision both to
-// device memory (read by the expert kernel) and to host-mapped memory (read by the host to issue fills).
+// Layout of the work: one workgroup.  All its wavefronts compute rows of z = W_gate x (128-bit loads, up to
+// four rows per wavefront with all their loads in flight together, fp32 accumulation, DPP reduction);
+// wavefront 0 then does the routing with lane e <-> expert e and lane s <-> slot s (N <= 64, C <= 64),
+// entirely in registers.  Rankings are counted with one 64-bit compare per pair: the key is the logit
+// mapped to an order-preserving unsigned integer, with 63 - lane below it so that equal logits rank the
+// lower index first.  The decision record is assembled in LDS and written with 16-byte stores to device
+// memory and to host-mapped memory, followed by a release of the completion tag.
 #include "common.h"
 
 namespace moe {
 namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kRecWords = sizeof(moe_route_out_t) / 4;
+static_assert(sizeof(moe_route_out_t) % 16 == 0, "route record is copied in 16-byte chunks");
+// word offsets inside moe_route_out_t
+constexpr int W_EXPERT = 0, W_SLOT = 8, W_WEIGHT = 16, W_MISS = 24, W_EVICT = 32, W_NMISS = 40, W_TOKEN = 41,
+              W_DELTA = 42, W_MARGIN = 43, W_LOGITS = 44, W_SEQ = 44 + MOE_MAX_EXPERTS;
+static_assert(W_SEQ * 4 == offsetof(moe_route_out_t, seq), "record layout");
+static_assert(W_LOGITS * 4 == offsetof(moe_route_out_t, logits), "record layout");
 
 __device__ __forceinline__ uint64_t ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }
 __device__ __forceinline__ int readlane_i(int v, int l) { return __builtin_amdgcn_readlane(v, l); }
 __device__ __forceinline__ float readlane_f(float v, int l) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
 }
-__device__ __forceinline__ int64_t readlane_i64(int64_t v, int l) {
-  uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, l);
-  uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)((uint64_t)v >> 32), l);
-  return (int64_t)(((uint64_t)hi << 32) | lo);
+__device__ __forceinline__ uint64_t readlane_u64(uint64_t v, int l) {
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, l);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), l);
+  return ((uint64_t)hi << 32) | lo;
 }
 
 template <int CTRL>
@@ -38,66 +52,108 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 __device__ __forceinline__ float wave_min(float v) { return -wave_max(-v); }
 
-// Position of each lane's key in the descending order of (key, lower lane first) over lanes < n.
-__device__ __forceinline__ int rank_desc(float key, int lane, int n) {
-  int r = 0;
-  for (int j = 0; j < n; ++j) {
-    float kj = readlane_f(key, j);
-    r += (kj > key) || (kj == key && j < lane);
-  }
-  return r;
+// Order-preserving map of a finite float to uint32 (+0 and -0 must have been merged by the caller).
+__device__ __forceinline__ uint32_t sortable(float f) {
+  const uint32_t u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
-// Same for ascending integer keys (unique keys expected).
-__device__ __forceinline__ int rank_asc_i(int key, int n) {
+// key: larger = earlier in a descending ranking; equal values rank the lower lane first
+__device__ __forceinline__ uint64_t rank_key(float v, int lane, bool active) {
+  return active ? (((uint64_t)sortable(v + 0.f) << 32) | (uint32_t)(63 - lane)) : 0ull;
+}
+// number of lanes < n whose key is larger than mine = my position in the descending ranking
+__device__ __forceinline__ int rank_of(uint64_t key, int n) {
   int r = 0;
-  for (int j = 0; j < n; ++j) r += readlane_i(key, j) < key;
+  for (int j = 0; j < n; ++j) r += readlane_u64(key, j) > key;
   return r;
 }
 
-__device__ __forceinline__ float gate_row_dot(const void *gate_w, const void *x, int row, int d, int act_fmt,
-                                              int lane) {
-  float acc = 0.f;
+__device__ __forceinline__ float dot2(uint32_t w, uint32_t x, float acc) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w), __builtin_bit_cast(bf16x2, x), acc, false);
+}
+
+// Up to R consecutive rows of z = W_gate x for one wavefront, all loads of a chunk column issued together.
+template <int R>
+__device__ __forceinline__ void gate_rows(const void *gate_w, const void *x, int row0, int nrows, int d, int act_fmt,
+                                          int lane, float *out) {
+  float acc[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) acc[r] = 0.f;
   if (act_fmt == MOE_A_BF16) {
-    const uint4 *w = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(gate_w) + (size_t)row * d);
-    const uint4 *xv = reinterpret_cast<const uint4 *>(x);
-    for (int c = lane; c < d / 8; c += kWave) {
-      uint4 a = w[c], b = xv[c];
-      acc = __builtin_fmaf(bf16_lo(a.x), bf16_lo(b.x), acc);
-      acc = __builtin_fmaf(bf16_hi(a.x), bf16_hi(b.x), acc);
-      acc = __builtin_fmaf(bf16_lo(a.y), bf16_lo(b.y), acc);
-      acc = __builtin_fmaf(bf16_hi(a.y), bf16_hi(b.y), acc);
-      acc = __builtin_fmaf(bf16_lo(a.z), bf16_lo(b.z), acc);
-      acc = __builtin_fmaf(bf16_hi(a.z), bf16_hi(b.z), acc);
-      acc = __builtin_fmaf(bf16_lo(a.w), bf16_lo(b.w), acc);
-      acc = __builtin_fmaf(bf16_hi(a.w), bf16_hi(b.w), acc);
+    const int nch = d / 8;
+    const u32x4 *xv = reinterpret_cast<const u32x4 *>(x);
+    const u32x4 *w = reinterpret_cast<const u32x4 *>(gate_w) + (size_t)row0 * nch;
+#pragma unroll 4
+    for (int c = lane; c < nch; c += kWave) {
+      const u32x4 b = xv[c];
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        // rows past the last one re-read the last row (always in bounds); their sums are discarded
+        const u32x4 a = w[(size_t)(r < nrows ? r : nrows - 1) * nch + c];
+        acc[r] = dot2(a.x, b.x, acc[r]);
+        acc[r] = dot2(a.y, b.y, acc[r]);
+        acc[r] = dot2(a.z, b.z, acc[r]);
+        acc[r] = dot2(a.w, b.w, acc[r]);
+      }
     }
   } else {
-    const float4 *w = reinterpret_cast<const float4 *>(static_cast<const float *>(gate_w) + (size_t)row * d);
+    const int nch = d / 4;
     const float4 *xv = reinterpret_cast<const float4 *>(x);
-    for (int c = lane; c < d / 4; c += kWave) {
-      float4 a = w[c], b = xv[c];
-      acc = __builtin_fmaf(a.x, b.x, acc);
-      acc = __builtin_fmaf(a.y, b.y, acc);
-      acc = __builtin_fmaf(a.z, b.z, acc);
-      acc = __builtin_fmaf(a.w, b.w, acc);
+    const float4 *w = reinterpret_cast<const float4 *>(gate_w) + (size_t)row0 * nch;
+#pragma unroll 4
+    for (int c = lane; c < nch; c += kWave) {
+      const float4 b = xv[c];
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        const float4 a = w[(size_t)(r < nrows ? r : nrows - 1) * nch + c];
+        acc[r] = __builtin_fmaf(a.x, b.x, acc[r]);
+        acc[r] = __builtin_fmaf(a.y, b.y, acc[r]);
+        acc[r] = __builtin_fmaf(a.z, b.z, acc[r]);
+        acc[r] = __builtin_fmaf(a.w, b.w, acc[r]);
+      }
     }
   }
-  return wave_sum(acc);
+#pragma unroll
+  for (int r = 0; r < R; ++r) out[r] = wave_sum(acc[r]);
 }
 
 __global__ __launch_bounds__(1024) void route_kernel(RouteParams p, const void *gate_w, const void *x,
                                                      const float *logits_in, LayerState *st,
                                                      moe_route_out_t *out_dev, moe_route_out_t *out_host) {
   __shared__ float z_s[MOE_MAX_EXPERTS];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n_waves = blockDim.x >> 6;
+  __shared__ __attribute__((aligned(16))) uint32_t rec_s[kRecWords];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), n_waves = blockDim.x >> 6;
   const int N = p.n_experts, K = p.top_k, C = p.capacity;
+
+  // wavefront 0 owns the cache state; its loads are issued before the GEMV so their latency overlaps it
+  int my_slot = -1, slot_exp = -1, t = 0;
+  int64_t stamp = 0;
+  uint64_t ever_used = 0;
+  float dsum_prev = 0.f;
+  if (wave == 0) {
+    if (lane < N) {
+      my_slot = st->expert_slot[lane];
+      stamp = st->stamp[lane];
+    }
+    if (lane < C) slot_exp = st->slot_expert[lane];
+    ever_used = st->ever_used;
+    dsum_prev = st->delta_sum;
+    t = st->count;
+  }
 
   if (logits_in != nullptr) {
     if (tid < N) z_s[tid] = logits_in[tid];
   } else {
-    for (int row = wave; row < N; row += n_waves) {
-      float v = gate_row_dot(gate_w, x, row, p.hidden, p.act_fmt, lane);
-      if (lane == 0) z_s[row] = v;
+    constexpr int R = 4;
+    const int rpw = (N + n_waves - 1) / n_waves;  // rows per wavefront (<= 4 by the launch shape)
+    for (int row0 = wave * rpw; row0 < min(N, (wave + 1) * rpw); row0 += R) {
+      float v[R];
+      const int nrows = min(R, min(N, (wave + 1) * rpw) - row0);
+      gate_rows<R>(gate_w, x, row0, nrows, p.hidden, p.act_fmt, lane, v);
+#pragma unroll
+      for (int r = 0; r < R; ++r)
+        if (lane == 0 && r < nrows) z_s[row0 + r] = v[r];
     }
   }
   __syncthreads();
@@ -116,42 +172,43 @@ __global__ __launch_bounds__(1024) void route_kernel(RouteParams p, const void *
 
   // Delta_avg (Eq. 10): cumulative mean of the logit range, current token included
   const float range = zmax - zmin;
-  const float dsum = st->delta_sum + range;
-  const int t = st->count;
+  const float dsum = dsum_prev + range;
   const int cnt = t + 1;
   const float delta = (p.delta_mode == MOE_DELTA_FIXED) ? p.delta_fixed : dsum / (float)cnt;
 
-  int my_slot = active ? st->expert_slot[lane] : -1;
   const bool resident = my_slot >= 0;
-  int64_t stamp = st->stamp[lane];
-  int slot_exp = (lane < C) ? st->slot_expert[lane] : -1;
-  uint64_t ever_used = st->ever_used;
 
-  // ranking by the router (Eq. 2), ties -> lower index
-  const int rank_z = rank_desc(z, lane, N);
-  const bool top_j = active && rank_z < p.top_j;
+  // router's own top-J (Sec. 3.3): J rounds of arg-max, ties -> lower index
+  uint64_t topj_mask = 0;
+  for (int j = 0; j < p.top_j; ++j) {
+    const bool cand = active && !((topj_mask >> lane) & 1);
+    const float m = wave_max(cand ? z : -INFINITY);
+    topj_mask |= 1ull << __builtin_ctzll(ballot(cand && z == m));
+  }
+  const bool top_j = (topj_mask >> lane) & 1;
 
-  int rank_p;      // position in the altered ranking r'
-  float zp = z;    // altered logits (Cache-Prior only)
+  int rank_p;    // position in the altered ranking r'
+  float zp = z;  // altered logits (Cache-Prior only)
   if (p.route_mode == MOE_ROUTE_CACHE_PRIOR) {
-    const float bias = p.lambda * delta;            // one rounding
+    const float bias = p.lambda * delta;               // one rounding
     if (active && (resident || top_j)) zp = z + bias;  // one rounding (Eq. 9)
-    rank_p = rank_desc(zp, lane, N);
+    rank_p = rank_of(rank_key(zp, lane, active), N);
   } else {
     // Max-Rank (Eq. 6-7) / Cumsum-Threshold (Eq. 8): two promote() passes = a three-class stable partition
+    const int rank_z = rank_of(rank_key(z, lane, active), N);
     int M = p.max_rank;
     if (p.route_mode == MOE_ROUTE_CUMSUM) {
-      // cumulative weight up to and including my rank; M = number of experts whose preceding mass < p
+      // mass ranked before me; M = number of experts whose preceding mass is still below p
       float before = 0.f;
       for (int r = 0; r < N; ++r) {
-        uint64_t m = ballot(active && rank_z == r);
-        float wr = readlane_f(w, (int)__builtin_ctzll(m));
+        const float wr = readlane_f(w, (int)__builtin_ctzll(ballot(active && rank_z == r)));
         if (rank_z > r) before += wr;
       }
       M = (int)__builtin_popcountll(ballot(active && before < p.cumsum_p));
     }
     const int cls = top_j ? 0 : ((resident && rank_z < M) ? 1 : 2);
-    rank_p = rank_asc_i(active ? cls * 64 + rank_z : 0x7fffffff, kWave);
+    const uint64_t key = active ? (((uint64_t)(2 - cls) << 32) | (uint32_t)(63 - rank_z)) : 0ull;
+    rank_p = rank_of(key, N);
   }
   const bool sel = active && rank_p < K;
   const uint64_t sel_mask = ballot(sel);
@@ -162,8 +219,8 @@ __global__ __launch_bounds__(1024) void route_kernel(RouteParams p, const void *
   // margin between the K-th and (K+1)-th altered logit (tie logging)
   float margin = INFINITY;
   if (K < N && p.route_mode == MOE_ROUTE_CACHE_PRIOR) {
-    float a = readlane_f(zp, (int)__builtin_ctzll(ballot(active && rank_p == K - 1)));
-    float b = readlane_f(zp, (int)__builtin_ctzll(ballot(active && rank_p == K)));
+    const float a = readlane_f(zp, (int)__builtin_ctzll(ballot(active && rank_p == K - 1)));
+    const float b = readlane_f(zp, (int)__builtin_ctzll(ballot(active && rank_p == K)));
     margin = a - b;
   }
 
@@ -174,9 +231,10 @@ __global__ __launch_bounds__(1024) void route_kernel(RouteParams p, const void *
   }
 
   // ---- LRU update (Sec. 4.2) ----------------------------------------------------------------
-  // touch order inside the token: descending original logit -> position pos; stamp = t*K + pos
+  // touch order inside the token: descending original logit (ties -> lower index) -> position pos
+  const uint64_t zkey = rank_key(z, lane, active);
   int pos = 0;
-  for (uint64_t m = sel_mask; m; m &= m - 1) pos += readlane_i(rank_z, (int)__builtin_ctzll(m)) < rank_z;
+  for (uint64_t m = sel_mask; m; m &= m - 1) pos += readlane_u64(zkey, (int)__builtin_ctzll(m)) > zkey;
   if (sel) stamp = (int64_t)t * K + pos;
   int ordinal = 0;  // among the misses, in touch order
   for (uint64_t m = miss_mask; m; m &= m - 1) ordinal += readlane_i(pos, (int)__builtin_ctzll(m)) < pos;
@@ -187,7 +245,8 @@ __global__ __launch_bounds__(1024) void route_kernel(RouteParams p, const void *
   const uint64_t elig_mask = ballot(eligible);
   int vrank = 0;  // eligible experts ordered by stamp, oldest first
   if (n_miss > n_empty) {
-    for (uint64_t m = elig_mask; m; m &= m - 1) vrank += readlane_i64(stamp, (int)__builtin_ctzll(m)) < stamp;
+    for (uint64_t m = elig_mask; m; m &= m - 1)
+      vrank += (int64_t)readlane_u64((uint64_t)stamp, (int)__builtin_ctzll(m)) < stamp;
   }
   int my_evicted = -1;
   int cold = 0, evictions = 0;
@@ -212,27 +271,12 @@ __global__ __launch_bounds__(1024) void route_kernel(RouteParams p, const void *
     ever_used |= 1ull << s;
   }
 
-  // ---- write the decision and the state -----------------------------------------------------
+  // ---- state back to device memory ------------------------------------------------------------
   if (active) {
     st->expert_slot[lane] = my_slot;
     st->stamp[lane] = stamp;
-    out_dev->logits[lane] = z;
-    out_host->logits[lane] = z;
   }
   if (lane < C) st->slot_expert[lane] = slot_exp;
-  if (sel) {
-    const int k = rank_p;
-    out_dev->sel_expert[k] = lane;
-    out_dev->sel_slot[k] = my_slot;
-    out_dev->sel_weight[k] = w;
-    out_dev->miss[k] = miss;
-    out_dev->evicted[k] = my_evicted;
-    out_host->sel_expert[k] = lane;
-    out_host->sel_slot[k] = my_slot;
-    out_host->sel_weight[k] = w;
-    out_host->miss[k] = miss;
-    out_host->evicted[k] = my_evicted;
-  }
   if (lane == 0) {
     st->ever_used = ever_used;
     st->delta_sum = dsum;
@@ -242,14 +286,37 @@ __global__ __launch_bounds__(1024) void route_kernel(RouteParams p, const void *
     st->misses += n_miss;
     st->cold_misses += cold;
     st->evictions += evictions;
-    out_dev->n_miss = n_miss;
-    out_dev->token = t;
-    out_dev->delta = delta;
-    out_dev->margin = margin;
-    out_host->n_miss = n_miss;
-    out_host->token = t;
-    out_host->delta = delta;
-    out_host->margin = margin;
+  }
+
+  // ---- decision record: assemble in LDS, copy out in 16-byte chunks -----------------------------
+  rec_s[lane] = 0;
+  if (lane + 64 < kRecWords) rec_s[lane + 64] = 0;
+  __builtin_amdgcn_wave_barrier();
+  if (lane < MOE_MAX_TOPK) rec_s[W_EVICT + lane] = (uint32_t)-1;
+  if (active) rec_s[W_LOGITS + lane] = __float_as_uint(z);
+  __builtin_amdgcn_wave_barrier();
+  if (sel) {
+    const int k = rank_p;
+    rec_s[W_EXPERT + k] = (uint32_t)lane;
+    rec_s[W_SLOT + k] = (uint32_t)my_slot;
+    rec_s[W_WEIGHT + k] = __float_as_uint(w);
+    rec_s[W_MISS + k] = miss ? 1u : 0u;
+    rec_s[W_EVICT + k] = (uint32_t)my_evicted;
+  }
+  if (lane == 0) {
+    rec_s[W_NMISS] = (uint32_t)n_miss;
+    rec_s[W_TOKEN] = (uint32_t)t;
+    rec_s[W_DELTA] = __float_as_uint(delta);
+    rec_s[W_MARGIN] = __float_as_uint(margin);
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  constexpr int kPayloadChunks = W_SEQ / 4;  // everything before the completion tag
+  if (lane < kPayloadChunks) {
+    const u32x4 v = reinterpret_cast<const u32x4 *>(rec_s)[lane];
+    reinterpret_cast<u32x4 *>(out_dev)[lane] = v;
+    reinterpret_cast<u32x4 *>(out_host)[lane] = v;
   }
   __threadfence_system();
   __builtin_amdgcn_wave_barrier();
@@ -286,7 +353,7 @@ __global__ void state_init_kernel(LayerState *state, int n_layers, const int32_t
 hipError_t launch_route(const RouteParams &p, const void *gate_w, const void *x, const float *logits,
                         LayerState *state, moe_route_out_t *out_dev, moe_route_out_t *out_host_mapped,
                         hipStream_t s) {
-  // enough wavefronts that every row of the gate matrix has all its loads in flight at once
+  // at most four rows of the gate matrix per wavefront, so that all of a wavefront's loads are in flight at once
   int waves = logits ? 1 : (p.n_experts + 3) / 4;
   if (waves > 16) waves = 16;
   if (waves < 1) waves = 1;
