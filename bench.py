@@ -132,6 +132,8 @@ def main():
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--cpu-tokens", type=int, default=2)
+    ap.add_argument("--no-calib-copy", action="store_true",
+                    help="skip the plain 256 MiB device copy that calibrates HBM byte counters under rocprofv3 --pmc")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; the path has no multi-GPU part (see DESIGN.md). "
@@ -165,6 +167,15 @@ def main():
     x = torch.zeros(cfg.hidden, dtype=cfg.act_dtype, device=dev)
     y = torch.zeros(cfg.hidden, dtype=cfg.act_dtype, device=dev)
     torch.cuda.synchronize()
+
+    if not args.no_calib_copy:
+        # one plain copy of known size: its FETCH_SIZE / WRITE_SIZE readings scale the counters of the other kernels
+        # (an elementwise add kernel over 32 Mi int64: reads 256 MiB, writes 256 MiB; a same-dtype copy_ would be a DMA)
+        src = torch.arange(32 << 20, dtype=torch.int64, device=dev)
+        dst = torch.empty_like(src)
+        torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- headline: lambda = 0.5 ---------------------------------------------------------------
     head = timed_run(dec, a, h, x, y, args.warmup, args.steps)
