@@ -42,7 +42,7 @@ def decode_tokens(dec, a, h, x, y, t0, t1):
                 dec.residual_rmsnorm(h, None, a[t, 0], 1.0, x, carry=False)
             else:
                 dec.residual_rmsnorm(h, y, a[t, l], PERTURB, x, carry=True)
-            dec.route_step(l, x=x)
+            dec.route_step(l, x=x, wait=False)
             dec.expert_forward(l, x, y)
 
 

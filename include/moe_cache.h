@@ -128,16 +128,24 @@ void moe_cache_destroy(moe_cache_t *ctx);
 
 /* Routing step of one layer for one token (Eq. 3, Eq. 9-10, Eq. 4, Sec. 4.2): exactly one of x_dev
  * (device [d], act_fmt: the router GEMV is computed) and logits_dev (device [N] fp32: used as z) is
- * non-NULL.  On return the decision is known on the host, written to *out_host if non-NULL, and the
- * copies filling missed experts' slots are enqueued on copy_stream.  MOE_ESTATE if the layer's
- * previous step has not been followed by moe_expert_forward. */
+ * non-NULL; the buffer must stay unchanged until the layer's moe_expert_forward has been called.
+ * With out_host non-NULL the call returns once the decision is known on the host (written to *out_host)
+ * and the copies filling missed experts' slots are enqueued on copy_stream.  With out_host NULL the call
+ * only enqueues the router kernel; the decision is collected, and the fills enqueued, inside
+ * moe_expert_forward.  MOE_ESTATE if the layer's previous step has not been followed by moe_expert_forward. */
 int moe_route_step(moe_cache_t *ctx, int32_t layer, const void *x_dev, const float *logits_dev,
                    moe_route_out_t *out_host);
 
-/* Eq. 1 for the layer's last routing step: y = sum_k w_k E_k(x) + shared(x); x_dev, y_dev device [d]
- * in act_fmt.  Asynchronous on compute_stream (which first waits for the step's miss fills).
- * MOE_ESTATE without a preceding moe_route_step. */
+/* Eq. 1 for the layer's last routing step: y = sum_k w_k E_k(x) + shared(x); x_dev (the vector given to
+ * moe_route_step), y_dev device [d] in act_fmt.  The kernels are asynchronous on compute_stream: a first
+ * launch covers the shared expert and the experts that were resident, a second one (after the fills) the
+ * experts that were missing.  The call returns once the routing decision has reached the host (it is needed
+ * to enqueue the fills), not when y is ready.  MOE_ESTATE without a preceding moe_route_step. */
 int moe_expert_forward(moe_cache_t *ctx, int32_t layer, const void *x_dev, void *y_dev);
+
+/* The last routing decision of a layer that has reached the host (after a blocking moe_route_step, or after
+ * the moe_expert_forward that followed a non-blocking one).  MOE_ESTATE if a decision is still pending. */
+int moe_cache_last_route(moe_cache_t *ctx, int32_t layer, moe_route_out_t *out_host);
 
 /* Counters of one layer, or summed over layers with layer = -1 (Eq. 4 numerators/denominators).
  * Synchronises compute_stream. */
@@ -157,8 +165,9 @@ int moe_cache_reset(moe_cache_t *ctx);
 int moe_residual_rmsnorm(float *h_dev, const void *y_dev, const float *a_dev, float perturb, int32_t carry,
                          void *x_dev, int32_t hidden, int32_t act_fmt, void *stream);
 
-/* Average duration in microseconds of the expert-GEMV kernel launches since the last call with
- * reset != 0 (measured with events on compute_stream when profiling is on), and their count. */
+/* Average duration in microseconds of the expert-GEMV launches that covered a whole layer (no expert missing)
+ * since the last call with reset != 0, and their count; measured with start/stop events attached to the
+ * launches on compute_stream while profiling is enabled. */
 int moe_cache_profile(moe_cache_t *ctx, int32_t enable, int32_t reset, double *avg_us, int64_t *launches);
 
 const char *moe_last_error(void);

@@ -108,6 +108,8 @@ lib.moe_route_step.restype = C.c_int
 lib.moe_route_step.argtypes = [_vp, C.c_int32, _vp, _vp, C.POINTER(moe_route_out_t)]
 lib.moe_expert_forward.restype = C.c_int
 lib.moe_expert_forward.argtypes = [_vp, C.c_int32, _vp, _vp]
+lib.moe_cache_last_route.restype = C.c_int
+lib.moe_cache_last_route.argtypes = [_vp, C.c_int32, C.POINTER(moe_route_out_t)]
 lib.moe_cache_stats.restype = C.c_int
 lib.moe_cache_stats.argtypes = [_vp, C.c_int32, C.POINTER(moe_cache_stats_t)]
 lib.moe_cache_tables.restype = C.c_int
@@ -127,7 +129,7 @@ lib.moe_last_error.argtypes = []
 
 EXPORTS = [
     "moe_blob_bytes", "moe_pack_expert", "moe_cache_init", "moe_cache_destroy", "moe_route_step",
-    "moe_expert_forward", "moe_cache_stats", "moe_cache_tables", "moe_cache_set_lambda",
+    "moe_expert_forward", "moe_cache_last_route", "moe_cache_stats", "moe_cache_tables", "moe_cache_set_lambda",
     "moe_cache_set_baseline", "moe_cache_reset", "moe_residual_rmsnorm", "moe_cache_profile", "moe_last_error",
 ]
 
@@ -166,7 +168,11 @@ def moe_cache_destroy(ctx) -> None:
     lib.moe_cache_destroy(ctx)
 
 
-def moe_route_step(ctx, layer: int, x_dev, logits_dev, out: moe_route_out_t | None = None) -> moe_route_out_t:
+def moe_route_step(ctx, layer: int, x_dev, logits_dev, out: moe_route_out_t | None = None, wait: bool = True):
+    """wait=True: returns the decision (blocking until the host has it); wait=False: enqueue only, returns None."""
+    if not wait:
+        _check(lib.moe_route_step(ctx, layer, x_dev, logits_dev, None), "moe_route_step")
+        return None
     out = moe_route_out_t() if out is None else out
     _check(lib.moe_route_step(ctx, layer, x_dev, logits_dev, C.byref(out)), "moe_route_step")
     return out
@@ -174,6 +180,12 @@ def moe_route_step(ctx, layer: int, x_dev, logits_dev, out: moe_route_out_t | No
 
 def moe_expert_forward(ctx, layer: int, x_dev, y_dev) -> None:
     _check(lib.moe_expert_forward(ctx, layer, x_dev, y_dev), "moe_expert_forward")
+
+
+def moe_cache_last_route(ctx, layer: int) -> moe_route_out_t:
+    out = moe_route_out_t()
+    _check(lib.moe_cache_last_route(ctx, layer, C.byref(out)), "moe_cache_last_route")
+    return out
 
 
 def moe_cache_stats(ctx, layer: int = -1) -> moe_cache_stats_t:

@@ -33,12 +33,13 @@ struct RouteParams {
 struct GemvParams {
   const uint8_t *slot_pool;      // this layer's slots
   const uint8_t *shared_blob;    // or nullptr
-  int64_t seg_off[MOE_MAX_TOPK];  // byte offset of each selected expert's slot in the pool
-  float seg_w[MOE_MAX_TOPK];      // its routing weight (known on the host after the route step)
+  const moe_route_out_t *route;  // device record of the layer's routing step (slots, weights, miss flags)
   const void *x;                 // [d] act_fmt
   float *partial;                // [grid][d] fp32
   int32_t hidden, inter, shared_inter, top_k, act_fmt;
   int64_t slot_bytes;
+  int32_t pass;        // 0: shared expert + experts that were resident; 1: experts whose slot was just filled
+  int32_t row_offset;  // first partial row this launch writes
 };
 
 // Blob geometry (see moe_blob_bytes).

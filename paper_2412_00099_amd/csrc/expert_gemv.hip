@@ -125,25 +125,15 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_kernel(GemvParams p) {
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform: keeps record addressing scalar
-  const int d = p.hidden, I = p.inter, K = p.top_k;
+  const int d = p.hidden;
   const int64_t row16 = (int64_t)d / VEC;  // 16-byte chunks per row
   const int64_t rec_bytes = 3 * row16 * 16;
-  const int routed = K * I;
-  const int total = routed + p.shared_inter;
-  const int r0 = (int)((int64_t)blockIdx.x * total / gridDim.x);
-  const int r1 = (int)((int64_t)(blockIdx.x + 1) * total / gridDim.x);
-
-  // this wavefront's records: first + j*NW, j = 0 .. n-1, walked as (segment, row) without divisions:
-  // segments 0..K-1 are the selected slots (I rows each), segment K is the shared expert
-  const int first = r0 + wave;
-  const int n = first < r1 ? (r1 - first + NW - 1) / NW : 0;
-  int seg = first < routed ? first / I : K;
-  int row = first < routed ? first - seg * I : first - routed;
+  RecordWalker<NW> walk;
+  walk.init(p, wave);
 
   auto issue = [&](RecRegs<LPR> &R) {
-    const uint8_t *base = seg < K ? p.slot_pool + p.seg_off[seg] : p.shared_blob;
-    R.wt = seg < K ? p.seg_w[seg] : 1.f;
-    const u32x4 *q = reinterpret_cast<const u32x4 *>(base + (int64_t)row * rec_bytes) + lane;
+    R.wt = walk.wt;
+    const u32x4 *q = reinterpret_cast<const u32x4 *>(walk.base + (int64_t)walk.at * rec_bytes) + lane;
 #pragma unroll
     for (int c = 0; c < LPR; ++c) R.g[c] = stream_load(q + c * kWave);
     q += row16;
@@ -152,18 +142,15 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_kernel(GemvParams p) {
     q += row16;
 #pragma unroll
     for (int c = 0; c < LPR; ++c) R.dn[c] = stream_load(q + c * kWave);
-    // advance to this wavefront's next record
-    row += NW;
-    while (seg < K && row >= I) {
-      row -= I;
-      ++seg;
-    }
   };
 
   RecRegs<LPR> ring[DEPTH];
+  bool live[DEPTH];
 #pragma unroll
-  for (int j = 0; j < DEPTH; ++j)
-    if (j < n) issue(ring[j]);  // weights first: they do not depend on x
+  for (int j = 0; j < DEPTH; ++j) {
+    live[j] = walk.next(p);
+    if (live[j]) issue(ring[j]);  // weights first: they do not depend on x
+  }
 
   // activations: the lane keeps the x entries of its own columns in registers
   float xr[LPR * XW];
@@ -188,17 +175,19 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_kernel(GemvParams p) {
     for (int c = 0; c < LPR; ++c) F::axpy(h, R.dn[c], &y[c * VEC]);
   };
 
-  for (int k = 0; k < n; k += DEPTH) {
+  // ring[0] is always the oldest record in flight: when it is dead, all are
+  while (live[0]) {
 #pragma unroll
     for (int j = 0; j < DEPTH; ++j) {
-      if (k + j < n) {
+      if (live[j]) {
         consume(ring[j]);
-        if (k + j + DEPTH < n) issue(ring[j]);
+        live[j] = walk.next(p);
+        if (live[j]) issue(ring[j]);
       }
     }
   }
 
-  reduce_and_store<NW, VEC, LPR>(y, red, p.partial + (int64_t)blockIdx.x * d, tid, lane, wave);
+  reduce_and_store<NW, VEC, LPR>(y, red, p.partial + (int64_t)(p.row_offset + blockIdx.x) * d, tid, lane, wave);
 }
 
 // y[j] = sum over partial rows in index order, rounded to the activation type.

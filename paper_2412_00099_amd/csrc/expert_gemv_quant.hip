@@ -53,7 +53,8 @@ template <int LPR>
 struct RecI8 {
   u32x4 g[LPR], u[LPR], dn[LPR];
   float sg, su, wt;
-  int seg;
+  const uint8_t *base;  // blob of the record's expert (its tail holds the down scales)
+  int rows;
 };
 
 template <int LPR, int NW, int DEPTH>
@@ -62,27 +63,18 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int8_kernel(GemvParams 
   __shared__ float red[kRedFloats];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int d = p.hidden, I = p.inter, K = p.top_k;
+  const int d = p.hidden;
   const int64_t row16 = d / VEC;
   const int64_t rec_bytes = 3 * row16 * 16;
-  const int routed = K * I;
-  const int total = routed + p.shared_inter;
-  const int r0 = (int)((int64_t)blockIdx.x * total / gridDim.x);
-  const int r1 = (int)((int64_t)(blockIdx.x + 1) * total / gridDim.x);
-  const int first = r0 + wave;
-  const int n = first < r1 ? (r1 - first + NW - 1) / NW : 0;
-  int seg = first < routed ? first / I : K;
-  int row = first < routed ? first - seg * I : first - routed;
-
-  auto seg_base = [&](int s) -> const uint8_t * { return s < K ? p.slot_pool + p.seg_off[s] : p.shared_blob; };
-  auto seg_rows = [&](int s) -> int { return s < K ? I : p.shared_inter; };
+  RecordWalker<NW> walk;
+  walk.init(p, wave);
 
   auto issue = [&](RecI8<LPR> &R) {
-    const uint8_t *base = seg_base(seg);
-    const uint16_t *tail = reinterpret_cast<const uint16_t *>(base + (int64_t)seg_rows(seg) * rec_bytes);
-    R.wt = seg < K ? p.seg_w[seg] : 1.f;
-    R.seg = seg;
-    const u32x4 *q = reinterpret_cast<const u32x4 *>(base + (int64_t)row * rec_bytes) + lane;
+    const uint16_t *tail = reinterpret_cast<const uint16_t *>(walk.base + (int64_t)walk.rows * rec_bytes);
+    R.wt = walk.wt;
+    R.base = walk.base;
+    R.rows = walk.rows;
+    const u32x4 *q = reinterpret_cast<const u32x4 *>(walk.base + (int64_t)walk.at * rec_bytes) + lane;
 #pragma unroll
     for (int c = 0; c < LPR; ++c) R.g[c] = stream_load(q + c * kWave);
     q += row16;
@@ -91,19 +83,17 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int8_kernel(GemvParams 
     q += row16;
 #pragma unroll
     for (int c = 0; c < LPR; ++c) R.dn[c] = stream_load(q + c * kWave);
-    R.sg = f16_bits(tail[row]);                 // gate scales [rows]
-    R.su = f16_bits(tail[seg_rows(seg) + row]);  // up scales [rows]
-    row += NW;
-    while (seg < K && row >= I) {
-      row -= I;
-      ++seg;
-    }
+    R.sg = f16_bits(tail[walk.at]);              // gate scales [rows]
+    R.su = f16_bits(tail[walk.rows + walk.at]);  // up scales [rows]
   };
 
   RecI8<LPR> ring[DEPTH];
+  bool live[DEPTH];
 #pragma unroll
-  for (int j = 0; j < DEPTH; ++j)
-    if (j < n) issue(ring[j]);
+  for (int j = 0; j < DEPTH; ++j) {
+    live[j] = walk.next(p);
+    if (live[j]) issue(ring[j]);
+  }
 
   // activations as packed fp16 pairs in column order, and their sum over this lane's columns
   uint32_t xh[CPL / 2];
@@ -123,12 +113,12 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int8_kernel(GemvParams 
 #pragma unroll
   for (int j = 0; j < CPL; ++j) y[j] = acc[j] = 0.f;
   float hsum = 0.f;
-  int cur_seg = -1;
+  const uint8_t *cur_base = nullptr;
+  int cur_rows = 0;
 
-  // y += scale_col * (acc - 128*hsum) with the per-column scales of expert `s`
-  auto flush = [&](int s) {
-    const uint16_t *sd = reinterpret_cast<const uint16_t *>(seg_base(s) + (int64_t)seg_rows(s) * rec_bytes) +
-                         2 * seg_rows(s);
+  // y += scale_col * (acc - 128*hsum) with the per-column scales of the expert whose blob is `base`
+  auto flush = [&](const uint8_t *base, int rows) {
+    const uint16_t *sd = reinterpret_cast<const uint16_t *>(base + (int64_t)rows * rec_bytes) + 2 * rows;
     const float off = 128.f * hsum;
 #pragma unroll
     for (int c = 0; c < LPR; ++c) {
@@ -147,9 +137,10 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int8_kernel(GemvParams 
   };
 
   auto consume = [&](const RecI8<LPR> &R) {
-    if (R.seg != cur_seg) {
-      if (cur_seg >= 0) flush(cur_seg);
-      cur_seg = R.seg;
+    if (R.base != cur_base) {
+      if (cur_base) flush(cur_base, cur_rows);
+      cur_base = R.base;
+      cur_rows = R.rows;
     }
     float g0 = 0.f, g1 = 0.f, u0 = 0.f, u1 = 0.f;
 #pragma unroll
@@ -189,17 +180,18 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int8_kernel(GemvParams 
     }
   };
 
-  for (int k = 0; k < n; k += DEPTH) {
+  while (live[0]) {
 #pragma unroll
     for (int j = 0; j < DEPTH; ++j) {
-      if (k + j < n) {
+      if (live[j]) {
         consume(ring[j]);
-        if (k + j + DEPTH < n) issue(ring[j]);
+        live[j] = walk.next(p);
+        if (live[j]) issue(ring[j]);
       }
     }
   }
-  if (cur_seg >= 0) flush(cur_seg);
-  reduce_and_store<NW, VEC, LPR>(y, red, p.partial + (int64_t)blockIdx.x * d, tid, lane, wave);
+  if (cur_base) flush(cur_base, cur_rows);
+  reduce_and_store<NW, VEC, LPR>(y, red, p.partial + (int64_t)(p.row_offset + blockIdx.x) * d, tid, lane, wave);
 }
 
 // =================================================================================================
@@ -210,7 +202,8 @@ struct RecI4 {
   u32x4 g[LPR], u[LPR], dn[LPR];
   uint32_t sc[LPR];  // (gate scale, up scale) fp16 pair of this lane's group, per chunk
   float wt;
-  int seg, grp;
+  const uint8_t *base;  // blob of the record's expert (its tail holds the down scales)
+  int rows, grp;
 };
 
 template <int LPR, int NW, int DEPTH>
@@ -219,26 +212,18 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int4_kernel(GemvParams 
   __shared__ float red[kRedFloats];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int d = p.hidden, I = p.inter, K = p.top_k;
-  const int64_t row16 = d / VEC;                          // 16-byte chunks per row of nibbles
+  const int d = p.hidden;
+  const int64_t row16 = d / VEC;                             // 16-byte chunks per row of nibbles
   const int64_t rec_bytes = 3 * row16 * 16 + (d / 128) * 4;  // three rows + (gate, up) scale pairs
-  const int routed = K * I;
-  const int total = routed + p.shared_inter;
-  const int r0 = (int)((int64_t)blockIdx.x * total / gridDim.x);
-  const int r1 = (int)((int64_t)(blockIdx.x + 1) * total / gridDim.x);
-  const int first = r0 + wave;
-  const int n = first < r1 ? (r1 - first + NW - 1) / NW : 0;
-  int seg = first < routed ? first / I : K;
-  int row = first < routed ? first - seg * I : first - routed;
-
-  auto seg_base = [&](int s) -> const uint8_t * { return s < K ? p.slot_pool + p.seg_off[s] : p.shared_blob; };
-  auto seg_rows = [&](int s) -> int { return s < K ? I : p.shared_inter; };
+  RecordWalker<NW> walk;
+  walk.init(p, wave);
 
   auto issue = [&](RecI4<LPR> &R) {
-    const uint8_t *rec = seg_base(seg) + (int64_t)row * rec_bytes;
-    R.wt = seg < K ? p.seg_w[seg] : 1.f;
-    R.seg = seg;
-    R.grp = row >> 7;
+    const uint8_t *rec = walk.base + (int64_t)walk.at * rec_bytes;
+    R.wt = walk.wt;
+    R.base = walk.base;
+    R.rows = walk.rows;
+    R.grp = walk.at >> 7;
     const u32x4 *q = reinterpret_cast<const u32x4 *>(rec) + lane;
 #pragma unroll
     for (int c = 0; c < LPR; ++c) R.g[c] = stream_load(q + c * kWave);
@@ -251,17 +236,15 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int4_kernel(GemvParams 
     const uint32_t *sc = reinterpret_cast<const uint32_t *>(rec + 3 * row16 * 16);
 #pragma unroll
     for (int c = 0; c < LPR; ++c) R.sc[c] = sc[(c * kWave + lane) >> 2];  // 4 lanes (128 columns) per group
-    row += NW;
-    while (seg < K && row >= I) {
-      row -= I;
-      ++seg;
-    }
   };
 
   RecI4<LPR> ring[DEPTH];
+  bool live[DEPTH];
 #pragma unroll
-  for (int j = 0; j < DEPTH; ++j)
-    if (j < n) issue(ring[j]);
+  for (int j = 0; j < DEPTH; ++j) {
+    live[j] = walk.next(p);
+    if (live[j]) issue(ring[j]);
+  }
 
   // activations as packed bf16 pairs (column t, column t+4) per dword of 8 nibbles, and per-chunk sums
   uint32_t xp[CPL / 2];
@@ -286,12 +269,12 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int4_kernel(GemvParams 
 #pragma unroll
   for (int j = 0; j < CPL; ++j) y[j] = acc[j] = 0.f;
   float hsum = 0.f;
-  int cur_seg = -1, cur_grp = -1;
+  const uint8_t *cur_base = nullptr;
+  int cur_rows = 0, cur_grp = -1;
 
   // y += scale[group][col] * (acc - 1032*hsum)
-  auto flush = [&](int s, int grp) {
-    const uint16_t *sd = reinterpret_cast<const uint16_t *>(seg_base(s) + (int64_t)seg_rows(s) * rec_bytes) +
-                         (int64_t)grp * d;
+  auto flush = [&](const uint8_t *base, int rows, int grp) {
+    const uint16_t *sd = reinterpret_cast<const uint16_t *>(base + (int64_t)rows * rec_bytes) + (int64_t)grp * d;
     const float off = (1024.f + 8.f) * hsum;
 #pragma unroll
     for (int c = 0; c < LPR; ++c) {
@@ -313,9 +296,10 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int4_kernel(GemvParams 
   };
 
   auto consume = [&](const RecI4<LPR> &R) {
-    if (R.seg != cur_seg || R.grp != cur_grp) {
-      if (cur_seg >= 0) flush(cur_seg, cur_grp);
-      cur_seg = R.seg;
+    if (R.base != cur_base || R.grp != cur_grp) {
+      if (cur_base) flush(cur_base, cur_rows, cur_grp);
+      cur_base = R.base;
+      cur_rows = R.rows;
       cur_grp = R.grp;
     }
     float g = 0.f, u = 0.f;
@@ -359,17 +343,18 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int4_kernel(GemvParams 
     }
   };
 
-  for (int k = 0; k < n; k += DEPTH) {
+  while (live[0]) {
 #pragma unroll
     for (int j = 0; j < DEPTH; ++j) {
-      if (k + j < n) {
+      if (live[j]) {
         consume(ring[j]);
-        if (k + j + DEPTH < n) issue(ring[j]);
+        live[j] = walk.next(p);
+        if (live[j]) issue(ring[j]);
       }
     }
   }
-  if (cur_seg >= 0) flush(cur_seg, cur_grp);
-  reduce_and_store<NW, VEC, LPR>(y, red, p.partial + (int64_t)blockIdx.x * d, tid, lane, wave);
+  if (cur_base) flush(cur_base, cur_rows, cur_grp);
+  reduce_and_store<NW, VEC, LPR>(y, red, p.partial + (int64_t)(p.row_offset + blockIdx.x) * d, tid, lane, wave);
 }
 
 }  // namespace

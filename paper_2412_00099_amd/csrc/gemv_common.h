@@ -41,6 +41,92 @@ __device__ __forceinline__ void wave_sum2(float &a, float &b) {
 }
 
 
+// Walks the records one wavefront owns in one launch.
+//
+// The launch's work list is, per workgroup, its even share of the shared expert's records followed by its
+// even share of the routed records (the K selected slots side by side, I records each); the wavefronts of the
+// workgroup take list entries wave, wave+NW, ...  Shared records need nothing from the routing step, so a
+// workgroup starts streaming them at once while the loads of the routing record (slots, weights, miss flags)
+// are still in flight.  Pass 0 covers the shared expert and the experts that were resident; pass 1 covers
+// only the experts whose slots were filled for this token, so the first pass can run while the fills stream.
+template <int NW>
+struct RecordWalker {
+  int idx, ns, nl, s0, q0;
+  int seg, row;  // position in the routed part (seg < 0: not entered yet)
+  // routing record entries of segment `have` (current) and `have + 1` (prefetched)
+  int have, slot_c, miss_c, slot_n, miss_n;
+  float w_c, w_n;
+  // the record found by next()
+  const uint8_t *base;  // blob of the record's expert
+  int rows, at;
+  float wt;
+
+  __device__ __forceinline__ void fetch(const GemvParams &p, int k, int &slot, int &miss, float &w) {
+    const int kk = k < p.top_k ? k : p.top_k - 1;  // always a valid entry; values past the end are never used
+    slot = p.route->sel_slot[kk];
+    miss = p.route->miss[kk];
+    w = p.route->sel_weight[kk];
+  }
+
+  __device__ __forceinline__ void init(const GemvParams &p, int wave) {
+    const int G = gridDim.x, b = blockIdx.x;
+    const int routed = p.top_k * p.inter;
+    s0 = p.pass == 0 ? (int)((int64_t)b * p.shared_inter / G) : 0;
+    const int s1 = p.pass == 0 ? (int)((int64_t)(b + 1) * p.shared_inter / G) : 0;
+    q0 = (int)((int64_t)b * routed / G);
+    const int q1 = (int)((int64_t)(b + 1) * routed / G);
+    ns = s1 - s0;
+    nl = ns + (q1 - q0);
+    idx = wave;
+    seg = -1;
+    row = 0;
+    // issued now, first needed when the routed part begins
+    have = q0 / p.inter;
+    fetch(p, have, slot_c, miss_c, w_c);
+    fetch(p, have + 1, slot_n, miss_n, w_n);
+  }
+
+  // advance to this wavefront's next record of the pass; false when the list is exhausted
+  __device__ __forceinline__ bool next(const GemvParams &p) {
+    const int I = p.inter, K = p.top_k;
+    while (idx < nl) {
+      if (idx < ns) {
+        base = p.shared_blob;
+        rows = p.shared_inter;
+        at = s0 + idx;
+        wt = 1.f;
+        idx += NW;
+        return true;
+      }
+      if (seg < 0) {
+        const int r = q0 + (idx - ns);
+        seg = r / I;
+        row = r - seg * I;
+      }
+      while (have < seg) {  // entered a new segment: the prefetched entries become current
+        ++have;
+        slot_c = slot_n;
+        miss_c = miss_n;
+        w_c = w_n;
+        fetch(p, have + 1, slot_n, miss_n, w_n);
+      }
+      const bool wanted = (miss_c != 0) == (p.pass == 1);
+      base = p.slot_pool + (int64_t)slot_c * p.slot_bytes;
+      rows = I;
+      at = row;
+      wt = w_c;
+      idx += NW;
+      row += NW;
+      while (row >= I && seg < K) {
+        row -= I;
+        ++seg;
+      }
+      if (wanted) return true;
+    }
+    return false;
+  }
+};
+
 // Sum the wavefronts' private outputs through LDS (one barrier per pass) and write the workgroup's fp32
 // partial row.  y holds, for load index c and v < VEC, column (c*64 + lane)*VEC + v at y[c*VEC + v].
 // Slot (cv*64 + lane) of a wavefront's LDS row holds 4 columns with cv = c_in_pass*(VEC/4) + v4, so

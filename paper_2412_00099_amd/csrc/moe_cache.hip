@@ -59,8 +59,8 @@ struct moe_cache {
   GemvPlan plan{};
   hipEvent_t ev_route = nullptr;
   std::vector<hipEvent_t> ev_copy;
-  std::vector<uint8_t> routed;        // per layer: a route step awaits its expert_forward
-  std::vector<uint8_t> copy_pending;  // per layer: fills were enqueued for the pending step
+  std::vector<uint8_t> routed;        // per layer: 0 idle, 1 routed (decision on the host), 2 routed (not collected yet)
+  std::vector<uint32_t> route_seq;    // per layer: completion tag of the pending route step
   std::vector<int64_t> bytes_filled;
   uint32_t seq = 0;
   bool poll = false;
@@ -68,6 +68,7 @@ struct moe_cache {
   // optional timing of the expert GEMV launches
   bool profiling = false;
   std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_events;
+  std::vector<uint8_t> prof_full;  // launch covered the whole layer (no expert was missing)
   size_t prof_used = 0;
 };
 
@@ -93,7 +94,6 @@ int do_reset(moe_cache_t *c) {
                         c->host_blob[(size_t)l * N + e], c->slot_layout.total, hipMemcpyHostToDevice));
     }
     c->routed[l] = 0;
-    c->copy_pending[l] = 0;
     c->bytes_filled[l] = 0;
   }
   HIP_TRY(hipStreamSynchronize(c->compute));
@@ -187,7 +187,7 @@ int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, 
   c->compute = static_cast<hipStream_t>(cfg->compute_stream);
   c->copy = static_cast<hipStream_t>(cfg->copy_stream);
   c->routed.assign(L, 0);
-  c->copy_pending.assign(L, 0);
+  c->route_seq.assign(L, 0);
   c->bytes_filled.assign(L, 0);
   c->ev_copy.assign(L, nullptr);
 
@@ -222,7 +222,7 @@ int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, 
   memset(c->h_route, 0, sizeof(moe_route_out_t) * L);
   HIP_INIT(hipHostGetDevicePointer(reinterpret_cast<void **>(&c->h_route_dev), c->h_route, 0));
   HIP_INIT(hipMalloc(&c->d_initial, sizeof(int32_t) * (size_t)L * (b->n_initial > 0 ? b->n_initial : 1)));
-  HIP_INIT(hipMalloc(&c->d_partial, sizeof(float) * (size_t)c->plan.grid * cfg->hidden));
+  HIP_INIT(hipMalloc(&c->d_partial, sizeof(float) * 2 * (size_t)c->plan.grid * cfg->hidden));
   HIP_INIT(hipEventCreateWithFlags(&c->ev_route, hipEventDisableTiming));
   for (int l = 0; l < L; ++l) HIP_INIT(hipEventCreateWithFlags(&c->ev_copy[l], hipEventDisableTiming));
 #undef HIP_INIT
@@ -251,6 +251,48 @@ void moe_cache_destroy(moe_cache_t *c) {
   delete c;
 }
 
+// Wait until the routing decision of `layer` (tag `seq`) is visible on the host, then enqueue the fills of the
+// missed experts on the copy stream.  Returns the number of misses through *n_miss.
+static int collect_route(moe_cache_t *c, int32_t layer, uint32_t seq, int *n_miss) {
+  const moe_cache_config_t &g = c->cfg;
+  moe_route_out_t *h = c->h_route + layer;
+  bool seen = false;
+  if (c->poll) {
+    // the kernel stores the record to mapped host memory and then the tag, with a system-scope release
+    const auto t0 = std::chrono::steady_clock::now();
+    volatile uint32_t *tag = &h->seq;
+    for (uint32_t spin = 0;; ++spin) {
+      if (__atomic_load_n(tag, __ATOMIC_ACQUIRE) == seq) {
+        seen = true;
+        break;
+      }
+      if ((spin & 0x3ff) == 0x3ff && std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(200))
+        break;  // fall back to a stream synchronisation (also surfaces launch errors)
+    }
+  }
+  if (!seen) {
+    HIP_TRY(hipEventRecord(c->ev_route, c->compute));
+    HIP_TRY(hipEventSynchronize(c->ev_route));
+    if (h->seq != seq) return fail(MOE_EHIP, "route kernel of layer %d did not publish its result", layer);
+  }
+  const size_t slot_bytes = (size_t)c->slot_layout.total;
+  if (h->n_miss > 0) {
+    for (int k = 0; k < g.top_k; ++k) {
+      if (!h->miss[k]) continue;
+      const int e = h->sel_expert[k], s = h->sel_slot[k];
+      if (e < 0 || e >= g.n_experts || s < 0 || s >= g.capacity)
+        return fail(MOE_EHIP, "route kernel returned expert %d slot %d out of range", e, s);
+      HIP_TRY(hipMemcpyAsync(static_cast<uint8_t *>(c->slot_pool[layer]) + (size_t)s * slot_bytes,
+                             c->host_blob[(size_t)layer * g.n_experts + e], slot_bytes, hipMemcpyHostToDevice,
+                             c->copy));
+      c->bytes_filled[layer] += (int64_t)slot_bytes;
+    }
+    HIP_TRY(hipEventRecord(c->ev_copy[layer], c->copy));
+  }
+  *n_miss = h->n_miss;
+  return MOE_OK;
+}
+
 int moe_route_step(moe_cache_t *c, int32_t layer, const void *x_dev, const float *logits_dev,
                    moe_route_out_t *out_host) {
   if (int rc = check_layer(c, layer)) return rc;
@@ -273,46 +315,17 @@ int moe_route_step(moe_cache_t *c, int32_t layer, const void *x_dev, const float
   p.cumsum_p = g.cumsum_p;
   if (++c->seq == 0) c->seq = 1;
   p.seq = c->seq;
-  moe_route_out_t *h = c->h_route + layer;
   HIP_TRY(launch_route(p, c->gate_w[layer], x_dev, logits_dev, c->d_state + layer, c->d_route + layer,
                        c->h_route_dev + layer, c->compute));
-  bool seen = false;
-  if (c->poll) {
-    // the kernel stores the record to mapped host memory and then the tag, with a system-scope release
-    const auto t0 = std::chrono::steady_clock::now();
-    volatile uint32_t *tag = &h->seq;
-    for (uint32_t spin = 0;; ++spin) {
-      if (__atomic_load_n(tag, __ATOMIC_ACQUIRE) == p.seq) {
-        seen = true;
-        break;
-      }
-      if ((spin & 0x3ff) == 0x3ff &&
-          std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(200))
-        break;  // fall back to a stream synchronisation (also surfaces launch errors)
-    }
+  c->route_seq[layer] = p.seq;
+  if (!out_host) {
+    c->routed[layer] = 2;  // decision collected by moe_expert_forward, behind the first expert launch
+    return MOE_OK;
   }
-  if (!seen) {
-    HIP_TRY(hipEventRecord(c->ev_route, c->compute));
-    HIP_TRY(hipEventSynchronize(c->ev_route));
-    if (h->seq != p.seq) return fail(MOE_EHIP, "route kernel of layer %d did not publish its result", layer);
-  }
-  const size_t slot_bytes = (size_t)c->slot_layout.total;
-  if (h->n_miss > 0) {
-    for (int k = 0; k < g.top_k; ++k) {
-      if (!h->miss[k]) continue;
-      const int e = h->sel_expert[k], s = h->sel_slot[k];
-      if (e < 0 || e >= g.n_experts || s < 0 || s >= g.capacity)
-        return fail(MOE_EHIP, "route kernel returned expert %d slot %d out of range", e, s);
-      HIP_TRY(hipMemcpyAsync(static_cast<uint8_t *>(c->slot_pool[layer]) + (size_t)s * slot_bytes,
-                             c->host_blob[(size_t)layer * g.n_experts + e], slot_bytes, hipMemcpyHostToDevice,
-                             c->copy));
-      c->bytes_filled[layer] += (int64_t)slot_bytes;
-    }
-    HIP_TRY(hipEventRecord(c->ev_copy[layer], c->copy));
-    c->copy_pending[layer] = 1;
-  }
+  int n_miss = 0;
+  if (int rc = collect_route(c, layer, p.seq, &n_miss)) return rc;
   c->routed[layer] = 1;
-  if (out_host) *out_host = *h;
+  *out_host = c->h_route[layer];
   return MOE_OK;
 }
 
@@ -321,17 +334,10 @@ int moe_expert_forward(moe_cache_t *c, int32_t layer, const void *x_dev, void *y
   if (!x_dev || !y_dev) return fail(MOE_EINVAL, "x_dev or y_dev is NULL");
   if (!c->routed[layer]) return fail(MOE_ESTATE, "layer %d: moe_expert_forward without a preceding moe_route_step", layer);
   const moe_cache_config_t &g = c->cfg;
-  if (c->copy_pending[layer]) {
-    HIP_TRY(hipStreamWaitEvent(c->compute, c->ev_copy[layer], 0));
-    c->copy_pending[layer] = 0;
-  }
   GemvParams p{};
   p.slot_pool = static_cast<const uint8_t *>(c->slot_pool[layer]);
   p.shared_blob = g.shared_inter > 0 ? static_cast<const uint8_t *>(c->shared_blob[layer]) : nullptr;
-  for (int k = 0; k < g.top_k; ++k) {
-    p.seg_off[k] = (int64_t)c->h_route[layer].sel_slot[k] * c->slot_layout.total;
-    p.seg_w[k] = c->h_route[layer].sel_weight[k];
-  }
+  p.route = c->d_route + layer;
   p.x = x_dev;
   p.partial = c->d_partial;
   p.hidden = g.hidden;
@@ -340,6 +346,10 @@ int moe_expert_forward(moe_cache_t *c, int32_t layer, const void *x_dev, void *y
   p.top_k = g.top_k;
   p.act_fmt = g.act_fmt;
   p.slot_bytes = c->slot_layout.total;
+  // pass 0: the shared expert and the experts that were resident; it reads slots, weights and miss flags from
+  // the device record, so it is launched before the host knows the decision
+  p.pass = 0;
+  p.row_offset = 0;
   const bool prof = c->profiling && c->prof_used < (1u << 16);
   if (prof) {
     if (c->prof_used == c->prof_events.size()) {
@@ -347,15 +357,37 @@ int moe_expert_forward(moe_cache_t *c, int32_t layer, const void *x_dev, void *y
       HIP_TRY(hipEventCreate(&a));
       HIP_TRY(hipEventCreate(&b));
       c->prof_events.emplace_back(a, b);
+      c->prof_full.push_back(0);
     }
     HIP_TRY(launch_expert_gemv(p, g.weight_fmt, c->plan, c->compute, c->prof_events[c->prof_used].first,
                                c->prof_events[c->prof_used].second));
-    ++c->prof_used;
   } else {
     HIP_TRY(launch_expert_gemv(p, g.weight_fmt, c->plan, c->compute));
   }
-  HIP_TRY(launch_partial_reduce(c->d_partial, c->plan.grid, y_dev, g.hidden, g.act_fmt, c->compute));
+  int n_miss = c->h_route[layer].n_miss;
+  if (c->routed[layer] == 2) {
+    if (int rc = collect_route(c, layer, c->route_seq[layer], &n_miss)) return rc;
+  }
+  if (prof) c->prof_full[c->prof_used++] = n_miss == 0;
+  int rows = c->plan.grid;
+  if (n_miss > 0) {
+    // pass 1: the experts whose slots are being filled, once the fills have landed
+    HIP_TRY(hipStreamWaitEvent(c->compute, c->ev_copy[layer], 0));
+    p.pass = 1;
+    p.row_offset = c->plan.grid;
+    HIP_TRY(launch_expert_gemv(p, g.weight_fmt, c->plan, c->compute));
+    rows = 2 * c->plan.grid;
+  }
+  HIP_TRY(launch_partial_reduce(c->d_partial, rows, y_dev, g.hidden, g.act_fmt, c->compute));
   c->routed[layer] = 0;
+  return MOE_OK;
+}
+
+int moe_cache_last_route(moe_cache_t *c, int32_t layer, moe_route_out_t *out) {
+  if (int rc = check_layer(c, layer)) return rc;
+  if (!out) return fail(MOE_EINVAL, "out is NULL");
+  if (c->routed[layer] == 2) return fail(MOE_ESTATE, "layer %d: routing decision not collected yet", layer);
+  *out = c->h_route[layer];
   return MOE_OK;
 }
 
@@ -431,13 +463,16 @@ int moe_cache_profile(moe_cache_t *c, int32_t enable, int32_t reset, double *avg
   if (!c) return fail(MOE_EINVAL, "context is NULL");
   HIP_TRY(hipStreamSynchronize(c->compute));
   double total_ms = 0.0;
+  int64_t n_full = 0;
   for (size_t i = 0; i < c->prof_used; ++i) {
+    if (!c->prof_full[i]) continue;  // a launch that left out missing experts moved fewer bytes
     float ms = 0.f;
     HIP_TRY(hipEventElapsedTime(&ms, c->prof_events[i].first, c->prof_events[i].second));
     total_ms += ms;
+    ++n_full;
   }
-  if (avg_us) *avg_us = c->prof_used ? total_ms * 1000.0 / (double)c->prof_used : 0.0;
-  if (launches) *launches = (int64_t)c->prof_used;
+  if (avg_us) *avg_us = n_full ? total_ms * 1000.0 / (double)n_full : 0.0;
+  if (launches) *launches = n_full;
   if (reset) c->prof_used = 0;
   c->profiling = enable != 0;
   return MOE_OK;

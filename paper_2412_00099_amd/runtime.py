@@ -129,11 +129,14 @@ class MoEDecoder:
     def __del__(self):
         self.close()
 
-    def route_step(self, layer, x=None, logits=None, out=None):
-        return B.moe_route_step(self.ctx, layer, _ptr(x), _ptr(logits), out)
+    def route_step(self, layer, x=None, logits=None, out=None, wait=True):
+        return B.moe_route_step(self.ctx, layer, _ptr(x), _ptr(logits), out, wait)
 
     def expert_forward(self, layer, x, y):
         B.moe_expert_forward(self.ctx, layer, _ptr(x), _ptr(y))
+
+    def last_route(self, layer):
+        return B.moe_cache_last_route(self.ctx, layer)
 
     def stats(self, layer=-1):
         return B.moe_cache_stats(self.ctx, layer)

@@ -22,11 +22,14 @@ C1 = CONFIGS["c1_single_fp32"]
 C2 = CONFIGS["c2_qwen_bf16"]
 
 
-def test_bf16_stack_reduced_with_shared_expert_and_ragged_split():
-    # 4*200 + 328 = 1128 records over 256 workgroups of 8 wavefronts: uneven spans, idle wavefronts
+@pytest.mark.parametrize("deferred", [False, True])
+def test_bf16_stack_reduced_with_shared_expert_and_ragged_split(deferred):
+    # 4*200 + 328 = 1128 records over 256 workgroups of 8 wavefronts: uneven spans, idle wavefronts;
+    # lambda = 0 keeps misses frequent, so the second (post-fill) expert launch is exercised often
     cfg = C2.with_(n_layers=2, n_experts=12, inter=200, shared_inter=328, capacity=6, seed=91)
-    print("case bf16 reduced stack", flush=True)
-    free_run(cfg, 0.5, 48, top_j=2)
+    print(f"case bf16 reduced stack deferred={deferred}", flush=True)
+    free_run(cfg, 0.5, 48, top_j=2, deferred=deferred)
+    free_run(cfg, 0.0, 48, deferred=deferred)
 
 
 @pytest.mark.parametrize("fmt,hidden", [("fp32", 512), ("fp32", 1024), ("fp32", 2048), ("bf16", 512),
@@ -114,6 +117,7 @@ def test_int8_reduced(hidden, inter):
     cfg = CONFIGS["c5_mixtral_int8"].with_(n_layers=2, hidden=hidden, inter=inter, seed=400 + hidden)
     print(f"case int8 hidden={hidden}", flush=True)
     free_run(cfg, 0.5, 32, top_j=1)
+    free_run(cfg, 0.0, 24, deferred=True)
 
 
 @pytest.mark.parametrize("hidden,inter,shared", [(2048, 256, 384), (4096, 128, 0)])
@@ -122,6 +126,7 @@ def test_int4_reduced(hidden, inter, shared):
                                             n_experts=16, capacity=8, seed=500 + hidden)
     print(f"case int4 hidden={hidden}", flush=True)
     free_run(cfg, 0.5, 32, top_j=2)
+    free_run(cfg, 0.0, 24, deferred=True)
 
 
 @pytest.mark.parametrize("fmt", ["int8", "int4"])

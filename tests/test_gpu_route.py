@@ -114,7 +114,7 @@ def test_state_errors():
     dec.close()
 
 
-def free_run(cfg, lam, T, top_j=0, check_outputs_every=1, tol=None):
+def free_run(cfg, lam, T, top_j=0, check_outputs_every=1, tol=None, deferred=False):
     """x-in mode: the device computes the router GEMV; tie protocol on disagreement."""
     from oracle import experts as oexp
 
@@ -132,8 +132,13 @@ def free_run(cfg, lam, T, top_j=0, check_outputs_every=1, tol=None):
     picks = []
     for t in range(T):
         for l in range(L):
-            raw = dec.route_step(l, x=xs_dev[t, l])
-            dec.expert_forward(l, xs_dev[t, l], ys[t, l])
+            if deferred:  # the router kernel is only enqueued; the decision is collected by expert_forward
+                assert dec.route_step(l, x=xs_dev[t, l], wait=False) is None
+                dec.expert_forward(l, xs_dev[t, l], ys[t, l])
+                raw = dec.last_route(l)
+            else:
+                raw = dec.route_step(l, x=xs_dev[t, l])
+                dec.expert_forward(l, xs_dev[t, l], ys[t, l])
             out = route_fields(raw, K)
             x_np = xs[t, l].float().numpy()
             z = routing.router_logits(ow.gate(l), x_np)
@@ -180,3 +185,9 @@ def free_run(cfg, lam, T, top_j=0, check_outputs_every=1, tol=None):
 def test_c1_free_run_routing_and_outputs(lam):
     print(f"case c1 free run lam={lam}", flush=True)
     free_run(CONFIGS["c1_single_fp32"], lam, 256)
+
+
+@pytest.mark.parametrize("lam", [0.0, 0.5])
+def test_c1_free_run_deferred_decision(lam):
+    print(f"case c1 deferred lam={lam}", flush=True)
+    free_run(CONFIGS["c1_single_fp32"], lam, 128, deferred=True)
