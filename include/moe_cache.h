@@ -90,7 +90,8 @@ typedef struct moe_route_out {
   float margin;                     /* gap between the K-th and (K+1)-th altered logit */
   float logits[MOE_MAX_EXPERTS];    /* z, as used */
   uint32_t seq;                     /* internal completion tag */
-  uint32_t pad_[3];
+  uint32_t packed_slots[2];         /* internal: sel_slot, 8 bits each (read by the expert kernels) */
+  uint32_t miss_mask;               /* internal: bit k = miss[k] */
 } moe_route_out_t;
 
 typedef struct moe_cache_stats {

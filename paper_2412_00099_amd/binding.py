@@ -74,7 +74,8 @@ class moe_route_out_t(C.Structure):
         ("margin", C.c_float),
         ("logits", C.c_float * MOE_MAX_EXPERTS),
         ("seq", C.c_uint32),
-        ("pad_", C.c_uint32 * 3),
+        ("packed_slots", C.c_uint32 * 2),
+        ("miss_mask", C.c_uint32),
     ]
 
 

@@ -43,47 +43,66 @@ __device__ __forceinline__ void wave_sum2(float &a, float &b) {
 
 // Walks the records one wavefront owns in one launch.
 //
-// The launch's work list is, per workgroup, its even share of the shared expert's records followed by its
-// even share of the routed records (the K selected slots side by side, I records each); the wavefronts of the
-// workgroup take list entries wave, wave+NW, ...  Shared records need nothing from the routing step, so a
-// workgroup starts streaming them at once while the loads of the routing record (slots, weights, miss flags)
-// are still in flight.  Pass 0 covers the shared expert and the experts that were resident; pass 1 covers
-// only the experts whose slots were filled for this token, so the first pass can run while the fills stream.
+// Every workgroup owns a share of the shared expert's records followed by a share of the routed records (the K
+// selected slots side by side, I records each); its wavefronts take list entries wave, wave+NW, ...  Shared
+// records need nothing from the routing step, so streaming starts at once while the loads of the routing
+// record are in flight; the record is unpacked when the first routed entry comes up.  Pass 0 covers the
+// shared expert and the experts that were resident; pass 1 covers only the experts whose slots were filled
+// for this token, so the first pass can run while the fills stream.
+//
+// Shares are equal and fixed.  Workgroups do not finish together (XCDs and compute units get unequal slices
+// of HBM bandwidth: finish times of equal shares spread over about 4 us of 23), but handing records out
+// dynamically with device-scope atomics is far slower (an atomic on a contended address costs about 200 ns
+// while HBM is saturated) and skewing the shares by XCD parity gave nothing measurable.  Fixed shares also
+// keep the summation order of y, hence y itself, identical from run to run.
 template <int NW>
 struct RecordWalker {
-  int idx, ns, nl, s0, q0;
-  int seg, row;  // position in the routed part (seg < 0: not entered yet)
-  // routing record entries of segment `have` (current) and `have + 1` (prefetched)
-  int have, slot_c, miss_c, slot_n, miss_n;
-  float w_c, w_n;
+  int s0, q0, ns, nl;  // this workgroup's shared rows start at s0 (ns of them), routed records at q0; nl entries
+  int idx;             // next list entry of this wavefront
+  int seg, row;        // position in the routed part (seg < 0: not entered yet)
+  // the routing record: loaded at kernel start, unpacked when the first routed record comes up
+  u32x4 rw0, rw1, rd;  // sel_weight[0..3], sel_weight[4..7], {tag, slots lo, slots hi, miss mask}
+  uint64_t slots;
+  uint32_t miss_mask;
   // the record found by next()
   const uint8_t *base;  // blob of the record's expert
   int rows, at;
   float wt;
 
-  __device__ __forceinline__ void fetch(const GemvParams &p, int k, int &slot, int &miss, float &w) {
-    const int kk = k < p.top_k ? k : p.top_k - 1;  // always a valid entry; values past the end are never used
-    slot = p.route->sel_slot[kk];
-    miss = p.route->miss[kk];
-    w = p.route->sel_weight[kk];
-  }
+  // start of workgroup b's share of n records
+  static __device__ __forceinline__ int bound(int b, int n, int G) { return (int)((int64_t)b * n / G); }
 
   __device__ __forceinline__ void init(const GemvParams &p, int wave) {
     const int G = gridDim.x, b = blockIdx.x;
+    // the routing record first: these loads return before any weight load issued after them
+    const u32x4 *rr = reinterpret_cast<const u32x4 *>(p.route);
+    rw0 = rr[offsetof(moe_route_out_t, sel_weight) / 16];
+    rw1 = rr[offsetof(moe_route_out_t, sel_weight) / 16 + 1];
+    rd = rr[offsetof(moe_route_out_t, seq) / 16];
     const int routed = p.top_k * p.inter;
-    s0 = p.pass == 0 ? (int)((int64_t)b * p.shared_inter / G) : 0;
-    const int s1 = p.pass == 0 ? (int)((int64_t)(b + 1) * p.shared_inter / G) : 0;
-    q0 = (int)((int64_t)b * routed / G);
-    const int q1 = (int)((int64_t)(b + 1) * routed / G);
-    ns = s1 - s0;
-    nl = ns + (q1 - q0);
+    const int shared = p.pass == 0 ? p.shared_inter : 0;
+    s0 = bound(b, shared, G);
+    ns = bound(b + 1, shared, G) - s0;
+    q0 = bound(b, routed, G);
+    nl = ns + bound(b + 1, routed, G) - q0;
     idx = wave;
     seg = -1;
     row = 0;
-    // issued now, first needed when the routed part begins
-    have = q0 / p.inter;
-    fetch(p, have, slot_c, miss_c, w_c);
-    fetch(p, have + 1, slot_n, miss_n, w_n);
+  }
+
+  // masks instead of a select chain: a chain over adjacent members is turned into an indexed load from a
+  // memory copy of the struct, which then lives in scratch
+  __device__ __forceinline__ float pick_weight(int k) const {
+    uint32_t v = 0;
+    v |= rw0.x & (0u - (uint32_t)(k == 0));
+    v |= rw0.y & (0u - (uint32_t)(k == 1));
+    v |= rw0.z & (0u - (uint32_t)(k == 2));
+    v |= rw0.w & (0u - (uint32_t)(k == 3));
+    v |= rw1.x & (0u - (uint32_t)(k == 4));
+    v |= rw1.y & (0u - (uint32_t)(k == 5));
+    v |= rw1.z & (0u - (uint32_t)(k == 6));
+    v |= rw1.w & (0u - (uint32_t)(k == 7));
+    return __uint_as_float(v);
   }
 
   // advance to this wavefront's next record of the pass; false when the list is exhausted
@@ -98,23 +117,19 @@ struct RecordWalker {
         idx += NW;
         return true;
       }
-      if (seg < 0) {
+      if (seg < 0) {  // first routed entry: unpack the routing record, locate the entry
+        slots = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)rd.y) |
+                ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)rd.z) << 32);
+        miss_mask = (uint32_t)__builtin_amdgcn_readfirstlane((int)rd.w);
         const int r = q0 + (idx - ns);
         seg = r / I;
         row = r - seg * I;
       }
-      while (have < seg) {  // entered a new segment: the prefetched entries become current
-        ++have;
-        slot_c = slot_n;
-        miss_c = miss_n;
-        w_c = w_n;
-        fetch(p, have + 1, slot_n, miss_n, w_n);
-      }
-      const bool wanted = (miss_c != 0) == (p.pass == 1);
-      base = p.slot_pool + (int64_t)slot_c * p.slot_bytes;
+      const bool wanted = (((miss_mask >> seg) & 1u) != 0) == (p.pass == 1);
+      base = p.slot_pool + (int64_t)((slots >> (8 * seg)) & 0xffu) * p.slot_bytes;
       rows = I;
       at = row;
-      wt = w_c;
+      wt = pick_weight(seg);
       idx += NW;
       row += NW;
       while (row >= I && seg < K) {

@@ -303,6 +303,23 @@ __global__ __launch_bounds__(1024) void route_kernel(RouteParams p, const void *
     rec_s[W_MISS + k] = miss ? 1u : 0u;
     rec_s[W_EVICT + k] = (uint32_t)my_evicted;
   }
+  // compact copy for the expert kernels: slots 8 bits each in selection order, miss flags as a mask
+  {
+    uint32_t lo = 0, hi = 0, mm = 0;
+    for (uint64_t m = sel_mask; m; m &= m - 1) {
+      const int e = (int)__builtin_ctzll(m);
+      const int k = readlane_i(rank_p, e);
+      const uint32_t s8 = (uint32_t)readlane_i(my_slot, e) & 0xffu;
+      if (k < 4) lo |= s8 << (8 * k); else hi |= s8 << (8 * (k - 4));
+      mm |= (uint32_t)((miss_mask >> e) & 1) << k;
+    }
+    if (lane == 0) {
+      rec_s[W_SEQ] = p.seq;
+      rec_s[W_SEQ + 1] = lo;
+      rec_s[W_SEQ + 2] = hi;
+      rec_s[W_SEQ + 3] = mm;
+    }
+  }
   if (lane == 0) {
     rec_s[W_NMISS] = (uint32_t)n_miss;
     rec_s[W_TOKEN] = (uint32_t)t;
@@ -313,15 +330,14 @@ __global__ __launch_bounds__(1024) void route_kernel(RouteParams p, const void *
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   constexpr int kPayloadChunks = W_SEQ / 4;  // everything before the completion tag
-  if (lane < kPayloadChunks) {
+  if (lane <= kPayloadChunks) {  // the device copy includes the last chunk (tag + compact fields)
     const u32x4 v = reinterpret_cast<const u32x4 *>(rec_s)[lane];
     reinterpret_cast<u32x4 *>(out_dev)[lane] = v;
-    reinterpret_cast<u32x4 *>(out_host)[lane] = v;
+    if (lane < kPayloadChunks) reinterpret_cast<u32x4 *>(out_host)[lane] = v;
   }
   __threadfence_system();
   __builtin_amdgcn_wave_barrier();
   if (lane == 0) {
-    out_dev->seq = p.seq;
     __hip_atomic_store(&out_host->seq, p.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
   }
 }
