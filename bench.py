@@ -3,8 +3,8 @@
 Workload (config.workload): the Qwen1.5-MoE-A2.7B-shaped stack, bf16, attention omitted - 24 layers,
 hidden 2048, 60 routed experts of intermediate 1408 (top-4) plus a shared SwiGLU of intermediate 5632,
 30 of 60 experts cached per layer, random N(0, 0.02) weights, AR(1) (rho = 0.9) hidden-state streams with
-a residual add between layers.  A step is one decode token through all layers: per layer the stack glue,
-the fused router kernel, the miss fills and the expert GEMV.  All weights and inputs are resident (device
+a residual add between layers.  A step is one decode token through all layers: per layer one fused launch
+(previous expert output, stack glue, router) , the miss fills and the expert GEMV.  All weights and inputs are resident (device
 slots / pinned host tier) before the timed region.
 
 Prints ONE JSON line.  `value` is tokens/s at the headline strength lambda = 0.5; `roofline` is the expert
@@ -33,17 +33,18 @@ def log(msg):
 
 
 def decode_tokens(dec, a, h, x, y, t0, t1):
-    """Tokens t0..t1-1 through the whole stack (all calls asynchronous except the router's host hand-off)."""
+    """Tokens t0..t1-1 through the whole stack; nothing here waits for the GPU except the hand-off of each
+    routing decision to the host inside expert_forward (needed to enqueue miss fills).
+
+    Per layer: one fused boundary launch (finish the previous layer's expert output, h_l = h_{l-1} + y_{l-1}
+    + 0.5 a[t,l] (h_0 = a[t,0]), x_l = rmsnorm(h_l), route layer l) and the expert launch(es); the expert output
+    stays inside the library as partial sums until the next boundary launch.
+    """
     L = dec.store.L
     for t in range(t0, t1):
         for l in range(L):
-            # h_0 = a[t,0]; h_{l} = h_{l-1} + y_{l-1} + 0.5 a[t,l]; x_l = rmsnorm(h_l)
-            if l == 0:
-                dec.residual_rmsnorm(h, None, a[t, 0], 1.0, x, carry=False)
-            else:
-                dec.residual_rmsnorm(h, y, a[t, l], PERTURB, x, carry=True)
-            dec.route_step(l, x=x, wait=False)
-            dec.expert_forward(l, x, y)
+            dec.stack_route_step(l, h, a[t, l], 1.0 if l == 0 else PERTURB, x, carry=l > 0, wait=False)
+            dec.expert_forward(l, x, None)
 
 
 def timed_run(dec, a, h, x, y, warmup, steps):

@@ -141,8 +141,21 @@ int moe_route_step(moe_cache_t *ctx, int32_t layer, const void *x_dev, const flo
  * moe_route_step), y_dev device [d] in act_fmt.  The kernels are asynchronous on compute_stream: a first
  * launch covers the shared expert and the experts that were resident, a second one (after the fills) the
  * experts that were missing.  The call returns once the routing decision has reached the host (it is needed
- * to enqueue the fills), not when y is ready.  MOE_ESTATE without a preceding moe_route_step. */
+ * to enqueue the fills), not when y is ready.  MOE_ESTATE without a preceding moe_route_step.
+ * y_dev may be NULL: the output then stays inside the library as fp32 partial sums and is finished by the next
+ * moe_stack_route_step (of any layer), which must follow before another moe_expert_forward. */
 int moe_expert_forward(moe_cache_t *ctx, int32_t layer, const void *x_dev, void *y_dev);
+
+/* Layer boundary of a multi-layer stack (workload glue fused with the router kernel: Eq. 3, 9, 10, 4, Sec. 4.2):
+ *   y  = the expert output left pending by moe_expert_forward(..., y_dev = NULL), if any
+ *   h  = carry ? h + y + perturb * a : perturb * a  (a may be NULL; carry = 0 starts a new token)
+ *   x  = h / sqrt(mean(h^2) + 1e-6), rounded to act_fmt, written to x_dev
+ *   then the routing step of `layer` on x, exactly as moe_route_step(ctx, layer, x_dev, NULL, out_host).
+ * h_dev: device fp32 [d] in/out; a_dev: device fp32 [d] or NULL; x_dev: device act_fmt [d] (pass it to the
+ * layer's moe_expert_forward); y_dev: device act_fmt [d] or NULL, receives the finished pending output.
+ * hidden must be at most 8192.  Same blocking rule and errors as moe_route_step. */
+int moe_stack_route_step(moe_cache_t *ctx, int32_t layer, float *h_dev, const float *a_dev, float perturb,
+                         int32_t carry, void *x_dev, void *y_dev, moe_route_out_t *out_host);
 
 /* The last routing decision of a layer that has reached the host (after a blocking moe_route_step, or after
  * the moe_expert_forward that followed a non-blocking one).  MOE_ESTATE if a decision is still pending. */

@@ -107,6 +107,8 @@ lib.moe_cache_destroy.restype = None
 lib.moe_cache_destroy.argtypes = [_vp]
 lib.moe_route_step.restype = C.c_int
 lib.moe_route_step.argtypes = [_vp, C.c_int32, _vp, _vp, C.POINTER(moe_route_out_t)]
+lib.moe_stack_route_step.restype = C.c_int
+lib.moe_stack_route_step.argtypes = [_vp, C.c_int32, _vp, _vp, C.c_float, C.c_int32, _vp, _vp, C.POINTER(moe_route_out_t)]
 lib.moe_expert_forward.restype = C.c_int
 lib.moe_expert_forward.argtypes = [_vp, C.c_int32, _vp, _vp]
 lib.moe_cache_last_route.restype = C.c_int
@@ -129,7 +131,7 @@ lib.moe_last_error.restype = C.c_char_p
 lib.moe_last_error.argtypes = []
 
 EXPORTS = [
-    "moe_blob_bytes", "moe_pack_expert", "moe_cache_init", "moe_cache_destroy", "moe_route_step",
+    "moe_blob_bytes", "moe_pack_expert", "moe_cache_init", "moe_cache_destroy", "moe_route_step", "moe_stack_route_step",
     "moe_expert_forward", "moe_cache_last_route", "moe_cache_stats", "moe_cache_tables", "moe_cache_set_lambda",
     "moe_cache_set_baseline", "moe_cache_reset", "moe_residual_rmsnorm", "moe_cache_profile", "moe_last_error",
 ]
@@ -176,6 +178,18 @@ def moe_route_step(ctx, layer: int, x_dev, logits_dev, out: moe_route_out_t | No
         return None
     out = moe_route_out_t() if out is None else out
     _check(lib.moe_route_step(ctx, layer, x_dev, logits_dev, C.byref(out)), "moe_route_step")
+    return out
+
+
+def moe_stack_route_step(ctx, layer: int, h_dev, a_dev, perturb: float, carry: int, x_dev, y_dev=None,
+                         out: moe_route_out_t | None = None, wait: bool = True):
+    if not wait:
+        _check(lib.moe_stack_route_step(ctx, layer, h_dev, a_dev, perturb, carry, x_dev, y_dev, None),
+               "moe_stack_route_step")
+        return None
+    out = moe_route_out_t() if out is None else out
+    _check(lib.moe_stack_route_step(ctx, layer, h_dev, a_dev, perturb, carry, x_dev, y_dev, C.byref(out)),
+           "moe_stack_route_step")
     return out
 
 

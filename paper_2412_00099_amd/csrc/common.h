@@ -30,6 +30,17 @@ struct RouteParams {
   uint32_t seq;
 };
 
+// Glue of a stack fused in front of the router (see fused_route_kernel).
+constexpr int kFusedMaxHidden = 8192;
+struct FusedParams {
+  const void *y;    // [d] act_fmt, the previous layer's expert output, or nullptr
+  float *h;         // [d] fp32 residual stream, updated in place
+  const float *a;   // [d] fp32 perturbation or nullptr
+  float perturb;
+  int32_t carry;    // 0: a new token starts, h = perturb * a
+  void *x_out;      // [d] act_fmt, the normalised vector (input of this layer)
+};
+
 struct GemvParams {
   const uint8_t *slot_pool;      // this layer's slots
   const uint8_t *shared_blob;    // or nullptr
@@ -63,6 +74,8 @@ struct GemvPlan {
   bool dot2;  // packed bf16 dot products (bf16 weights and activations)
 };
 GemvPlan gemv_plan(int n_cus, int total_records, int weight_fmt, int act_fmt);
+hipError_t launch_fused_route(const RouteParams &p, const FusedParams &f, const void *gate_w, LayerState *state,
+                              moe_route_out_t *out_dev, moe_route_out_t *out_host_mapped, hipStream_t s);
 hipError_t launch_expert_gemv(const GemvParams &p, int weight_fmt, const GemvPlan &plan, hipStream_t s,
                               hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
 hipError_t launch_partial_reduce(const float *partial, int n_partial, void *y, int hidden, int act_fmt,

@@ -56,6 +56,8 @@ struct moe_cache {
   moe_route_out_t *h_route_dev = nullptr;  // device view of h_route
   int32_t *d_initial = nullptr;
   float *d_partial = nullptr;
+  int pending_rows = 0;            // partial rows of an expert output not reduced yet (y_dev was NULL)
+  void *d_y = nullptr;             // [d] act_fmt: a pending expert output once summed, when the caller gave no y_dev
   GemvPlan plan{};
   hipEvent_t ev_route = nullptr;
   std::vector<hipEvent_t> ev_copy;
@@ -86,6 +88,7 @@ int do_reset(moe_cache_t *c) {
   if (c->n_initial > 0)
     HIP_TRY(hipMemcpy(c->d_initial, c->initial.data(), c->initial.size() * sizeof(int32_t), hipMemcpyHostToDevice));
   HIP_TRY(launch_state_init(c->d_state, c->cfg.n_layers, c->d_initial, c->n_initial, c->compute));
+  c->pending_rows = 0;
   const int N = c->cfg.n_experts;
   for (int l = 0; l < c->cfg.n_layers; ++l) {
     for (int i = 0; i < c->n_initial; ++i) {
@@ -223,6 +226,7 @@ int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, 
   HIP_INIT(hipHostGetDevicePointer(reinterpret_cast<void **>(&c->h_route_dev), c->h_route, 0));
   HIP_INIT(hipMalloc(&c->d_initial, sizeof(int32_t) * (size_t)L * (b->n_initial > 0 ? b->n_initial : 1)));
   HIP_INIT(hipMalloc(&c->d_partial, sizeof(float) * 2 * (size_t)c->plan.grid * cfg->hidden));
+  HIP_INIT(hipMalloc(&c->d_y, sizeof(float) * (size_t)cfg->hidden));
   HIP_INIT(hipEventCreateWithFlags(&c->ev_route, hipEventDisableTiming));
   for (int l = 0; l < L; ++l) HIP_INIT(hipEventCreateWithFlags(&c->ev_copy[l], hipEventDisableTiming));
 #undef HIP_INIT
@@ -241,6 +245,7 @@ void moe_cache_destroy(moe_cache_t *c) {
   if (c->h_route) (void)hipHostFree(c->h_route);
   if (c->d_initial) (void)hipFree(c->d_initial);
   if (c->d_partial) (void)hipFree(c->d_partial);
+  if (c->d_y) (void)hipFree(c->d_y);
   if (c->ev_route) (void)hipEventDestroy(c->ev_route);
   for (hipEvent_t e : c->ev_copy)
     if (e) (void)hipEventDestroy(e);
@@ -293,11 +298,7 @@ static int collect_route(moe_cache_t *c, int32_t layer, uint32_t seq, int *n_mis
   return MOE_OK;
 }
 
-int moe_route_step(moe_cache_t *c, int32_t layer, const void *x_dev, const float *logits_dev,
-                   moe_route_out_t *out_host) {
-  if (int rc = check_layer(c, layer)) return rc;
-  if ((x_dev == nullptr) == (logits_dev == nullptr)) return fail(MOE_EINVAL, "exactly one of x_dev and logits_dev must be given");
-  if (c->routed[layer]) return fail(MOE_ESTATE, "layer %d: previous route step not followed by moe_expert_forward", layer);
+static RouteParams make_route_params(moe_cache_t *c) {
   const moe_cache_config_t &g = c->cfg;
   RouteParams p{};
   p.n_experts = g.n_experts;
@@ -315,24 +316,66 @@ int moe_route_step(moe_cache_t *c, int32_t layer, const void *x_dev, const float
   p.cumsum_p = g.cumsum_p;
   if (++c->seq == 0) c->seq = 1;
   p.seq = c->seq;
-  HIP_TRY(launch_route(p, c->gate_w[layer], x_dev, logits_dev, c->d_state + layer, c->d_route + layer,
-                       c->h_route_dev + layer, c->compute));
-  c->route_seq[layer] = p.seq;
+  return p;
+}
+
+// after the router launch: either leave the decision for moe_expert_forward, or wait for it now
+static int finish_route_call(moe_cache_t *c, int32_t layer, uint32_t seq, moe_route_out_t *out_host) {
+  c->route_seq[layer] = seq;
   if (!out_host) {
     c->routed[layer] = 2;  // decision collected by moe_expert_forward, behind the first expert launch
     return MOE_OK;
   }
   int n_miss = 0;
-  if (int rc = collect_route(c, layer, p.seq, &n_miss)) return rc;
+  if (int rc = collect_route(c, layer, seq, &n_miss)) return rc;
   c->routed[layer] = 1;
   *out_host = c->h_route[layer];
   return MOE_OK;
 }
 
+int moe_route_step(moe_cache_t *c, int32_t layer, const void *x_dev, const float *logits_dev,
+                   moe_route_out_t *out_host) {
+  if (int rc = check_layer(c, layer)) return rc;
+  if ((x_dev == nullptr) == (logits_dev == nullptr)) return fail(MOE_EINVAL, "exactly one of x_dev and logits_dev must be given");
+  if (c->routed[layer]) return fail(MOE_ESTATE, "layer %d: previous route step not followed by moe_expert_forward", layer);
+  if (c->pending_rows) return fail(MOE_ESTATE, "an expert output is pending: the next routing call must be moe_stack_route_step");
+  const RouteParams p = make_route_params(c);
+  HIP_TRY(launch_route(p, c->gate_w[layer], x_dev, logits_dev, c->d_state + layer, c->d_route + layer,
+                       c->h_route_dev + layer, c->compute));
+  return finish_route_call(c, layer, p.seq, out_host);
+}
+
+int moe_stack_route_step(moe_cache_t *c, int32_t layer, float *h_dev, const float *a_dev, float perturb,
+                         int32_t carry, void *x_dev, void *y_dev, moe_route_out_t *out_host) {
+  if (int rc = check_layer(c, layer)) return rc;
+  if (!h_dev || !x_dev) return fail(MOE_EINVAL, "h_dev or x_dev is NULL");
+  if (c->cfg.hidden > kFusedMaxHidden) return fail(MOE_EINVAL, "hidden exceeds %d", kFusedMaxHidden);
+  if (c->routed[layer]) return fail(MOE_ESTATE, "layer %d: previous route step not followed by moe_expert_forward", layer);
+  const RouteParams p = make_route_params(c);
+  // the pending expert output is summed first (into y_dev if given, else into the library's own buffer)
+  void *y = nullptr;
+  if (c->pending_rows > 0) {
+    y = y_dev ? y_dev : c->d_y;
+    HIP_TRY(launch_partial_reduce(c->d_partial, c->pending_rows, y, c->cfg.hidden, c->cfg.act_fmt, c->compute));
+  }
+  FusedParams f{};
+  f.y = y;
+  f.h = h_dev;
+  f.a = a_dev;
+  f.perturb = perturb;
+  f.carry = carry;
+  f.x_out = x_dev;
+  HIP_TRY(launch_fused_route(p, f, c->gate_w[layer], c->d_state + layer, c->d_route + layer, c->h_route_dev + layer,
+                             c->compute));
+  c->pending_rows = 0;
+  return finish_route_call(c, layer, p.seq, out_host);
+}
+
 int moe_expert_forward(moe_cache_t *c, int32_t layer, const void *x_dev, void *y_dev) {
   if (int rc = check_layer(c, layer)) return rc;
-  if (!x_dev || !y_dev) return fail(MOE_EINVAL, "x_dev or y_dev is NULL");
+  if (!x_dev) return fail(MOE_EINVAL, "x_dev is NULL");
   if (!c->routed[layer]) return fail(MOE_ESTATE, "layer %d: moe_expert_forward without a preceding moe_route_step", layer);
+  if (c->pending_rows) return fail(MOE_ESTATE, "an expert output is pending: call moe_stack_route_step first");
   const moe_cache_config_t &g = c->cfg;
   GemvParams p{};
   p.slot_pool = static_cast<const uint8_t *>(c->slot_pool[layer]);
@@ -378,7 +421,10 @@ int moe_expert_forward(moe_cache_t *c, int32_t layer, const void *x_dev, void *y
     HIP_TRY(launch_expert_gemv(p, g.weight_fmt, c->plan, c->compute));
     rows = 2 * c->plan.grid;
   }
-  HIP_TRY(launch_partial_reduce(c->d_partial, rows, y_dev, g.hidden, g.act_fmt, c->compute));
+  if (y_dev)
+    HIP_TRY(launch_partial_reduce(c->d_partial, rows, y_dev, g.hidden, g.act_fmt, c->compute));
+  else
+    c->pending_rows = rows;  // finished by the next moe_stack_route_step
   c->routed[layer] = 0;
   return MOE_OK;
 }

@@ -117,47 +117,51 @@ __device__ __forceinline__ void gate_rows(const void *gate_w, const void *x, int
   for (int r = 0; r < R; ++r) out[r] = wave_sum(acc[r]);
 }
 
-__global__ __launch_bounds__(1024) void route_kernel(RouteParams p, const void *gate_w, const void *x,
-                                                     const float *logits_in, LayerState *st,
-                                                     moe_route_out_t *out_dev, moe_route_out_t *out_host) {
-  __shared__ float z_s[MOE_MAX_EXPERTS];
-  __shared__ __attribute__((aligned(16))) uint32_t rec_s[kRecWords];
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), n_waves = blockDim.x >> 6;
-  const int N = p.n_experts, K = p.top_k, C = p.capacity;
-
-  // wavefront 0 owns the cache state; its loads are issued before the GEMV so their latency overlaps it
-  int my_slot = -1, slot_exp = -1, t = 0;
-  int64_t stamp = 0;
-  uint64_t ever_used = 0;
-  float dsum_prev = 0.f;
-  if (wave == 0) {
-    if (lane < N) {
-      my_slot = st->expert_slot[lane];
-      stamp = st->stamp[lane];
-    }
-    if (lane < C) slot_exp = st->slot_expert[lane];
-    ever_used = st->ever_used;
-    dsum_prev = st->delta_sum;
-    t = st->count;
-  }
-
-  if (logits_in != nullptr) {
-    if (tid < N) z_s[tid] = logits_in[tid];
-  } else {
-    constexpr int R = 4;
-    const int rpw = (N + n_waves - 1) / n_waves;  // rows per wavefront (<= 4 by the launch shape)
-    for (int row0 = wave * rpw; row0 < min(N, (wave + 1) * rpw); row0 += R) {
-      float v[R];
-      const int nrows = min(R, min(N, (wave + 1) * rpw) - row0);
-      gate_rows<R>(gate_w, x, row0, nrows, p.hidden, p.act_fmt, lane, v);
+// z = W_gate x by all wavefronts of the workgroup, at most four rows each
+__device__ __forceinline__ void gate_gemv(const void *gate_w, const void *x, const RouteParams &p, int wave, int n_waves,
+                                          int lane, float *z_s) {
+  constexpr int R = 4;
+  const int N = p.n_experts;
+  const int rpw = (N + n_waves - 1) / n_waves;  // rows per wavefront
+  for (int row0 = wave * rpw; row0 < min(N, (wave + 1) * rpw); row0 += R) {
+    float v[R];
+    const int nrows = min(R, min(N, (wave + 1) * rpw) - row0);
+    gate_rows<R>(gate_w, x, row0, nrows, p.hidden, p.act_fmt, lane, v);
 #pragma unroll
-      for (int r = 0; r < R; ++r)
-        if (lane == 0 && r < nrows) z_s[row0 + r] = v[r];
-    }
+    for (int r = 0; r < R; ++r)
+      if (lane == 0 && r < nrows) z_s[row0 + r] = v[r];
   }
-  __syncthreads();
-  if (wave != 0) return;
+}
+
+// Cache state of one layer as held by wavefront 0 (lane e: expert e, lane s: slot s).
+struct CacheRegs {
+  int my_slot, slot_exp, t;
+  int64_t stamp;
+  uint64_t ever_used;
+  float dsum_prev;
+};
+
+__device__ __forceinline__ CacheRegs load_cache_regs(const LayerState *st, int lane, int N, int C) {
+  CacheRegs cr;
+  cr.my_slot = lane < N ? st->expert_slot[lane] : -1;
+  cr.stamp = lane < N ? st->stamp[lane] : 0;
+  cr.slot_exp = lane < C ? st->slot_expert[lane] : -1;
+  cr.ever_used = st->ever_used;
+  cr.dsum_prev = st->delta_sum;
+  cr.t = st->count;
+  return cr;
+}
+
+// Everything after the logits (Eq. 3 softmax, Eq. 10, Eq. 9, Eq. 2, Eq. 4, Sec. 4.2), run by one wavefront.
+__device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_s, const CacheRegs &cr, LayerState *st,
+                                           moe_route_out_t *out_dev, moe_route_out_t *out_host, uint32_t *rec_s,
+                                           int lane) {
+  const int N = p.n_experts, K = p.top_k, C = p.capacity;
+  int my_slot = cr.my_slot, slot_exp = cr.slot_exp;
+  const int t = cr.t;
+  int64_t stamp = cr.stamp;
+  uint64_t ever_used = cr.ever_used;
+  const float dsum_prev = cr.dsum_prev;
 
   // ---- lane e <-> expert e ------------------------------------------------------------------
   const bool active = lane < N;
@@ -342,6 +346,154 @@ __global__ __launch_bounds__(1024) void route_kernel(RouteParams p, const void *
   }
 }
 
+__global__ __launch_bounds__(1024) void route_kernel(RouteParams p, const void *gate_w, const void *x,
+                                                     const float *logits_in, LayerState *st,
+                                                     moe_route_out_t *out_dev, moe_route_out_t *out_host) {
+  __shared__ float z_s[MOE_MAX_EXPERTS];
+  __shared__ __attribute__((aligned(16))) uint32_t rec_s[kRecWords];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), n_waves = blockDim.x >> 6;
+  const int N = p.n_experts;
+
+  // wavefront 0 owns the cache state; its loads are issued before the GEMV so their latency overlaps it
+  CacheRegs cr{};
+  if (wave == 0) cr = load_cache_regs(st, lane, N, p.capacity);
+
+  if (logits_in != nullptr) {
+    if (tid < N) z_s[tid] = logits_in[tid];
+  } else {
+    gate_gemv(gate_w, x, p, wave, n_waves, lane, z_s);
+  }
+  __syncthreads();
+  if (wave != 0) return;
+  route_wave(p, z_s, cr, st, out_dev, out_host, rec_s, lane);
+}
+
+// Gate rows of one wavefront held in registers: loaded before x exists, used once x is in LDS.
+template <int R, int CH>
+struct GateRegs {
+  u32x4 w[R][CH];
+};
+template <int R, int CH>
+__device__ __forceinline__ void gate_prefetch(const void *gate_w, int row0, int nrows, int lane, GateRegs<R, CH> &g) {
+  const u32x4 *w = reinterpret_cast<const u32x4 *>(gate_w) + (size_t)row0 * (CH * kWave);
+#pragma unroll
+  for (int r = 0; r < R; ++r)
+#pragma unroll
+    for (int c = 0; c < CH; ++c) g.w[r][c] = w[(size_t)(r < nrows ? r : nrows - 1) * (CH * kWave) + c * kWave + lane];
+}
+template <int R, int CH>
+__device__ __forceinline__ void gate_dot(const GateRegs<R, CH> &g, const uint32_t *x_s, int act_fmt, int lane, float *out) {
+  float acc[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) acc[r] = 0.f;
+#pragma unroll
+  for (int c = 0; c < CH; ++c) {
+    const u32x4 b = reinterpret_cast<const u32x4 *>(x_s)[c * kWave + lane];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const u32x4 a = g.w[r][c];
+      if (act_fmt == MOE_A_BF16) {
+        acc[r] = dot2(a.x, b.x, acc[r]);
+        acc[r] = dot2(a.y, b.y, acc[r]);
+        acc[r] = dot2(a.z, b.z, acc[r]);
+        acc[r] = dot2(a.w, b.w, acc[r]);
+      } else {
+        acc[r] = __builtin_fmaf(__uint_as_float(a.x), __uint_as_float(b.x), acc[r]);
+        acc[r] = __builtin_fmaf(__uint_as_float(a.y), __uint_as_float(b.y), acc[r]);
+        acc[r] = __builtin_fmaf(__uint_as_float(a.z), __uint_as_float(b.z), acc[r]);
+        acc[r] = __builtin_fmaf(__uint_as_float(a.w), __uint_as_float(b.w), acc[r]);
+      }
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < R; ++r) out[r] = wave_sum(acc[r]);
+}
+
+// Layer boundary of a stack: the residual / perturbation / RMS-normalisation glue and the routing of this layer in
+// one launch of one workgroup (the previous layer's expert output y has been summed by partial_reduce_kernel).
+//   h = carry ? h + y + perturb*a : perturb*a ;  x = h / sqrt(mean(h^2) + 1e-6) -> x_out and LDS ;  route on x.
+// CH > 0: 16-byte chunks per gate row per lane (d = CH*64*VEC); the wavefront's gate rows are then loaded into
+// registers at the very start, so the weight fetch overlaps the glue.  CH == 0: any d, rows loaded afterwards.
+template <int CH>
+__global__ __launch_bounds__(1024) void fused_route_kernel(RouteParams p, FusedParams f, const void *gate_w,
+                                                           LayerState *st, moe_route_out_t *out_dev,
+                                                           moe_route_out_t *out_host) {
+  __shared__ float z_s[MOE_MAX_EXPERTS];
+  __shared__ __attribute__((aligned(16))) uint32_t rec_s[kRecWords];
+  __shared__ float part_s[16];
+  __shared__ __attribute__((aligned(16))) uint32_t x_s[kFusedMaxHidden];  // x in act_fmt (bf16 uses half of it)
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), n_waves = blockDim.x >> 6;
+  const int d = p.hidden, N = p.n_experts;
+  const bool bf16 = p.act_fmt == MOE_A_BF16;
+  constexpr int R = 4;
+  const int rpw = (N + n_waves - 1) / n_waves;  // rows per wavefront (<= 4 by the launch shape)
+  const int row0 = wave * rpw, nrows = min(R, N - row0);
+
+  GateRegs<R, (CH > 0 ? CH : 1)> greg;
+  if (CH > 0 && nrows > 0) gate_prefetch<R, (CH > 0 ? CH : 1)>(gate_w, row0, nrows, lane, greg);
+  CacheRegs cr{};
+  if (wave == 0) cr = load_cache_regs(st, lane, N, p.capacity);
+
+  // ---- glue: each thread owns columns tid, tid + 1024, ... (kept in registers between the two sweeps) ----
+  constexpr int kMaxPer = kFusedMaxHidden / 1024;
+  float hv[kMaxPer];
+  float ss = 0.f;
+#pragma unroll
+  for (int i = 0; i < kMaxPer; ++i) {
+    const int j = tid + i * 1024;
+    hv[i] = 0.f;
+    if (j < d) {
+      float v = f.carry ? f.h[j] : 0.f;
+      if (f.y != nullptr && f.carry)
+        v += bf16 ? __uint_as_float((uint32_t) static_cast<const uint16_t *>(f.y)[j] << 16)
+                  : static_cast<const float *>(f.y)[j];
+      if (f.a != nullptr) v = __builtin_fmaf(f.perturb, f.a[j], v);
+      f.h[j] = v;
+      hv[i] = v;
+      ss = __builtin_fmaf(v, v, ss);
+    }
+  }
+  ss = wave_sum(ss);
+  if (lane == 0) part_s[wave] = ss;
+  __syncthreads();
+  float tot = 0.f;
+  for (int w = 0; w < n_waves; ++w) tot += part_s[w];
+  const float scale = 1.0f / sqrtf(tot / (float)d + 1e-6f);
+#pragma unroll
+  for (int i = 0; i < kMaxPer; ++i) {
+    const int j = tid + i * 1024;
+    if (j < d) {
+      const float v = hv[i] * scale;
+      if (bf16) {
+        const uint16_t q = f32_to_bf16_rne(v);
+        static_cast<uint16_t *>(f.x_out)[j] = q;
+        reinterpret_cast<uint16_t *>(x_s)[j] = q;
+      } else {
+        static_cast<float *>(f.x_out)[j] = v;
+        reinterpret_cast<float *>(x_s)[j] = v;
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- gate GEMV on x in LDS ----------------------------------------------------------------------
+  if (nrows > 0) {
+    float v[R];
+    if (CH > 0)
+      gate_dot<R, (CH > 0 ? CH : 1)>(greg, x_s, p.act_fmt, lane, v);
+    else
+      gate_rows<R>(gate_w, x_s, row0, nrows, d, p.act_fmt, lane, v);
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+      if (lane == 0 && r < nrows) z_s[row0 + r] = v[r];
+  }
+  __syncthreads();
+  if (wave != 0) return;
+  route_wave(p, z_s, cr, st, out_dev, out_host, rec_s, lane);
+}
+
 __global__ void state_init_kernel(LayerState *state, int n_layers, const int32_t *initial, int n_initial) {
   const int layer = blockIdx.x, lane = threadIdx.x;
   if (layer >= n_layers) return;
@@ -375,6 +527,22 @@ hipError_t launch_route(const RouteParams &p, const void *gate_w, const void *x,
   if (waves < 1) waves = 1;
   hipLaunchKernelGGL(route_kernel, dim3(1), dim3(waves * kWave), 0, s, p, gate_w, x, logits, state, out_dev,
                      out_host_mapped);
+  return hipGetLastError();
+}
+
+hipError_t launch_fused_route(const RouteParams &p, const FusedParams &f, const void *gate_w, LayerState *state,
+                              moe_route_out_t *out_dev, moe_route_out_t *out_host_mapped, hipStream_t s) {
+  if (p.hidden > kFusedMaxHidden || p.hidden % 8 != 0) return hipErrorInvalidValue;
+  // 16 wavefronts, at most four gate rows each (N <= 64)
+  const dim3 g(1), b(1024);
+  const int vec = p.act_fmt == MOE_A_BF16 ? 8 : 4;
+  const int ch = p.hidden % (kWave * vec) == 0 ? p.hidden / (kWave * vec) : 0;
+  switch (ch) {
+    case 1: hipLaunchKernelGGL(fused_route_kernel<1>, g, b, 0, s, p, f, gate_w, state, out_dev, out_host_mapped); break;
+    case 2: hipLaunchKernelGGL(fused_route_kernel<2>, g, b, 0, s, p, f, gate_w, state, out_dev, out_host_mapped); break;
+    case 4: hipLaunchKernelGGL(fused_route_kernel<4>, g, b, 0, s, p, f, gate_w, state, out_dev, out_host_mapped); break;
+    default: hipLaunchKernelGGL(fused_route_kernel<0>, g, b, 0, s, p, f, gate_w, state, out_dev, out_host_mapped);
+  }
   return hipGetLastError();
 }
 

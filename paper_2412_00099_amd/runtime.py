@@ -132,6 +132,9 @@ class MoEDecoder:
     def route_step(self, layer, x=None, logits=None, out=None, wait=True):
         return B.moe_route_step(self.ctx, layer, _ptr(x), _ptr(logits), out, wait)
 
+    def stack_route_step(self, layer, h, a, perturb, x, carry=True, y=None, out=None, wait=True):
+        return B.moe_stack_route_step(self.ctx, layer, _ptr(h), _ptr(a), perturb, int(carry), _ptr(x), _ptr(y), out, wait)
+
     def expert_forward(self, layer, x, y):
         B.moe_expert_forward(self.ctx, layer, _ptr(x), _ptr(y))
 
