@@ -62,9 +62,19 @@ struct BlobLayout {
 };
 BlobLayout blob_layout(int fmt, int hidden, int inter);
 
+// What the host needs of a routing decision, written by the router into mapped host memory as three 8-byte words,
+// each complete in itself (no ordering between them is assumed):
+//   w[0] = seq | n_miss << 32 | miss flags by selection position << 40
+//   w[1] = (seq & 0xffff) | expert of position k << (16 + 6k)
+//   w[2] = (seq & 0xffff) | slot of position k   << (16 + 6k)
+// The host has the decision once all three carry the tag of the step it waits for.
+struct HostNote {
+  uint64_t w[4];
+};
+
 // launchers (each returns the hipError_t of the launch)
 hipError_t launch_route(const RouteParams &p, const void *gate_w, const void *x, const float *logits,
-                        LayerState *state, moe_route_out_t *out_dev, moe_route_out_t *out_host_mapped,
+                        LayerState *state, moe_route_out_t *out_dev, HostNote *note_mapped,
                         hipStream_t s);
 // launch shape of the expert GEMV
 struct GemvPlan {
@@ -75,7 +85,7 @@ struct GemvPlan {
 };
 GemvPlan gemv_plan(int n_cus, int total_records, int weight_fmt, int act_fmt);
 hipError_t launch_fused_route(const RouteParams &p, const FusedParams &f, const void *gate_w, LayerState *state,
-                              moe_route_out_t *out_dev, moe_route_out_t *out_host_mapped, hipStream_t s);
+                              moe_route_out_t *out_dev, HostNote *note_mapped, hipStream_t s);
 hipError_t launch_expert_gemv(const GemvParams &p, int weight_fmt, const GemvPlan &plan, hipStream_t s,
                               hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
 hipError_t launch_partial_reduce(const float *partial, int n_partial, void *y, int hidden, int act_fmt,

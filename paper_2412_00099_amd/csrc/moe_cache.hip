@@ -52,8 +52,14 @@ struct moe_cache {
 
   LayerState *d_state = nullptr;
   moe_route_out_t *d_route = nullptr;
-  moe_route_out_t *h_route = nullptr;      // pinned, mapped
-  moe_route_out_t *h_route_dev = nullptr;  // device view of h_route
+  HostNote *h_note = nullptr;      // pinned, mapped: the router's message to the host, one per layer
+  HostNote *h_note_dev = nullptr;  // device view of h_note
+  struct Decision {                // h_note decoded
+    int n_miss = 0;
+    uint8_t miss_mask = 0;
+    uint8_t expert[MOE_MAX_TOPK] = {}, slot[MOE_MAX_TOPK] = {};
+  };
+  std::vector<Decision> decided;
   int32_t *d_initial = nullptr;
   float *d_partial = nullptr;
   int pending_rows = 0;            // partial rows of an expert output not reduced yet (y_dev was NULL)
@@ -191,6 +197,7 @@ int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, 
   c->copy = static_cast<hipStream_t>(cfg->copy_stream);
   c->routed.assign(L, 0);
   c->route_seq.assign(L, 0);
+  c->decided.assign(L, {});
   c->bytes_filled.assign(L, 0);
   c->ev_copy.assign(L, nullptr);
 
@@ -220,10 +227,10 @@ int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, 
   HIP_INIT(hipMalloc(&c->d_state, sizeof(LayerState) * L));
   HIP_INIT(hipMalloc(&c->d_route, sizeof(moe_route_out_t) * L));
   HIP_INIT(hipMemset(c->d_route, 0, sizeof(moe_route_out_t) * L));
-  HIP_INIT(hipHostMalloc(reinterpret_cast<void **>(&c->h_route), sizeof(moe_route_out_t) * L,
+  HIP_INIT(hipHostMalloc(reinterpret_cast<void **>(&c->h_note), sizeof(HostNote) * L,
                          hipHostMallocMapped | hipHostMallocCoherent));
-  memset(c->h_route, 0, sizeof(moe_route_out_t) * L);
-  HIP_INIT(hipHostGetDevicePointer(reinterpret_cast<void **>(&c->h_route_dev), c->h_route, 0));
+  memset(c->h_note, 0, sizeof(HostNote) * L);
+  HIP_INIT(hipHostGetDevicePointer(reinterpret_cast<void **>(&c->h_note_dev), c->h_note, 0));
   HIP_INIT(hipMalloc(&c->d_initial, sizeof(int32_t) * (size_t)L * (b->n_initial > 0 ? b->n_initial : 1)));
   HIP_INIT(hipMalloc(&c->d_partial, sizeof(float) * 2 * (size_t)c->plan.grid * cfg->hidden));
   HIP_INIT(hipMalloc(&c->d_y, sizeof(float) * (size_t)cfg->hidden));
@@ -242,7 +249,7 @@ void moe_cache_destroy(moe_cache_t *c) {
   (void)hipStreamSynchronize(c->copy);
   if (c->d_state) (void)hipFree(c->d_state);
   if (c->d_route) (void)hipFree(c->d_route);
-  if (c->h_route) (void)hipHostFree(c->h_route);
+  if (c->h_note) (void)hipHostFree(c->h_note);
   if (c->d_initial) (void)hipFree(c->d_initial);
   if (c->d_partial) (void)hipFree(c->d_partial);
   if (c->d_y) (void)hipFree(c->d_y);
@@ -256,18 +263,24 @@ void moe_cache_destroy(moe_cache_t *c) {
   delete c;
 }
 
-// Wait until the routing decision of `layer` (tag `seq`) is visible on the host, then enqueue the fills of the
-// missed experts on the copy stream.  Returns the number of misses through *n_miss.
+// Wait until the routing decision of `layer` (tag `seq`) is visible on the host, decode it, then enqueue the fills
+// of the missed experts on the copy stream.  Returns the number of misses through *n_miss.
 static int collect_route(moe_cache_t *c, int32_t layer, uint32_t seq, int *n_miss) {
   const moe_cache_config_t &g = c->cfg;
-  moe_route_out_t *h = c->h_route + layer;
+  const HostNote *h = c->h_note + layer;
+  const uint64_t tag = seq & 0xffffu;
+  uint64_t w0 = 0, w1 = 0, w2 = 0;
+  auto arrived = [&]() {
+    w0 = __atomic_load_n(&h->w[0], __ATOMIC_ACQUIRE);
+    w1 = __atomic_load_n(&h->w[1], __ATOMIC_ACQUIRE);
+    w2 = __atomic_load_n(&h->w[2], __ATOMIC_ACQUIRE);
+    return (uint32_t)w0 == seq && (w1 & 0xffffu) == tag && (w2 & 0xffffu) == tag;
+  };
   bool seen = false;
   if (c->poll) {
-    // the kernel stores the record to mapped host memory and then the tag, with a system-scope release
     const auto t0 = std::chrono::steady_clock::now();
-    volatile uint32_t *tag = &h->seq;
     for (uint32_t spin = 0;; ++spin) {
-      if (__atomic_load_n(tag, __ATOMIC_ACQUIRE) == seq) {
+      if (arrived()) {
         seen = true;
         break;
       }
@@ -278,14 +291,21 @@ static int collect_route(moe_cache_t *c, int32_t layer, uint32_t seq, int *n_mis
   if (!seen) {
     HIP_TRY(hipEventRecord(c->ev_route, c->compute));
     HIP_TRY(hipEventSynchronize(c->ev_route));
-    if (h->seq != seq) return fail(MOE_EHIP, "route kernel of layer %d did not publish its result", layer);
+    if (!arrived()) return fail(MOE_EHIP, "route kernel of layer %d did not publish its result", layer);
+  }
+  moe_cache::Decision &d = c->decided[layer];
+  d.n_miss = (int)((w0 >> 32) & 0xff);
+  d.miss_mask = (uint8_t)((w0 >> 40) & 0xff);
+  for (int k = 0; k < g.top_k; ++k) {
+    d.expert[k] = (uint8_t)((w1 >> (16 + 6 * k)) & 63);
+    d.slot[k] = (uint8_t)((w2 >> (16 + 6 * k)) & 63);
   }
   const size_t slot_bytes = (size_t)c->slot_layout.total;
-  if (h->n_miss > 0) {
+  if (d.n_miss > 0) {
     for (int k = 0; k < g.top_k; ++k) {
-      if (!h->miss[k]) continue;
-      const int e = h->sel_expert[k], s = h->sel_slot[k];
-      if (e < 0 || e >= g.n_experts || s < 0 || s >= g.capacity)
+      if (!((d.miss_mask >> k) & 1)) continue;
+      const int e = d.expert[k], s = d.slot[k];
+      if (e >= g.n_experts || s >= g.capacity)
         return fail(MOE_EHIP, "route kernel returned expert %d slot %d out of range", e, s);
       HIP_TRY(hipMemcpyAsync(static_cast<uint8_t *>(c->slot_pool[layer]) + (size_t)s * slot_bytes,
                              c->host_blob[(size_t)layer * g.n_experts + e], slot_bytes, hipMemcpyHostToDevice,
@@ -294,7 +314,14 @@ static int collect_route(moe_cache_t *c, int32_t layer, uint32_t seq, int *n_mis
     }
     HIP_TRY(hipEventRecord(c->ev_copy[layer], c->copy));
   }
-  *n_miss = h->n_miss;
+  *n_miss = d.n_miss;
+  return MOE_OK;
+}
+
+// the full decision record of a layer, from device memory (waits for the compute stream)
+static int fetch_record(moe_cache_t *c, int32_t layer, moe_route_out_t *out) {
+  HIP_TRY(hipMemcpyAsync(out, c->d_route + layer, sizeof *out, hipMemcpyDeviceToHost, c->compute));
+  HIP_TRY(hipStreamSynchronize(c->compute));
   return MOE_OK;
 }
 
@@ -329,8 +356,7 @@ static int finish_route_call(moe_cache_t *c, int32_t layer, uint32_t seq, moe_ro
   int n_miss = 0;
   if (int rc = collect_route(c, layer, seq, &n_miss)) return rc;
   c->routed[layer] = 1;
-  *out_host = c->h_route[layer];
-  return MOE_OK;
+  return fetch_record(c, layer, out_host);
 }
 
 int moe_route_step(moe_cache_t *c, int32_t layer, const void *x_dev, const float *logits_dev,
@@ -341,7 +367,7 @@ int moe_route_step(moe_cache_t *c, int32_t layer, const void *x_dev, const float
   if (c->pending_rows) return fail(MOE_ESTATE, "an expert output is pending: the next routing call must be moe_stack_route_step");
   const RouteParams p = make_route_params(c);
   HIP_TRY(launch_route(p, c->gate_w[layer], x_dev, logits_dev, c->d_state + layer, c->d_route + layer,
-                       c->h_route_dev + layer, c->compute));
+                       c->h_note_dev + layer, c->compute));
   return finish_route_call(c, layer, p.seq, out_host);
 }
 
@@ -365,7 +391,7 @@ int moe_stack_route_step(moe_cache_t *c, int32_t layer, float *h_dev, const floa
   f.perturb = perturb;
   f.carry = carry;
   f.x_out = x_dev;
-  HIP_TRY(launch_fused_route(p, f, c->gate_w[layer], c->d_state + layer, c->d_route + layer, c->h_route_dev + layer,
+  HIP_TRY(launch_fused_route(p, f, c->gate_w[layer], c->d_state + layer, c->d_route + layer, c->h_note_dev + layer,
                              c->compute));
   c->pending_rows = 0;
   return finish_route_call(c, layer, p.seq, out_host);
@@ -407,7 +433,7 @@ int moe_expert_forward(moe_cache_t *c, int32_t layer, const void *x_dev, void *y
   } else {
     HIP_TRY(launch_expert_gemv(p, g.weight_fmt, c->plan, c->compute));
   }
-  int n_miss = c->h_route[layer].n_miss;
+  int n_miss = c->decided[layer].n_miss;
   if (c->routed[layer] == 2) {
     if (int rc = collect_route(c, layer, c->route_seq[layer], &n_miss)) return rc;
   }
@@ -433,8 +459,7 @@ int moe_cache_last_route(moe_cache_t *c, int32_t layer, moe_route_out_t *out) {
   if (int rc = check_layer(c, layer)) return rc;
   if (!out) return fail(MOE_EINVAL, "out is NULL");
   if (c->routed[layer] == 2) return fail(MOE_ESTATE, "layer %d: routing decision not collected yet", layer);
-  *out = c->h_route[layer];
-  return MOE_OK;
+  return fetch_record(c, layer, out);
 }
 
 int moe_cache_stats(moe_cache_t *c, int32_t layer, moe_cache_stats_t *out) {

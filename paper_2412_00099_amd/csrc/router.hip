@@ -62,9 +62,11 @@ __device__ __forceinline__ uint64_t rank_key(float v, int lane, bool active) {
   return active ? (((uint64_t)sortable(v + 0.f) << 32) | (uint32_t)(63 - lane)) : 0ull;
 }
 // number of lanes < n whose key is larger than mine = my position in the descending ranking
-__device__ __forceinline__ int rank_of(uint64_t key, int n) {
+// (lanes >= n hold key 0, which is larger than no key, so all 64 lanes are always compared: no loop-carried branch)
+__device__ __forceinline__ int rank_of(uint64_t key) {
   int r = 0;
-  for (int j = 0; j < n; ++j) r += readlane_u64(key, j) > key;
+#pragma unroll
+  for (int j = 0; j < kWave; ++j) r += readlane_u64(key, j) > key;
   return r;
 }
 
@@ -139,6 +141,7 @@ struct CacheRegs {
   int64_t stamp;
   uint64_t ever_used;
   float dsum_prev;
+  int64_t counter;  // lanes 0..4: selections, hits, misses, cold misses, evictions
 };
 
 __device__ __forceinline__ CacheRegs load_cache_regs(const LayerState *st, int lane, int N, int C) {
@@ -149,13 +152,13 @@ __device__ __forceinline__ CacheRegs load_cache_regs(const LayerState *st, int l
   cr.ever_used = st->ever_used;
   cr.dsum_prev = st->delta_sum;
   cr.t = st->count;
+  cr.counter = lane < 5 ? (&st->selections)[lane] : 0;
   return cr;
 }
 
 // Everything after the logits (Eq. 3 softmax, Eq. 10, Eq. 9, Eq. 2, Eq. 4, Sec. 4.2), run by one wavefront.
 __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_s, const CacheRegs &cr, LayerState *st,
-                                           moe_route_out_t *out_dev, moe_route_out_t *out_host, uint32_t *rec_s,
-                                           int lane) {
+                                           moe_route_out_t *out_dev, HostNote *note, uint32_t *rec_s, int lane) {
   const int N = p.n_experts, K = p.top_k, C = p.capacity;
   int my_slot = cr.my_slot, slot_exp = cr.slot_exp;
   const int t = cr.t;
@@ -191,15 +194,32 @@ __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_
   }
   const bool top_j = (topj_mask >> lane) & 1;
 
-  int rank_p;    // position in the altered ranking r'
+  int rank_p;    // position in the altered ranking r' (exact for the first K positions, >= K otherwise)
   float zp = z;  // altered logits (Cache-Prior only)
+  float margin = INFINITY;  // between the K-th and (K+1)-th altered logit (tie logging)
   if (p.route_mode == MOE_ROUTE_CACHE_PRIOR) {
     const float bias = p.lambda * delta;               // one rounding
     if (active && (resident || top_j)) zp = z + bias;  // one rounding (Eq. 9)
-    rank_p = rank_of(rank_key(zp, lane, active), N);
+    // only the head of r' matters: K (+1 for the margin) rounds of arg-max, ties -> lower index
+    rank_p = N;
+    uint64_t taken = 0;
+    float kth = 0.f;
+    const int rounds = K < N ? K + 1 : K;
+    for (int k = 0; k < rounds; ++k) {
+      const bool cand = active && !((taken >> lane) & 1);
+      const float m = wave_max(cand ? zp : -INFINITY);
+      const int l = (int)__builtin_ctzll(ballot(cand && zp == m));
+      if (k < K) {
+        taken |= 1ull << l;
+        if (lane == l) rank_p = k;
+        kth = m;
+      } else {
+        margin = kth - m;
+      }
+    }
   } else {
     // Max-Rank (Eq. 6-7) / Cumsum-Threshold (Eq. 8): two promote() passes = a three-class stable partition
-    const int rank_z = rank_of(rank_key(z, lane, active), N);
+    const int rank_z = rank_of(rank_key(z, lane, active));
     int M = p.max_rank;
     if (p.route_mode == MOE_ROUTE_CUMSUM) {
       // mass ranked before me; M = number of experts whose preceding mass is still below p
@@ -212,21 +232,13 @@ __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_
     }
     const int cls = top_j ? 0 : ((resident && rank_z < M) ? 1 : 2);
     const uint64_t key = active ? (((uint64_t)(2 - cls) << 32) | (uint32_t)(63 - rank_z)) : 0ull;
-    rank_p = rank_of(key, N);
+    rank_p = rank_of(key);
   }
   const bool sel = active && rank_p < K;
   const uint64_t sel_mask = ballot(sel);
   const bool miss = sel && !resident;
   const uint64_t miss_mask = ballot(miss);
   const int n_miss = (int)__builtin_popcountll(miss_mask);
-
-  // margin between the K-th and (K+1)-th altered logit (tie logging)
-  float margin = INFINITY;
-  if (K < N && p.route_mode == MOE_ROUTE_CACHE_PRIOR) {
-    const float a = readlane_f(zp, (int)__builtin_ctzll(ballot(active && rank_p == K - 1)));
-    const float b = readlane_f(zp, (int)__builtin_ctzll(ballot(active && rank_p == K)));
-    margin = a - b;
-  }
 
   // expert weights from the unmodified logits (Sec. 3.3), optional renormalisation (Sec. 2.1)
   if (p.renormalize) {
@@ -275,6 +287,26 @@ __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_
     ever_used |= 1ull << s;
   }
 
+  // ---- what the host needs (experts, slots, miss flags in selection order): three tagged 8-byte words ----
+  // stored to mapped host memory as early as possible, so the trip over the host link overlaps the rest
+  uint32_t lo = 0, hi = 0, mm = 0;
+  uint64_t ew = 0, sw = 0;
+  for (uint64_t m = sel_mask; m; m &= m - 1) {
+    const int e = (int)__builtin_ctzll(m);
+    const int k = readlane_i(rank_p, e);
+    const uint32_t s8 = (uint32_t)readlane_i(my_slot, e) & 0xffu;
+    if (k < 4) lo |= s8 << (8 * k); else hi |= s8 << (8 * (k - 4));
+    mm |= (uint32_t)((miss_mask >> e) & 1) << k;
+    ew |= (uint64_t)e << (16 + 6 * k);
+    sw |= (uint64_t)(s8 & 63u) << (16 + 6 * k);
+  }
+  if (lane < 3) {
+    const uint64_t tag = p.seq & 0xffffu;
+    const uint64_t w0 = (uint64_t)p.seq | ((uint64_t)n_miss << 32) | ((uint64_t)mm << 40);
+    const uint64_t v = lane == 0 ? w0 : (tag | (lane == 1 ? ew : sw));
+    __hip_atomic_store(&note->w[lane], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+  }
+
   // ---- state back to device memory ------------------------------------------------------------
   if (active) {
     st->expert_slot[lane] = my_slot;
@@ -285,14 +317,13 @@ __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_
     st->ever_used = ever_used;
     st->delta_sum = dsum;
     st->count = cnt;
-    st->selections += K;
-    st->hits += K - n_miss;
-    st->misses += n_miss;
-    st->cold_misses += cold;
-    st->evictions += evictions;
+  }
+  if (lane < 5) {
+    const int inc = lane == 0 ? K : lane == 1 ? K - n_miss : lane == 2 ? n_miss : lane == 3 ? cold : evictions;
+    (&st->selections)[lane] = cr.counter + inc;
   }
 
-  // ---- decision record: assemble in LDS, copy out in 16-byte chunks -----------------------------
+  // ---- full decision record in device memory: assembled in LDS, copied out in 16-byte chunks ----
   rec_s[lane] = 0;
   if (lane + 64 < kRecWords) rec_s[lane + 64] = 0;
   __builtin_amdgcn_wave_barrier();
@@ -307,24 +338,12 @@ __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_
     rec_s[W_MISS + k] = miss ? 1u : 0u;
     rec_s[W_EVICT + k] = (uint32_t)my_evicted;
   }
-  // compact copy for the expert kernels: slots 8 bits each in selection order, miss flags as a mask
-  {
-    uint32_t lo = 0, hi = 0, mm = 0;
-    for (uint64_t m = sel_mask; m; m &= m - 1) {
-      const int e = (int)__builtin_ctzll(m);
-      const int k = readlane_i(rank_p, e);
-      const uint32_t s8 = (uint32_t)readlane_i(my_slot, e) & 0xffu;
-      if (k < 4) lo |= s8 << (8 * k); else hi |= s8 << (8 * (k - 4));
-      mm |= (uint32_t)((miss_mask >> e) & 1) << k;
-    }
-    if (lane == 0) {
-      rec_s[W_SEQ] = p.seq;
-      rec_s[W_SEQ + 1] = lo;
-      rec_s[W_SEQ + 2] = hi;
-      rec_s[W_SEQ + 3] = mm;
-    }
-  }
   if (lane == 0) {
+    // compact copy for the expert kernels: slots 8 bits each in selection order, miss flags as a mask
+    rec_s[W_SEQ] = p.seq;
+    rec_s[W_SEQ + 1] = lo;
+    rec_s[W_SEQ + 2] = hi;
+    rec_s[W_SEQ + 3] = mm;
     rec_s[W_NMISS] = (uint32_t)n_miss;
     rec_s[W_TOKEN] = (uint32_t)t;
     rec_s[W_DELTA] = __float_as_uint(delta);
@@ -333,22 +352,12 @@ __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-  constexpr int kPayloadChunks = W_SEQ / 4;  // everything before the completion tag
-  if (lane <= kPayloadChunks) {  // the device copy includes the last chunk (tag + compact fields)
-    const u32x4 v = reinterpret_cast<const u32x4 *>(rec_s)[lane];
-    reinterpret_cast<u32x4 *>(out_dev)[lane] = v;
-    if (lane < kPayloadChunks) reinterpret_cast<u32x4 *>(out_host)[lane] = v;
-  }
-  __threadfence_system();
-  __builtin_amdgcn_wave_barrier();
-  if (lane == 0) {
-    __hip_atomic_store(&out_host->seq, p.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
-  }
+  if (lane < kRecWords / 4) reinterpret_cast<u32x4 *>(out_dev)[lane] = reinterpret_cast<const u32x4 *>(rec_s)[lane];
 }
 
 __global__ __launch_bounds__(1024) void route_kernel(RouteParams p, const void *gate_w, const void *x,
                                                      const float *logits_in, LayerState *st,
-                                                     moe_route_out_t *out_dev, moe_route_out_t *out_host) {
+                                                     moe_route_out_t *out_dev, HostNote *note) {
   __shared__ float z_s[MOE_MAX_EXPERTS];
   __shared__ __attribute__((aligned(16))) uint32_t rec_s[kRecWords];
   const int tid = threadIdx.x, lane = tid & 63;
@@ -366,7 +375,7 @@ __global__ __launch_bounds__(1024) void route_kernel(RouteParams p, const void *
   }
   __syncthreads();
   if (wave != 0) return;
-  route_wave(p, z_s, cr, st, out_dev, out_host, rec_s, lane);
+  route_wave(p, z_s, cr, st, out_dev, note, rec_s, lane);
 }
 
 // Gate rows of one wavefront held in registers: loaded before x exists, used once x is in LDS.
@@ -418,7 +427,7 @@ __device__ __forceinline__ void gate_dot(const GateRegs<R, CH> &g, const uint32_
 template <int CH>
 __global__ __launch_bounds__(1024) void fused_route_kernel(RouteParams p, FusedParams f, const void *gate_w,
                                                            LayerState *st, moe_route_out_t *out_dev,
-                                                           moe_route_out_t *out_host) {
+                                                           HostNote *note) {
   __shared__ float z_s[MOE_MAX_EXPERTS];
   __shared__ __attribute__((aligned(16))) uint32_t rec_s[kRecWords];
   __shared__ float part_s[16];
@@ -431,25 +440,36 @@ __global__ __launch_bounds__(1024) void fused_route_kernel(RouteParams p, FusedP
   const int rpw = (N + n_waves - 1) / n_waves;  // rows per wavefront (<= 4 by the launch shape)
   const int row0 = wave * rpw, nrows = min(R, N - row0);
 
-  GateRegs<R, (CH > 0 ? CH : 1)> greg;
-  if (CH > 0 && nrows > 0) gate_prefetch<R, (CH > 0 ? CH : 1)>(gate_w, row0, nrows, lane, greg);
+  // ---- glue: each thread owns columns tid, tid + 1024, ... (kept in registers between the two sweeps) ----
+  // its loads are issued first: loads complete in order, and the glue must not wait for the gate rows
+  constexpr int kMaxPer = kFusedMaxHidden / 1024;
+  float hv[kMaxPer], yv[kMaxPer], av[kMaxPer];
+  const bool with_y = f.y != nullptr && f.carry;
+#pragma unroll
+  for (int i = 0; i < kMaxPer; ++i) {
+    const int j = tid + i * 1024;
+    hv[i] = yv[i] = av[i] = 0.f;
+    if (j < d) {
+      if (f.carry) hv[i] = f.h[j];
+      if (with_y)
+        yv[i] = bf16 ? __uint_as_float((uint32_t) static_cast<const uint16_t *>(f.y)[j] << 16)
+                     : static_cast<const float *>(f.y)[j];
+      if (f.a != nullptr) av[i] = f.a[j];
+    }
+  }
   CacheRegs cr{};
   if (wave == 0) cr = load_cache_regs(st, lane, N, p.capacity);
+  GateRegs<R, (CH > 0 ? CH : 1)> greg;
+  if (CH > 0 && nrows > 0) gate_prefetch<R, (CH > 0 ? CH : 1)>(gate_w, row0, nrows, lane, greg);
 
-  // ---- glue: each thread owns columns tid, tid + 1024, ... (kept in registers between the two sweeps) ----
-  constexpr int kMaxPer = kFusedMaxHidden / 1024;
-  float hv[kMaxPer];
   float ss = 0.f;
 #pragma unroll
   for (int i = 0; i < kMaxPer; ++i) {
     const int j = tid + i * 1024;
-    hv[i] = 0.f;
     if (j < d) {
-      float v = f.carry ? f.h[j] : 0.f;
-      if (f.y != nullptr && f.carry)
-        v += bf16 ? __uint_as_float((uint32_t) static_cast<const uint16_t *>(f.y)[j] << 16)
-                  : static_cast<const float *>(f.y)[j];
-      if (f.a != nullptr) v = __builtin_fmaf(f.perturb, f.a[j], v);
+      float v = hv[i];
+      if (with_y) v += yv[i];
+      if (f.a != nullptr) v = __builtin_fmaf(f.perturb, av[i], v);
       f.h[j] = v;
       hv[i] = v;
       ss = __builtin_fmaf(v, v, ss);
@@ -491,7 +511,7 @@ __global__ __launch_bounds__(1024) void fused_route_kernel(RouteParams p, FusedP
   }
   __syncthreads();
   if (wave != 0) return;
-  route_wave(p, z_s, cr, st, out_dev, out_host, rec_s, lane);
+  route_wave(p, z_s, cr, st, out_dev, note, rec_s, lane);
 }
 
 __global__ void state_init_kernel(LayerState *state, int n_layers, const int32_t *initial, int n_initial) {
@@ -519,29 +539,29 @@ __global__ void state_init_kernel(LayerState *state, int n_layers, const int32_t
 }  // namespace
 
 hipError_t launch_route(const RouteParams &p, const void *gate_w, const void *x, const float *logits,
-                        LayerState *state, moe_route_out_t *out_dev, moe_route_out_t *out_host_mapped,
+                        LayerState *state, moe_route_out_t *out_dev, HostNote *note_mapped,
                         hipStream_t s) {
   // at most four rows of the gate matrix per wavefront, so that all of a wavefront's loads are in flight at once
   int waves = logits ? 1 : (p.n_experts + 3) / 4;
   if (waves > 16) waves = 16;
   if (waves < 1) waves = 1;
   hipLaunchKernelGGL(route_kernel, dim3(1), dim3(waves * kWave), 0, s, p, gate_w, x, logits, state, out_dev,
-                     out_host_mapped);
+                     note_mapped);
   return hipGetLastError();
 }
 
 hipError_t launch_fused_route(const RouteParams &p, const FusedParams &f, const void *gate_w, LayerState *state,
-                              moe_route_out_t *out_dev, moe_route_out_t *out_host_mapped, hipStream_t s) {
+                              moe_route_out_t *out_dev, HostNote *note_mapped, hipStream_t s) {
   if (p.hidden > kFusedMaxHidden || p.hidden % 8 != 0) return hipErrorInvalidValue;
   // 16 wavefronts, at most four gate rows each (N <= 64)
   const dim3 g(1), b(1024);
   const int vec = p.act_fmt == MOE_A_BF16 ? 8 : 4;
   const int ch = p.hidden % (kWave * vec) == 0 ? p.hidden / (kWave * vec) : 0;
   switch (ch) {
-    case 1: hipLaunchKernelGGL(fused_route_kernel<1>, g, b, 0, s, p, f, gate_w, state, out_dev, out_host_mapped); break;
-    case 2: hipLaunchKernelGGL(fused_route_kernel<2>, g, b, 0, s, p, f, gate_w, state, out_dev, out_host_mapped); break;
-    case 4: hipLaunchKernelGGL(fused_route_kernel<4>, g, b, 0, s, p, f, gate_w, state, out_dev, out_host_mapped); break;
-    default: hipLaunchKernelGGL(fused_route_kernel<0>, g, b, 0, s, p, f, gate_w, state, out_dev, out_host_mapped);
+    case 1: hipLaunchKernelGGL(fused_route_kernel<1>, g, b, 0, s, p, f, gate_w, state, out_dev, note_mapped); break;
+    case 2: hipLaunchKernelGGL(fused_route_kernel<2>, g, b, 0, s, p, f, gate_w, state, out_dev, note_mapped); break;
+    case 4: hipLaunchKernelGGL(fused_route_kernel<4>, g, b, 0, s, p, f, gate_w, state, out_dev, note_mapped); break;
+    default: hipLaunchKernelGGL(fused_route_kernel<0>, g, b, 0, s, p, f, gate_w, state, out_dev, note_mapped);
   }
   return hipGetLastError();
 }
