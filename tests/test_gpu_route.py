@@ -114,6 +114,81 @@ def test_state_errors():
     dec.close()
 
 
+def run_baseline_case(cfg, mode, T, top_j, max_rank=0, cumsum_p=0.0, scale=1.0):
+    """Max-Rank (Eq. 6-7) and Cumsum-Threshold (Eq. 8) re-ranking on the device against the oracle's lists.
+
+    Cumsum-Threshold turns a sum of fp32 softmax weights into the integer M: the device sums in fp32, the oracle
+    in fp64, so a token whose prefix sum lies within 1e-6 of p may take either neighbouring M; both are tried and
+    such tokens are logged.  Everything else is compared exactly.
+    """
+    import paper_2412_00099_amd as pkg
+    from oracle import rerank
+
+    route_mode = {"max_rank": pkg.MOE_ROUTE_MAX_RANK, "cumsum": pkg.MOE_ROUTE_CUMSUM}[mode]
+    store, dec = build(cfg, top_j=top_j, route_mode=route_mode, max_rank=max_rank, cumsum_p=cumsum_p)
+    N, K, C = cfg.n_experts, cfg.top_k, cfg.capacity
+    routers = [routing.CachePriorRouter(N, K, C, 0.0, top_j, cfg.renormalize) for _ in range(cfg.n_layers)]
+    x = torch.zeros(cfg.hidden, dtype=cfg.act_dtype, device=DEV)
+    y = torch.zeros(cfg.hidden, dtype=cfg.act_dtype, device=DEV)
+    zs = [workloads.logits_stream(cfg, T, layer=l, scale=scale) for l in range(cfg.n_layers)]
+    zs_dev = [z.to(DEV) for z in zs]
+    torch.cuda.synchronize()
+    near = 0
+    for t in range(T):
+        for l in range(cfg.n_layers):
+            out = route_fields(dec.route_step(l, logits=zs_dev[l][t]), K)
+            dec.expert_forward(l, x, y)
+            z = zs[l][t].numpy()
+            rt = routers[l]
+            delta = rt.range.update(z)
+            r = routing.ranking(z).tolist()
+            cache = {e for e in range(N) if rt.cache.slot_of[e] >= 0}
+            ctx = f"{mode} token {t} layer {l}"
+            if mode == "max_rank":
+                options = [rerank.max_rank(r, cache, max_rank, top_j)[:K]]
+            else:
+                w = routing.softmax(z)
+                prefix = np.cumsum([w[e] for e in r])
+                m = rerank.cumsum_rank([w[e] for e in r], cumsum_p)
+                assert m == min(int(np.searchsorted(prefix, cumsum_p, side="left")) + 1, N), ctx
+                ms = {m} | {i + 1 + d for i in range(N) if abs(prefix[i] - cumsum_p) < 1e-6 for d in (0, 1) if i + 1 + d <= N}
+                options = [rerank.max_rank(r, cache, mm, top_j)[:K] for mm in sorted(ms, key=lambda v: v != m)]
+            if out["sel"] != options[0]:
+                assert out["sel"] in options, (ctx, out["sel"], options)
+                near += 1
+                print(f"  {ctx}: prefix sum within 1e-6 of p, device took the neighbouring M", flush=True)
+            ref = rt.commit(z, np.asarray(out["sel"]), delta=delta)
+            assert out["slot"] == ref.slot and out["miss"] == ref.miss and out["evicted"] == ref.evicted, ctx
+            assert out["delta"] == ref.delta and out["token"] == t, ctx
+            np.testing.assert_allclose(out["weight"], ref.weight, rtol=2e-6, err_msg=ctx)
+    assert near <= max(1, T * cfg.n_layers // 100)
+    for l in range(cfg.n_layers):
+        check_tables(dec, l, routers[l], N, C)
+    dec.close()
+    return routers
+
+
+@pytest.mark.parametrize("M,J", [(0, 0), (8, 0), (16, 1), (60, 2), (4, 4)])
+def test_max_rank_mode_bit_exact(M, J):
+    print(f"case max-rank M={M} J={J}", flush=True)
+    cfg = TINY.with_(n_experts=60, top_k=4, capacity=30, n_layers=2, seed=311)
+    routers = run_baseline_case(cfg, "max_rank", 200, J, max_rank=M, scale=1.5)
+    if M == 0 or J == cfg.top_k:
+        # nothing is promoted past the router's own top-K: plain LRU caching of the original routing
+        ref = [routing.CachePriorRouter(60, 4, 30, 0.0) for _ in range(2)]
+        for l in range(2):
+            for z in workloads.logits_stream(cfg, 200, layer=l, scale=1.5).numpy():
+                ref[l].step(z)
+            assert ref[l].stats.misses == routers[l].stats.misses
+
+
+@pytest.mark.parametrize("p,J", [(0.0, 0), (0.3, 0), (0.7, 1), (0.95, 2), (1.5, 0)])
+def test_cumsum_threshold_mode(p, J):
+    print(f"case cumsum p={p} J={J}", flush=True)
+    cfg = TINY.with_(n_experts=60, top_k=4, capacity=30, n_layers=2, seed=312)
+    run_baseline_case(cfg, "cumsum", 200, J, cumsum_p=p, scale=1.5)
+
+
 def free_run(cfg, lam, T, top_j=0, check_outputs_every=1, tol=None, deferred=False):
     """x-in mode: the device computes the router GEMV; tie protocol on disagreement."""
     from oracle import experts as oexp
