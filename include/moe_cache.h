@@ -96,6 +96,8 @@ typedef struct moe_route_out {
 
 typedef struct moe_cache_stats {
   int64_t tokens, selections, hits, misses, cold_misses, evictions, bytes_filled;
+  int64_t lifetime_sum; /* over the evictions: tokens between an expert's load and its eviction; divided by
+                         * `evictions` it is the average cache lifetime of Sec. 4.4 / Table 2 */
 } moe_cache_stats_t;
 
 /* Per-layer tables, for checking against a reference (host struct). */
@@ -166,6 +168,16 @@ int moe_cache_last_route(moe_cache_t *ctx, int32_t layer, moe_route_out_t *out_h
 int moe_cache_stats(moe_cache_t *ctx, int32_t layer, moe_cache_stats_t *out_host);
 /* Slot table, stamps and Delta accumulator of one layer.  Synchronises compute_stream. */
 int moe_cache_tables(moe_cache_t *ctx, int32_t layer, moe_cache_tables_t *out_host);
+/* Save / restore the cache state of one layer (slot tables, stamps, Delta_avg accumulator of Eq. 10, counters of
+ * Eq. 4) as an opaque host blob, e.g. to resume a decode or to start a comparison from a recorded state.
+ * moe_cache_snapshot: *bytes holds the size of buf_host on entry and the size of the blob on return; with
+ * buf_host NULL only the size is returned.  MOE_EINVAL if the buffer is too small.  Synchronises compute_stream.
+ * moe_cache_restore: checks that the blob was taken from a context of the same n_experts / capacity / top_k and
+ * that its tables are consistent (MOE_EINVAL otherwise, nothing changed), then installs it and copies every
+ * resident expert's blob from the host tier into its slot, synchronously.  MOE_ESTATE while a routing step of
+ * the layer or an expert output is pending. */
+int moe_cache_snapshot(moe_cache_t *ctx, int32_t layer, void *buf_host, size_t *bytes);
+int moe_cache_restore(moe_cache_t *ctx, int32_t layer, const void *buf_host, size_t bytes);
 /* Change lambda (and for the baselines M / p) between steps. */
 int moe_cache_set_lambda(moe_cache_t *ctx, float lambda);
 int moe_cache_set_baseline(moe_cache_t *ctx, int32_t route_mode, int32_t max_rank, float cumsum_p);
@@ -178,6 +190,22 @@ int moe_cache_reset(moe_cache_t *ctx);
  * carry = 0 starts a new token (h is overwritten). */
 int moe_residual_rmsnorm(float *h_dev, const void *y_dev, const float *a_dev, float perturb, int32_t carry,
                          void *x_dev, int32_t hidden, int32_t act_fmt, void *stream);
+
+/* Offline analysis of a recorded selection trace; host memory only, no GPU work, no context.
+ * trace[t*top_k + k]: the experts one layer selected at token t (distinct, each in 0..n_experts-1), in the order
+ * the cache touches them (descending router weight, Sec. 4.2).  Misses are counted per token against the cache
+ * before the token (Eq. 4), starting from `initial` (n_initial experts, may be NULL/0).
+ *   MOE_POLICY_LRU       least-recently-used eviction as in Sec. 4.2; any capacity in 1..n_experts (below top_k
+ *                        only the most recently touched experts of a token stay: the cache-size sweep of Sec. 4.6)
+ *   MOE_POLICY_FARTHEST  evict the resident expert, not needed by the current token, whose next use is farthest
+ *                        (never again first, ties to the lowest id): the optimal-eviction bound of Sec. 4.6;
+ *                        needs capacity >= top_k
+ * Outputs: *misses; optionally (may be NULL) *lifetime_sum and *evictions as in moe_cache_stats_t.
+ * MOE_EINVAL on NULL/out-of-range arguments or a token with repeated experts. */
+enum { MOE_POLICY_LRU = 0, MOE_POLICY_FARTHEST = 1 };
+int moe_trace_misses(const int32_t *trace, int64_t n_tokens, int32_t top_k, int32_t n_experts, int32_t capacity,
+                     int32_t policy, const int32_t *initial, int32_t n_initial, int64_t *misses,
+                     int64_t *lifetime_sum, int64_t *evictions);
 
 /* Average duration in microseconds of the expert-GEMV launches that covered a whole layer (no expert missing)
  * since the last call with reset != 0, and their count; measured with start/stop events attached to the

@@ -35,6 +35,25 @@ def lru_list_misses(trace, capacity: int, initial=()):
     return misses, order
 
 
+def lru_list_lifetimes(trace, capacity: int, initial=()):
+    """Stays in memory under the recency-list LRU: (sum, count) of the lengths in tokens of the stays that ended
+    by eviction, and the still-open stays as {expert: token it was loaded at} (Sec. 4.4, Table 2 'lifetime')."""
+    order = list(initial)
+    born = {e: 0 for e in order}
+    total = count = 0
+    for t, token in enumerate(trace):
+        token = list(token)
+        for e in token:
+            if e not in born:
+                born[e] = t
+        order = [e for e in order if e not in token] + token
+        while len(order) > capacity:
+            old = order.pop(0)
+            total += t - born.pop(old)
+            count += 1
+    return total, count, born
+
+
 def belady_misses(trace, capacity: int, initial=()):
     """Misses under farthest-next-use eviction (never-again first; ties -> lowest id)."""
     trace = [list(tok) for tok in trace]

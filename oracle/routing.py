@@ -100,10 +100,16 @@ class CacheStats:
     misses: int = 0
     cold_misses: int = 0
     evictions: int = 0
+    lifetime_sum: int = 0  # over evicted experts: tokens between being loaded and being evicted
 
     @property
     def miss_rate(self) -> float:
         return self.misses / max(self.selections, 1)
+
+    @property
+    def mean_lifetime(self) -> float:
+        """Average number of time steps an expert stays in memory (Sec. 4.4, Table 2), over completed stays."""
+        return self.lifetime_sum / max(self.evictions, 1)
 
 
 class ExpertCache:
@@ -115,6 +121,7 @@ class ExpertCache:
         self.expert_in = [-1] * capacity  # slot -> expert
         self.stamp = [0] * n_experts  # valid while resident
         self.ever_used = [False] * capacity
+        self.born = [0] * n_experts  # token index at which the expert was loaded (initial residents: 0)
         self.stats = CacheStats()
         initial = list(initial)
         assert len(initial) <= capacity and len(set(initial)) == len(initial)
@@ -164,6 +171,8 @@ class ExpertCache:
                 self.slot_of[old] = -1
                 evicted[e] = old
                 self.stats.evictions += 1
+                self.stats.lifetime_sum += t - self.born[old]
+            self.born[e] = t
             self.expert_in[s] = e
             self.slot_of[e] = s
             self.ever_used[s] = True

@@ -20,6 +20,7 @@ MOE_W_FP32, MOE_W_BF16, MOE_W_INT8_PC, MOE_W_INT4_G128 = 0, 1, 2, 3
 MOE_A_FP32, MOE_A_BF16 = 0, 1
 MOE_DELTA_RUNNING_MEAN, MOE_DELTA_FIXED = 0, 1
 MOE_ROUTE_CACHE_PRIOR, MOE_ROUTE_MAX_RANK, MOE_ROUTE_CUMSUM = 0, 1, 2
+MOE_POLICY_LRU, MOE_POLICY_FARTHEST = 0, 1
 
 WEIGHT_FMT = {"fp32": MOE_W_FP32, "bf16": MOE_W_BF16, "int8": MOE_W_INT8_PC, "int4": MOE_W_INT4_G128}
 ACT_FMT = {"fp32": MOE_A_FP32, "bf16": MOE_A_BF16}
@@ -82,7 +83,8 @@ class moe_route_out_t(C.Structure):
 class moe_cache_stats_t(C.Structure):
     _fields_ = [
         (n, C.c_int64)
-        for n in ("tokens", "selections", "hits", "misses", "cold_misses", "evictions", "bytes_filled")
+        for n in ("tokens", "selections", "hits", "misses", "cold_misses", "evictions", "bytes_filled",
+                  "lifetime_sum")
     ]
 
 
@@ -117,6 +119,13 @@ lib.moe_cache_stats.restype = C.c_int
 lib.moe_cache_stats.argtypes = [_vp, C.c_int32, C.POINTER(moe_cache_stats_t)]
 lib.moe_cache_tables.restype = C.c_int
 lib.moe_cache_tables.argtypes = [_vp, C.c_int32, C.POINTER(moe_cache_tables_t)]
+lib.moe_cache_snapshot.restype = C.c_int
+lib.moe_cache_snapshot.argtypes = [_vp, C.c_int32, _vp, C.POINTER(C.c_size_t)]
+lib.moe_cache_restore.restype = C.c_int
+lib.moe_cache_restore.argtypes = [_vp, C.c_int32, _vp, C.c_size_t]
+lib.moe_trace_misses.restype = C.c_int
+lib.moe_trace_misses.argtypes = [_vp, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, C.c_int32,
+                                 C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
 lib.moe_cache_set_lambda.restype = C.c_int
 lib.moe_cache_set_lambda.argtypes = [_vp, C.c_float]
 lib.moe_cache_set_baseline.restype = C.c_int
@@ -132,7 +141,8 @@ lib.moe_last_error.argtypes = []
 
 EXPORTS = [
     "moe_blob_bytes", "moe_pack_expert", "moe_cache_init", "moe_cache_destroy", "moe_route_step", "moe_stack_route_step",
-    "moe_expert_forward", "moe_cache_last_route", "moe_cache_stats", "moe_cache_tables", "moe_cache_set_lambda",
+    "moe_expert_forward", "moe_cache_last_route", "moe_cache_stats", "moe_cache_tables", "moe_cache_snapshot",
+    "moe_cache_restore", "moe_trace_misses", "moe_cache_set_lambda",
     "moe_cache_set_baseline", "moe_cache_reset", "moe_residual_rmsnorm", "moe_cache_profile", "moe_last_error",
 ]
 
@@ -213,6 +223,33 @@ def moe_cache_tables(ctx, layer: int) -> moe_cache_tables_t:
     out = moe_cache_tables_t()
     _check(lib.moe_cache_tables(ctx, layer, C.byref(out)), "moe_cache_tables")
     return out
+
+
+def moe_cache_snapshot(ctx, layer: int) -> bytes:
+    n = C.c_size_t(0)
+    _check(lib.moe_cache_snapshot(ctx, layer, None, C.byref(n)), "moe_cache_snapshot")
+    buf = C.create_string_buffer(n.value)
+    _check(lib.moe_cache_snapshot(ctx, layer, buf, C.byref(n)), "moe_cache_snapshot")
+    return buf.raw[: n.value]
+
+
+def moe_cache_restore(ctx, layer: int, blob: bytes) -> None:
+    _check(lib.moe_cache_restore(ctx, layer, blob, len(blob)), "moe_cache_restore")
+
+
+def moe_trace_misses(trace, n_experts: int, capacity: int, policy: int = MOE_POLICY_LRU, initial=()):
+    """trace: int32 array [T, K] (host).  Returns (misses, lifetime_sum, evictions)."""
+    import numpy as np
+
+    tr = np.ascontiguousarray(trace, dtype=np.int32)
+    if tr.ndim != 2:
+        raise ValueError("trace must be [tokens, top_k]")
+    init = np.ascontiguousarray(list(initial), dtype=np.int32)
+    m, life, ev = C.c_int64(), C.c_int64(), C.c_int64()
+    _check(lib.moe_trace_misses(tr.ctypes.data, tr.shape[0], tr.shape[1], n_experts, capacity, policy,
+                                init.ctypes.data if init.size else None, init.size,
+                                C.byref(m), C.byref(life), C.byref(ev)), "moe_trace_misses")
+    return m.value, life.value, ev.value
 
 
 def moe_cache_set_lambda(ctx, lam: float) -> None:

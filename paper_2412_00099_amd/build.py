@@ -31,6 +31,7 @@ SOURCES = {
     "expert_gemv_quant.hip": [],
     "pack.hip": [],
     "moe_cache.hip": [],
+    "trace_sim.hip": [],
 }
 
 

@@ -17,10 +17,11 @@ struct LayerState {
   int32_t expert_slot[MOE_MAX_EXPERTS];  // expert -> slot, -1 = not resident
   int32_t slot_expert[MOE_MAX_EXPERTS];  // slot -> expert, -1 = empty
   int64_t stamp[MOE_MAX_EXPERTS];        // recency stamp per expert (valid while resident)
+  int32_t born[MOE_MAX_EXPERTS];         // token at which the expert was loaded (valid while resident)
   uint64_t ever_used;                    // bit s: slot s has held an expert
   float delta_sum;                       // Eq. 10 accumulator
   int32_t count;                         // tokens routed
-  int64_t selections, hits, misses, cold_misses, evictions;
+  int64_t selections, hits, misses, cold_misses, evictions, lifetime_sum;  // contiguous: updated lane-wise
 };
 
 struct RouteParams {

@@ -478,6 +478,7 @@ int moe_cache_stats(moe_cache_t *c, int32_t layer, moe_cache_stats_t *out) {
     out->misses += st[l].misses;
     out->cold_misses += st[l].cold_misses;
     out->evictions += st[l].evictions;
+    out->lifetime_sum += st[l].lifetime_sum;
     out->bytes_filled += c->bytes_filled[l];
   }
   return MOE_OK;
@@ -494,6 +495,69 @@ int moe_cache_tables(moe_cache_t *c, int32_t layer, moe_cache_tables_t *out) {
   memcpy(out->stamp, st.stamp, sizeof out->stamp);
   out->delta_sum = st.delta_sum;
   out->count = st.count;
+  return MOE_OK;
+}
+
+namespace {
+struct SnapshotHeader {
+  uint32_t magic, version;
+  int32_t n_experts, capacity, top_k, reserved;
+};
+constexpr uint32_t kSnapMagic = 0x43454f4du, kSnapVersion = 1;  // "MOEC"
+constexpr size_t kSnapBytes = sizeof(SnapshotHeader) + sizeof(LayerState);
+}  // namespace
+
+int moe_cache_snapshot(moe_cache_t *c, int32_t layer, void *buf, size_t *bytes) {
+  if (int rc = check_layer(c, layer)) return rc;
+  if (!bytes) return fail(MOE_EINVAL, "bytes is NULL");
+  const size_t have = *bytes;
+  *bytes = kSnapBytes;
+  if (!buf) return MOE_OK;
+  if (have < kSnapBytes) return fail(MOE_EINVAL, "snapshot needs %zu bytes, buffer has %zu", kSnapBytes, have);
+  HIP_TRY(hipStreamSynchronize(c->compute));
+  SnapshotHeader hd{kSnapMagic, kSnapVersion, c->cfg.n_experts, c->cfg.capacity, c->cfg.top_k, 0};
+  memcpy(buf, &hd, sizeof hd);
+  HIP_TRY(hipMemcpy(static_cast<uint8_t *>(buf) + sizeof hd, c->d_state + layer, sizeof(LayerState),
+                    hipMemcpyDeviceToHost));
+  return MOE_OK;
+}
+
+int moe_cache_restore(moe_cache_t *c, int32_t layer, const void *buf, size_t bytes) {
+  if (int rc = check_layer(c, layer)) return rc;
+  if (!buf || bytes < kSnapBytes) return fail(MOE_EINVAL, "snapshot buffer is NULL or shorter than %zu bytes", kSnapBytes);
+  if (c->routed[layer] || c->pending_rows) return fail(MOE_ESTATE, "layer %d: a routing step or an expert output is pending", layer);
+  const moe_cache_config_t &g = c->cfg;
+  SnapshotHeader hd;
+  memcpy(&hd, buf, sizeof hd);
+  if (hd.magic != kSnapMagic || hd.version != kSnapVersion) return fail(MOE_EINVAL, "not a cache snapshot");
+  if (hd.n_experts != g.n_experts || hd.capacity != g.capacity || hd.top_k != g.top_k)
+    return fail(MOE_EINVAL, "snapshot is for n_experts=%d capacity=%d top_k=%d", hd.n_experts, hd.capacity, hd.top_k);
+  LayerState st;
+  memcpy(&st, static_cast<const uint8_t *>(buf) + sizeof hd, sizeof st);
+  // the two tables must describe one partial bijection expert <-> slot inside the configured ranges
+  for (int e = 0; e < MOE_MAX_EXPERTS; ++e) {
+    const int s = st.expert_slot[e];
+    const bool ok = e < g.n_experts ? (s == -1 || (s >= 0 && s < g.capacity && st.slot_expert[s] == e)) : s == -1;
+    if (!ok) return fail(MOE_EINVAL, "snapshot tables inconsistent at expert %d", e);
+  }
+  for (int s = 0; s < MOE_MAX_EXPERTS; ++s) {
+    const int e = st.slot_expert[s];
+    const bool ok = s < g.capacity ? (e == -1 || (e >= 0 && e < g.n_experts && st.expert_slot[e] == s &&
+                                                   ((st.ever_used >> s) & 1)))
+                                   : e == -1;
+    if (!ok) return fail(MOE_EINVAL, "snapshot tables inconsistent at slot %d", s);
+  }
+  if (st.count < 0 || st.selections < 0 || st.misses < 0) return fail(MOE_EINVAL, "snapshot counters negative");
+  HIP_TRY(hipStreamSynchronize(c->compute));
+  HIP_TRY(hipStreamSynchronize(c->copy));
+  HIP_TRY(hipMemcpy(c->d_state + layer, &st, sizeof st, hipMemcpyHostToDevice));
+  const size_t slot_bytes = (size_t)c->slot_layout.total;
+  for (int s = 0; s < g.capacity; ++s) {
+    const int e = st.slot_expert[s];
+    if (e < 0) continue;
+    HIP_TRY(hipMemcpy(static_cast<uint8_t *>(c->slot_pool[layer]) + (size_t)s * slot_bytes,
+                      c->host_blob[(size_t)layer * g.n_experts + e], slot_bytes, hipMemcpyHostToDevice));
+  }
   return MOE_OK;
 }
 

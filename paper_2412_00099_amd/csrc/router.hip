@@ -137,22 +137,23 @@ __device__ __forceinline__ void gate_gemv(const void *gate_w, const void *x, con
 
 // Cache state of one layer as held by wavefront 0 (lane e: expert e, lane s: slot s).
 struct CacheRegs {
-  int my_slot, slot_exp, t;
+  int my_slot, slot_exp, t, born;
   int64_t stamp;
   uint64_t ever_used;
   float dsum_prev;
-  int64_t counter;  // lanes 0..4: selections, hits, misses, cold misses, evictions
+  int64_t counter;  // lanes 0..5: selections, hits, misses, cold misses, evictions, lifetime sum
 };
 
 __device__ __forceinline__ CacheRegs load_cache_regs(const LayerState *st, int lane, int N, int C) {
   CacheRegs cr;
   cr.my_slot = lane < N ? st->expert_slot[lane] : -1;
   cr.stamp = lane < N ? st->stamp[lane] : 0;
+  cr.born = lane < N ? st->born[lane] : 0;
   cr.slot_exp = lane < C ? st->slot_expert[lane] : -1;
   cr.ever_used = st->ever_used;
   cr.dsum_prev = st->delta_sum;
   cr.t = st->count;
-  cr.counter = lane < 5 ? (&st->selections)[lane] : 0;
+  cr.counter = lane < 6 ? (&st->selections)[lane] : 0;
   return cr;
 }
 
@@ -265,7 +266,8 @@ __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_
       vrank += (int64_t)readlane_u64((uint64_t)stamp, (int)__builtin_ctzll(m)) < stamp;
   }
   int my_evicted = -1;
-  int cold = 0, evictions = 0;
+  int born = cr.born;
+  int cold = 0, evictions = 0, lifetime = 0;  // lifetime: tokens the evicted experts had stayed (Sec. 4.4)
   for (int q = 0; q < n_miss; ++q) {
     const int ml = (int)__builtin_ctzll(ballot(miss && ordinal == q));
     int s, victim = -1;
@@ -276,12 +278,14 @@ __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_
     } else {
       victim = (int)__builtin_ctzll(ballot(eligible && vrank == q - n_empty));
       s = readlane_i(my_slot, victim);
+      lifetime += t - readlane_i(born, victim);
       if (lane == victim) my_slot = -1;
       ++evictions;
     }
     if (lane == ml) {
       my_slot = s;
       my_evicted = victim;
+      born = t;
     }
     if (lane == s) slot_exp = ml;
     ever_used |= 1ull << s;
@@ -311,6 +315,7 @@ __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_
   if (active) {
     st->expert_slot[lane] = my_slot;
     st->stamp[lane] = stamp;
+    st->born[lane] = born;
   }
   if (lane < C) st->slot_expert[lane] = slot_exp;
   if (lane == 0) {
@@ -318,8 +323,9 @@ __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_
     st->delta_sum = dsum;
     st->count = cnt;
   }
-  if (lane < 5) {
-    const int inc = lane == 0 ? K : lane == 1 ? K - n_miss : lane == 2 ? n_miss : lane == 3 ? cold : evictions;
+  if (lane < 6) {
+    const int inc = lane == 0 ? K : lane == 1 ? K - n_miss : lane == 2 ? n_miss : lane == 3 ? cold
+                  : lane == 4 ? evictions : lifetime;
     (&st->selections)[lane] = cr.counter + inc;
   }
 
@@ -521,6 +527,7 @@ __global__ void state_init_kernel(LayerState *state, int n_layers, const int32_t
   st->expert_slot[lane] = -1;
   st->slot_expert[lane] = -1;
   st->stamp[lane] = 0;
+  st->born[lane] = 0;
   __syncthreads();
   if (lane < n_initial) {
     const int e = initial[layer * n_initial + lane];
@@ -532,7 +539,7 @@ __global__ void state_init_kernel(LayerState *state, int n_layers, const int32_t
     st->ever_used = n_initial >= 64 ? ~0ull : ((1ull << n_initial) - 1ull);
     st->delta_sum = 0.f;
     st->count = 0;
-    st->selections = st->hits = st->misses = st->cold_misses = st->evictions = 0;
+    st->selections = st->hits = st->misses = st->cold_misses = st->evictions = st->lifetime_sum = 0;
   }
 }
 

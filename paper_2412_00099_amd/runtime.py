@@ -147,6 +147,12 @@ class MoEDecoder:
     def tables(self, layer):
         return B.moe_cache_tables(self.ctx, layer)
 
+    def snapshot(self, layer) -> bytes:
+        return B.moe_cache_snapshot(self.ctx, layer)
+
+    def restore(self, layer, blob: bytes):
+        B.moe_cache_restore(self.ctx, layer, blob)
+
     def set_lambda(self, lam):
         B.moe_cache_set_lambda(self.ctx, lam)
 

@@ -90,5 +90,5 @@ def check_tables(dec, layer, router, n_experts, capacity):
     assert t.count == router.range.count
     s = dec.stats(layer)
     o = router.stats
-    assert (s.tokens, s.selections, s.hits, s.misses, s.cold_misses, s.evictions) == (
-        o.tokens, o.selections, o.hits, o.misses, o.cold_misses, o.evictions)
+    assert (s.tokens, s.selections, s.hits, s.misses, s.cold_misses, s.evictions, s.lifetime_sum) == (
+        o.tokens, o.selections, o.hits, o.misses, o.cold_misses, o.evictions, o.lifetime_sum)

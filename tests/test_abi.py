@@ -31,7 +31,7 @@ def test_every_declared_symbol_is_exported(B):
 
 def test_struct_sizes_match_header(B):
     assert C.sizeof(B.moe_route_out_t) == 4 * (5 * 8 + 4 + 64 + 4)
-    assert C.sizeof(B.moe_cache_stats_t) == 56
+    assert C.sizeof(B.moe_cache_stats_t) == 64
     assert C.sizeof(B.moe_cache_tables_t) == 64 * 4 * 2 + 64 * 8 + 8
     assert C.sizeof(B.moe_cache_config_t) == 18 * 4 + 16
 
@@ -113,3 +113,68 @@ def test_null_context_calls_fail_cleanly(B):
     assert B.lib.moe_pack_expert(B.MOE_W_BF16, 2048, 64, None, None, None, None, None, None, None, None) == B.MOE_EINVAL
     assert B.lib.moe_residual_rmsnorm(None, None, None, 0.5, 1, None, 256, 0, None) == B.MOE_EINVAL
     B.lib.moe_cache_destroy(None)
+
+
+# ---- offline trace analysis (host code of the library, no GPU): against the oracle's eviction references ----
+
+
+def _random_traces(seed, n):
+    import numpy as np
+
+    r = np.random.default_rng(seed)
+    for _ in range(n):
+        N = int(r.integers(2, 12))
+        K = int(r.integers(1, min(4, N) + 1))
+        T = int(r.integers(0, 40))
+        # skewed popularity so that re-use happens
+        p = r.dirichlet(np.ones(N) * 0.7)
+        trace = np.array([r.choice(N, size=K, replace=False, p=p) for _ in range(T)], np.int32).reshape(T, K)
+        yield r, N, K, T, trace
+
+
+def test_trace_lru_matches_recency_list_oracle(B):
+    from oracle import eviction
+
+    for r, N, K, T, trace in _random_traces(3, 300):
+        C_ = int(r.integers(1, N + 1))  # below K too: counting mode of the cache-size sweep
+        n_init = int(r.integers(0, C_ + 1))
+        init = r.permutation(N)[:n_init].tolist()
+        misses, life, ev = B.moe_trace_misses(trace, N, C_, B.MOE_POLICY_LRU, init)
+        ref_m, _ = eviction.lru_list_misses(trace.tolist(), C_, init)
+        ref_life, ref_ev, _ = eviction.lru_list_lifetimes(trace.tolist(), C_, init)
+        assert (misses, life, ev) == (ref_m, ref_life, ref_ev), (N, K, C_, T, init)
+
+
+def test_trace_farthest_matches_belady_oracle_and_bounds_lru(B):
+    from oracle import eviction
+
+    for r, N, K, T, trace in _random_traces(4, 300):
+        C_ = int(r.integers(K, N + 1))
+        n_init = int(r.integers(0, C_ + 1))
+        init = r.permutation(N)[:n_init].tolist()
+        opt, _, _ = B.moe_trace_misses(trace, N, C_, B.MOE_POLICY_FARTHEST, init)
+        assert opt == eviction.belady_misses(trace.tolist(), C_, init), (N, K, C_, T, init)
+        lru, _, _ = B.moe_trace_misses(trace, N, C_, B.MOE_POLICY_LRU, init)
+        assert opt <= lru
+    # tiny traces: the count is the true minimum over all eviction choices
+    for r, N, K, T, trace in _random_traces(5, 60):
+        if N > 6 or T > 9:
+            continue
+        C_ = int(r.integers(K, N + 1))
+        opt, _, _ = B.moe_trace_misses(trace, N, C_, B.MOE_POLICY_FARTHEST)
+        assert opt == eviction.min_misses_search(trace.tolist(), C_)
+
+
+def test_trace_misses_rejects_bad_arguments(B):
+    import numpy as np
+
+    ok = np.array([[0, 1], [1, 2]], np.int32)
+    assert B.moe_trace_misses(ok, 3, 2)[0] == 3
+    for bad in (dict(trace=np.array([[0, 0]], np.int32), n_experts=3, capacity=2),      # repeated expert
+                dict(trace=np.array([[0, 3]], np.int32), n_experts=3, capacity=2),      # out of range
+                dict(trace=ok, n_experts=3, capacity=0), dict(trace=ok, n_experts=3, capacity=4),
+                dict(trace=ok, n_experts=3, capacity=1, policy=1),                      # farthest needs C >= K
+                dict(trace=ok, n_experts=3, capacity=2, initial=[1, 1])):
+        with pytest.raises(B.MoEError) as e:
+            B.moe_trace_misses(**bad)
+        assert e.value.code == B.MOE_EINVAL

@@ -227,6 +227,44 @@ def test_lru_stamps_match_recency_list_on_tiny_traces():
         assert sorted(order, key=lambda e: cache.stamp[e]) == order
 
 
+def test_lifetimes_two_ways_and_occupancy_identity():
+    """Cache lifetime (Sec. 4.4, Table 2): the stamp-table cache and the literal recency list agree on the stays
+    that ended, and all stays together (open ones closed at the end) add up to the occupancy summed over tokens."""
+    r = np.random.default_rng(11)
+    for case in range(200):
+        N = int(r.integers(3, 9))
+        K = int(r.integers(1, min(3, N) + 1))
+        C = int(r.integers(K, N + 1))
+        T = int(r.integers(1, 30))
+        n_init = int(r.integers(0, C + 1))
+        init = r.permutation(N)[:n_init].tolist()
+        cache = routing.ExpertCache(N, C, init)
+        trace, occupancy = [], 0
+        for t in range(T):
+            occupancy += len(cache.residents())  # experts in memory while token t is routed
+            z = r.standard_normal(N).astype(np.float32)
+            sel = r.permutation(N)[:K].tolist()
+            trace.append(sorted(sel, key=lambda e: (-float(z[e]), e)))
+            cache.access(sel, z)
+        total, count, open_stays = eviction.lru_list_lifetimes(trace, C, init)
+        assert (cache.stats.lifetime_sum, cache.stats.evictions) == (total, count), case
+        assert open_stays == {e: cache.born[e] for e in cache.residents()}, case
+        # a stay loaded while token b is processed is seen by the cache look-ups of tokens b+1 .. (eviction token):
+        # that count is its lifetime.  Closing the open stays at T counts one look-up too many for each of them,
+        # and an initial resident (loaded "at 0") is also seen by token 0's look-up, one more than its lifetime.
+        closed_at_end = sum(T - b for b in open_stays.values())
+        assert total + closed_at_end == occupancy + len(open_stays) - n_init, case
+
+
+def test_lifetime_known_case():
+    # capacity 2, K = 1: 0 1 2 0 -> 2 evicts 0 (loaded at 0, evicted at 2: lifetime 2), 0 evicts 1 (1 -> 3: 2)
+    total, count, open_stays = eviction.lru_list_lifetimes([[0], [1], [2], [0]], 2)
+    assert (total, count, open_stays) == (4, 2, {2: 2, 0: 3})
+    # a hit renews recency, not the load time: 0 1 0 2 1 -> 2 evicts 1 (1 -> 3), 1 evicts 0 (0 -> 4)
+    total, count, _ = eviction.lru_list_lifetimes([[0], [1], [0], [2], [1]], 2)
+    assert (total, count) == (2 + 4, 2)
+
+
 def test_set_based_vs_sequential_counter_example():
     # cache [a=0 (older), b=1], capacity 2, token selects {c=2 (higher weight), a=0}:
     # Eq. 4 counts 1 miss (a is resident at selection time); a request-at-a-time LRU
