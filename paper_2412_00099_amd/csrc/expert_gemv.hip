@@ -144,13 +144,29 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_kernel(GemvParams p) {
     for (int c = 0; c < LPR; ++c) R.dn[c] = stream_load(q + c * kWave);
   };
 
+  // Pass 0 loads every list entry of the wavefront, also the rare ones whose expert is only being filled (their
+  // arithmetic is skipped): the number of records is then known up front, the steady-state loop below issues
+  // its loads unconditionally, and the compiler can wait for exactly the oldest record in flight instead of for
+  // all loads.  Pass 1 (only the experts just filled) skips the other records without loading them.
+  const bool all = p.pass == 0;
+  int todo = all ? walk.remaining() : 0;  // entries not issued yet (pass 0)
   RecRegs<LPR> ring[DEPTH];
-  bool live[DEPTH];
+  bool live[DEPTH], want[DEPTH];
+  auto advance = [&](int j) {  // next record into ring[j], if there is one
+    if (all) {
+      live[j] = todo > 0;
+      if (live[j]) {
+        --todo;
+        want[j] = walk.step(p);
+      }
+    } else {
+      live[j] = walk.next(p);
+      want[j] = true;
+    }
+    if (live[j]) issue(ring[j]);
+  };
 #pragma unroll
-  for (int j = 0; j < DEPTH; ++j) {
-    live[j] = walk.next(p);
-    if (live[j]) issue(ring[j]);  // weights first: they do not depend on x
-  }
+  for (int j = 0; j < DEPTH; ++j) advance(j);  // weights first: they do not depend on x
 
   // activations: the lane keeps the x entries of its own columns in registers
   float xr[LPR * XW];
@@ -175,14 +191,26 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_kernel(GemvParams p) {
     for (int c = 0; c < LPR; ++c) F::axpy(h, R.dn[c], &y[c * VEC]);
   };
 
-  // ring[0] is always the oldest record in flight: when it is dead, all are
+  // steady state of pass 0: all ring entries live and at least DEPTH more entries to fetch
+  if (all && live[DEPTH - 1]) {
+    while (todo >= DEPTH) {
+#pragma unroll
+      for (int j = 0; j < DEPTH; ++j) {
+        if (want[j]) consume(ring[j]);
+        want[j] = walk.step(p);
+        issue(ring[j]);
+      }
+      todo -= DEPTH;
+    }
+  }
+  // start-up of short lists, tail, and pass 1.  ring[0] is always the oldest record in flight: when it is dead,
+  // all are
   while (live[0]) {
 #pragma unroll
     for (int j = 0; j < DEPTH; ++j) {
       if (live[j]) {
-        consume(ring[j]);
-        live[j] = walk.next(p);
-        if (live[j]) issue(ring[j]);
+        if (want[j]) consume(ring[j]);
+        advance(j);
       }
     }
   }

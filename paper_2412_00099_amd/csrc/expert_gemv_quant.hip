@@ -41,9 +41,42 @@ __device__ __forceinline__ uint32_t pack_f16(float a, float b) {
   f16x2 v = {(_Float16)a, (_Float16)b};
   return __builtin_bit_cast(uint32_t, v);
 }
-__device__ __forceinline__ float x_at(const void *x, int act_fmt, int col) {
-  return act_fmt == MOE_A_BF16 ? __uint_as_float((uint32_t) static_cast<const uint16_t *>(x)[col] << 16)
-                               : static_cast<const float *>(x)[col];
+// N consecutive activations starting at column col (a multiple of 8), in two steps so that other loads can be
+// issued between the fetch (16-byte loads into raw registers) and the conversion to float
+template <int N>
+struct XRaw {
+  u32x4 v[N / 4];
+};
+template <int N>
+__device__ __forceinline__ void fetch_x(const void *x, int act_fmt, int col, XRaw<N> &r) {
+  if (act_fmt == MOE_A_BF16) {
+    const u32x4 *q = reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(x) + col);
+#pragma unroll
+    for (int i = 0; i < N / 8; ++i) r.v[i] = q[i];
+  } else {
+    const u32x4 *q = reinterpret_cast<const u32x4 *>(static_cast<const float *>(x) + col);
+#pragma unroll
+    for (int i = 0; i < N / 4; ++i) r.v[i] = q[i];
+  }
+}
+template <int N>
+__device__ __forceinline__ void unpack_x(const XRaw<N> &r, int act_fmt, float *out) {
+  if (act_fmt == MOE_A_BF16) {
+#pragma unroll
+    for (int i = 0; i < N / 8; ++i) {
+      const u32x4 v = r.v[i];
+      out[8 * i + 0] = bf16_lo(v.x); out[8 * i + 1] = bf16_hi(v.x); out[8 * i + 2] = bf16_lo(v.y);
+      out[8 * i + 3] = bf16_hi(v.y); out[8 * i + 4] = bf16_lo(v.z); out[8 * i + 5] = bf16_hi(v.z);
+      out[8 * i + 6] = bf16_lo(v.w); out[8 * i + 7] = bf16_hi(v.w);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < N / 4; ++i) {
+      const u32x4 v = r.v[i];
+      out[4 * i + 0] = __uint_as_float(v.x); out[4 * i + 1] = __uint_as_float(v.y);
+      out[4 * i + 2] = __uint_as_float(v.z); out[4 * i + 3] = __uint_as_float(v.w);
+    }
+  }
 }
 
 // =================================================================================================
@@ -57,7 +90,9 @@ struct RecI8 {
   int rows;
 };
 
-template <int LPR, int NW, int DEPTH>
+// PRE: the per-column scales of W_down are fetched when the wavefront enters an expert, so that the flush at the
+// next change finds them in registers (costs 2*LPR 16-byte registers per lane)
+template <int LPR, int NW, int DEPTH, bool PRE>
 __global__ __launch_bounds__(NW *kWave) void expert_gemv_int8_kernel(GemvParams p) {
   constexpr int VEC = 16, CPL = LPR * VEC;
   __shared__ float red[kRedFloats];
@@ -87,6 +122,12 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int8_kernel(GemvParams 
     R.su = f16_bits(tail[walk.rows + walk.at]);  // up scales [rows]
   };
 
+  // the activations' few loads go out ahead of the weights (loads complete in order, and the first routed record
+  // has to wait for the routing record); they are converted after the ring has been filled
+  XRaw<VEC> xraw[LPR];
+#pragma unroll
+  for (int c = 0; c < LPR; ++c) fetch_x<VEC>(p.x, p.act_fmt, (c * kWave + lane) * VEC, xraw[c]);
+
   RecI8<LPR> ring[DEPTH];
   bool live[DEPTH];
 #pragma unroll
@@ -99,14 +140,16 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int8_kernel(GemvParams 
   uint32_t xh[CPL / 2];
   float xsum = 0.f;
 #pragma unroll
-  for (int c = 0; c < LPR; ++c)
+  for (int c = 0; c < LPR; ++c) {
+    float xf[VEC];
+    unpack_x<VEC>(xraw[c], p.act_fmt, xf);
 #pragma unroll
     for (int v = 0; v < VEC; v += 2) {
-      const int col = (c * kWave + lane) * VEC + v;
-      const uint32_t pr = pack_f16(x_at(p.x, p.act_fmt, col), x_at(p.x, p.act_fmt, col + 1));
+      const uint32_t pr = pack_f16(xf[v], xf[v + 1]);
       xh[(c * VEC + v) / 2] = pr;
       xsum += f16_lo(pr) + f16_hi(pr);
     }
+  }
   const float xoff = -(1024.f + 128.f) * xsum;
 
   float y[CPL], acc[CPL];
@@ -116,6 +159,17 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int8_kernel(GemvParams 
   const uint8_t *cur_base = nullptr;
   int cur_rows = 0;
 
+  u32x4 dsc[PRE ? 2 * LPR : 1];
+  auto load_scales = [&](const uint8_t *base, int rows) {
+    const uint16_t *sd = reinterpret_cast<const uint16_t *>(base + (int64_t)rows * rec_bytes) + 2 * rows;
+#pragma unroll
+    for (int c = 0; c < (PRE ? LPR : 0); ++c) {
+      const u32x4 *sp = reinterpret_cast<const u32x4 *>(sd + (c * kWave + lane) * VEC);
+      dsc[2 * c] = sp[0];
+      dsc[2 * c + 1] = sp[1];
+    }
+  };
+
   // y += scale_col * (acc - 128*hsum) with the per-column scales of the expert whose blob is `base`
   auto flush = [&](const uint8_t *base, int rows) {
     const uint16_t *sd = reinterpret_cast<const uint16_t *>(base + (int64_t)rows * rec_bytes) + 2 * rows;
@@ -123,7 +177,7 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int8_kernel(GemvParams 
 #pragma unroll
     for (int c = 0; c < LPR; ++c) {
       const u32x4 *sp = reinterpret_cast<const u32x4 *>(sd + (c * kWave + lane) * VEC);
-      const u32x4 s0 = sp[0], s1 = sp[1];
+      const u32x4 s0 = PRE ? dsc[PRE ? 2 * c : 0] : sp[0], s1 = PRE ? dsc[PRE ? 2 * c + 1 : 0] : sp[1];
       const uint32_t sw[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
 #pragma unroll
       for (int v = 0; v < VEC; v += 2) {
@@ -141,6 +195,7 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int8_kernel(GemvParams 
       if (cur_base) flush(cur_base, cur_rows);
       cur_base = R.base;
       cur_rows = R.rows;
+      load_scales(cur_base, cur_rows);
     }
     float g0 = 0.f, g1 = 0.f, u0 = 0.f, u1 = 0.f;
 #pragma unroll
@@ -206,7 +261,7 @@ struct RecI4 {
   int rows, grp;
 };
 
-template <int LPR, int NW, int DEPTH>
+template <int LPR, int NW, int DEPTH, bool PRE>
 __global__ __launch_bounds__(NW *kWave) void expert_gemv_int4_kernel(GemvParams p) {
   constexpr int VEC = 32, CPL = LPR * VEC;
   __shared__ float red[kRedFloats];
@@ -238,6 +293,10 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int4_kernel(GemvParams 
     for (int c = 0; c < LPR; ++c) R.sc[c] = sc[(c * kWave + lane) >> 2];  // 4 lanes (128 columns) per group
   };
 
+  XRaw<VEC> xraw[LPR];  // fetched ahead of the weights, converted after the ring has been filled (see int8)
+#pragma unroll
+  for (int c = 0; c < LPR; ++c) fetch_x<VEC>(p.x, p.act_fmt, (c * kWave + lane) * VEC, xraw[c]);
+
   RecI4<LPR> ring[DEPTH];
   bool live[DEPTH];
 #pragma unroll
@@ -251,13 +310,14 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int4_kernel(GemvParams 
   float xoff[LPR];
 #pragma unroll
   for (int c = 0; c < LPR; ++c) {
+    float xf[VEC];
+    unpack_x<VEC>(xraw[c], p.act_fmt, xf);
     float s = 0.f;
 #pragma unroll
     for (int w = 0; w < 4; ++w)
 #pragma unroll
       for (int t = 0; t < 4; ++t) {
-        const int col = (c * kWave + lane) * VEC + w * 8 + t;
-        const float a = x_at(p.x, p.act_fmt, col), b = x_at(p.x, p.act_fmt, col + 4);
+        const float a = xf[w * 8 + t], b = xf[w * 8 + t + 4];
         const uint32_t pa = f32_to_bf16_rne(a), pb = f32_to_bf16_rne(b);
         xp[c * 16 + w * 4 + t] = pa | (pb << 16);
         s += __uint_as_float(pa << 16) + __uint_as_float(pb << 16);
@@ -272,6 +332,18 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int4_kernel(GemvParams 
   const uint8_t *cur_base = nullptr;
   int cur_rows = 0, cur_grp = -1;
 
+  // PRE: a group's per-column scales of W_down are fetched when the wavefront enters the group
+  u32x4 dsc[PRE ? 4 * LPR : 1];
+  auto load_scales = [&](const uint8_t *base, int rows, int grp) {
+    const uint16_t *sd = reinterpret_cast<const uint16_t *>(base + (int64_t)rows * rec_bytes) + (int64_t)grp * d;
+#pragma unroll
+    for (int c = 0; c < (PRE ? LPR : 0); ++c) {
+      const u32x4 *sp = reinterpret_cast<const u32x4 *>(sd + (c * kWave + lane) * VEC);
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) dsc[4 * c + q4] = sp[q4];
+    }
+  };
+
   // y += scale[group][col] * (acc - 1032*hsum)
   auto flush = [&](const uint8_t *base, int rows, int grp) {
     const uint16_t *sd = reinterpret_cast<const uint16_t *>(base + (int64_t)rows * rec_bytes) + (int64_t)grp * d;
@@ -281,7 +353,7 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int4_kernel(GemvParams 
       const u32x4 *sp = reinterpret_cast<const u32x4 *>(sd + (c * kWave + lane) * VEC);
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
-        const u32x4 sv = sp[q4];
+        const u32x4 sv = PRE ? dsc[PRE ? 4 * c + q4 : 0] : sp[q4];
         const uint32_t sw[4] = {sv.x, sv.y, sv.z, sv.w};
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
@@ -301,6 +373,7 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int4_kernel(GemvParams 
       cur_base = R.base;
       cur_rows = R.rows;
       cur_grp = R.grp;
+      load_scales(cur_base, cur_rows, cur_grp);
     }
     float g = 0.f, u = 0.f;
 #pragma unroll
@@ -364,15 +437,15 @@ hipError_t launch_expert_gemv_quant(const GemvParams &p, int weight_fmt, const G
   const dim3 g(plan.grid), b(8 * kWave);
   if (weight_fmt == MOE_W_INT8_PC) {
     switch (p.hidden / (kWave * 16)) {
-      case 1: hipExtLaunchKernelGGL((expert_gemv_int8_kernel<1, 8, 2>), g, b, 0, s, e0, e1, 0, p); break;
-      case 2: hipExtLaunchKernelGGL((expert_gemv_int8_kernel<2, 8, 2>), g, b, 0, s, e0, e1, 0, p); break;
-      case 4: hipExtLaunchKernelGGL((expert_gemv_int8_kernel<4, 8, 1>), g, b, 0, s, e0, e1, 0, p); break;
+      case 1: hipExtLaunchKernelGGL((expert_gemv_int8_kernel<1, 8, 2, true>), g, b, 0, s, e0, e1, 0, p); break;
+      case 2: hipExtLaunchKernelGGL((expert_gemv_int8_kernel<2, 8, 2, false>), g, b, 0, s, e0, e1, 0, p); break;
+      case 4: hipExtLaunchKernelGGL((expert_gemv_int8_kernel<4, 8, 1, false>), g, b, 0, s, e0, e1, 0, p); break;
       default: return hipErrorInvalidValue;
     }
   } else if (weight_fmt == MOE_W_INT4_G128) {
     switch (p.hidden / (kWave * 32)) {
-      case 1: hipExtLaunchKernelGGL((expert_gemv_int4_kernel<1, 8, 4>), g, b, 0, s, e0, e1, 0, p); break;
-      case 2: hipExtLaunchKernelGGL((expert_gemv_int4_kernel<2, 8, 2>), g, b, 0, s, e0, e1, 0, p); break;
+      case 1: hipExtLaunchKernelGGL((expert_gemv_int4_kernel<1, 8, 4, true>), g, b, 0, s, e0, e1, 0, p); break;
+      case 2: hipExtLaunchKernelGGL((expert_gemv_int4_kernel<2, 8, 2, false>), g, b, 0, s, e0, e1, 0, p); break;
       default: return hipErrorInvalidValue;
     }
   } else {

@@ -50,11 +50,14 @@ __device__ __forceinline__ void wave_sum2(float &a, float &b) {
 // shared expert and the experts that were resident; pass 1 covers only the experts whose slots were filled
 // for this token, so the first pass can run while the fills stream.
 //
-// Shares are equal and fixed.  Workgroups do not finish together (XCDs and compute units get unequal slices
-// of HBM bandwidth: finish times of equal shares spread over about 4 us of 23), but handing records out
-// dynamically with device-scope atomics is far slower (an atomic on a contended address costs about 200 ns
-// while HBM is saturated) and skewing the shares by XCD parity gave nothing measurable.  Fixed shares also
-// keep the summation order of y, hence y itself, identical from run to run.
+// Shares are equal and fixed.  With equal shares the workgroups do not finish together: the mean finish time of
+// a workgroup depends on its XCD (about 1.4 us between the fastest and the slowest of 8, the same from launch to
+// launch, nothing else systematic), plus about 0.9 us of launch-to-launch noise.  Neither of the two remedies
+// pays: handing records out dynamically with device-scope atomics is far slower (an atomic on a contended
+// address costs about 200 ns while HBM is saturated), and shares proportional to measured per-XCD rates (or
+// skewed by XCD parity) leave the kernel time unchanged - the XCDs that finish early free bandwidth for the
+// late ones, so the spread is not lost time.  Fixed shares keep the summation order of y, hence y itself,
+// identical from run to run.
 template <int NW>
 struct RecordWalker {
   int s0, q0, ns, nl;  // this workgroup's shared rows start at s0 (ns of them), routed records at q0; nl entries
@@ -105,39 +108,48 @@ struct RecordWalker {
     return __uint_as_float(v);
   }
 
-  // advance to this wavefront's next record of the pass; false when the list is exhausted
-  __device__ __forceinline__ bool next(const GemvParams &p) {
+  // list entries this wavefront still owns
+  __device__ __forceinline__ int remaining() const { return idx < nl ? (nl - idx + NW - 1) / NW : 0; }
+
+  // Move to this wavefront's next list entry (there must be one: see remaining()) and describe its record, whether
+  // the pass covers it or not; returns whether it does.  The caller loads the record in any case, so that the
+  // number of loads in flight does not depend on the routing decision, and only skips the arithmetic.
+  __device__ __forceinline__ bool step(const GemvParams &p) {
     const int I = p.inter, K = p.top_k;
-    while (idx < nl) {
-      if (idx < ns) {
-        base = p.shared_blob;
-        rows = p.shared_inter;
-        at = s0 + idx;
-        wt = 1.f;
-        idx += NW;
-        return true;
-      }
-      if (seg < 0) {  // first routed entry: unpack the routing record, locate the entry
-        slots = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)rd.y) |
-                ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)rd.z) << 32);
-        miss_mask = (uint32_t)__builtin_amdgcn_readfirstlane((int)rd.w);
-        const int r = q0 + (idx - ns);
-        seg = r / I;
-        row = r - seg * I;
-      }
-      const bool wanted = (((miss_mask >> seg) & 1u) != 0) == (p.pass == 1);
-      base = p.slot_pool + (int64_t)((slots >> (8 * seg)) & 0xffu) * p.slot_bytes;
-      rows = I;
-      at = row;
-      wt = pick_weight(seg);
+    if (idx < ns) {
+      base = p.shared_blob;
+      rows = p.shared_inter;
+      at = s0 + idx;
+      wt = 1.f;
       idx += NW;
-      row += NW;
-      while (row >= I && seg < K) {
-        row -= I;
-        ++seg;
-      }
-      if (wanted) return true;
+      return true;
     }
+    if (seg < 0) {  // first routed entry: unpack the routing record, locate the entry
+      slots = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)rd.y) |
+              ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)rd.z) << 32);
+      miss_mask = (uint32_t)__builtin_amdgcn_readfirstlane((int)rd.w);
+      const int r = q0 + (idx - ns);
+      seg = r / I;
+      row = r - seg * I;
+    }
+    const bool wanted = (((miss_mask >> seg) & 1u) != 0) == (p.pass == 1);
+    base = p.slot_pool + (int64_t)((slots >> (8 * seg)) & 0xffu) * p.slot_bytes;
+    rows = I;
+    at = row;
+    wt = pick_weight(seg);
+    idx += NW;
+    row += NW;
+    while (row >= I && seg < K) {
+      row -= I;
+      ++seg;
+    }
+    return wanted;
+  }
+
+  // advance to this wavefront's next record of the pass, skipping the others; false when the list is exhausted
+  __device__ __forceinline__ bool next(const GemvParams &p) {
+    while (idx < nl)
+      if (step(p)) return true;
     return false;
   }
 };
