@@ -27,6 +27,53 @@ HBM_PEAK_GBS = 8000.0
 HEADLINE_LAMBDA = 0.5
 PERTURB = 0.5
 
+# HBM traffic of one whole-layer launch of the expert GEMV on the default workload, from two rocprofv3 --pmc runs
+# (FETCH_SIZE, WRITE_SIZE in KiB per dispatch), each scaled by what the same counter reads for an elementwise kernel
+# of known size in the same run (summary and commands: profiles/hbm_counters_expert_gemv_c2_qwen_bf16.txt).  Valid
+# only for the kernel sources it was taken with: reported as null once their hash differs.
+GEMV_TRAFFIC = {
+    "workload": "c2_qwen_bf16",
+    "sources_sha256": "29be46d43382e309c19538a788e1443623221a98eb1ca73613a2e0685cbddb35",
+    "fetch_kib": 67717.1, "fetch_scale": 2.0,
+    "write_kib": 2048.0, "write_scale": 1.0,
+}
+GEMV_SOURCES = ("expert_gemv.hip", "gemv_common.h", "common.h")
+
+
+def gemv_sources_hash():
+    import hashlib
+
+    h = hashlib.sha256()
+    for f in GEMV_SOURCES:
+        with open(os.path.join(ROOT, "paper_2412_00099_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
+def measured_traffic(workload):
+    t = GEMV_TRAFFIC
+    if workload != t["workload"] or not t["sources_sha256"] or gemv_sources_hash() != t["sources_sha256"]:
+        return None
+    return int((t["fetch_kib"] * t["fetch_scale"] + t["write_kib"] * t["write_scale"]) * 1024)
+
+
+def host_link_rate(store, n_copies=24):
+    """GB/s of the miss-fill copy (pinned host blob -> device slot) on a side stream, timed with events."""
+    import torch
+
+    side = torch.cuda.Stream()
+    slot = torch.empty(store.blob_bytes, dtype=torch.uint8, device=store.device)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        slot.copy_(store.host[0, 0], non_blocking=True)  # warm-up
+        e0.record()
+        for i in range(n_copies):
+            slot.copy_(store.host[i % store.L, (i // store.L) % store.N], non_blocking=True)
+        e1.record()
+    side.synchronize()
+    return n_copies * store.blob_bytes / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
 
 def log(msg):
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
@@ -66,6 +113,7 @@ def timed_run(dec, a, h, x, y, warmup, steps):
         miss_rate_incl_warmup=s1.misses / max(s1.selections, 1),
         cold_misses=s1.cold_misses, misses=s1.misses - s0.misses,
         host_link_bytes=s1.bytes_filled - s0.bytes_filled,
+        mean_lifetime=(s1.lifetime_sum - s0.lifetime_sum) / max(s1.evictions - s0.evictions, 1),
     )
 
 
@@ -132,7 +180,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debugging)")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
-    ap.add_argument("--cpu-tokens", type=int, default=2)
+    ap.add_argument("--cpu-tokens", type=int, default=8)
     ap.add_argument("--no-calib-copy", action="store_true",
                     help="skip the plain 256 MiB device copy that calibrates HBM byte counters under rocprofv3 --pmc")
     args = ap.parse_args()
@@ -197,7 +245,8 @@ def main():
             dec.set_lambda(lam)
             r = timed_run(dec, a, h, x, y, args.warmup, args.steps)
             sweep[str(lam)] = dict(tok_s=round(r["tok_s"], 2), miss_rate=round(r["miss_rate"], 5),
-                                   host_link_GB=round(r["host_link_bytes"] / 1e9, 3))
+                                   host_link_GB=round(r["host_link_bytes"] / 1e9, 3),
+                                   mean_lifetime_tokens=round(r["mean_lifetime"], 2))
             log(f"lambda={lam}: {r['tok_s']:.1f} tok/s, miss rate {r['miss_rate']:.4f}")
         # miss-free run: with an overwhelming prior the cache freezes after warm-up (Sec. 3.3)
         dec.set_lambda(1e6)
@@ -205,6 +254,9 @@ def main():
         sweep["miss_free"] = dict(tok_s=round(r["tok_s"], 2), miss_rate=round(r["miss_rate"], 5))
         log(f"miss-free: {r['tok_s']:.1f} tok/s")
         dec.set_lambda(HEADLINE_LAMBDA)
+
+    link_gbs = host_link_rate(store)
+    log(f"miss fill copy: {link_gbs:.1f} GB/s")
 
     cpu = None
     if not args.no_cpu:
@@ -251,9 +303,11 @@ def main():
         "miss_rate": round(head["miss_rate"], 5),
         "miss_rate_incl_warmup": round(head["miss_rate_incl_warmup"], 5),
         "host_link_GB_filled": round(head["host_link_bytes"] / 1e9, 3),
+        "host_link_GBps": round(link_gbs, 2),
+        "mean_cache_lifetime_tokens": round(head["mean_lifetime"], 2),
         "roofline": {
             "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+            "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(cfg.name),
             "kernel": "expert_gemv_kernel", "algorithmic_bytes_per_launch": algo_bytes,
             "avg_launch_us": round(gemv_us, 3), "launches": gemv_launches,
             "tok_s_while_profiled": round(prof["tok_s"], 2),

@@ -97,7 +97,7 @@ typedef struct moe_route_out {
 typedef struct moe_cache_stats {
   int64_t tokens, selections, hits, misses, cold_misses, evictions, bytes_filled;
   int64_t lifetime_sum; /* over the evictions: tokens between an expert's load and its eviction; divided by
-                         * `evictions` it is the average cache lifetime of Sec. 4.4 / Table 2 */
+                         * `evictions` it is the average cache lifetime of Sec. 4.6 / Table 2 */
 } moe_cache_stats_t;
 
 /* Per-layer tables, for checking against a reference (host struct). */
@@ -196,9 +196,9 @@ int moe_residual_rmsnorm(float *h_dev, const void *y_dev, const float *a_dev, fl
  * the cache touches them (descending router weight, Sec. 4.2).  Misses are counted per token against the cache
  * before the token (Eq. 4), starting from `initial` (n_initial experts, may be NULL/0).
  *   MOE_POLICY_LRU       least-recently-used eviction as in Sec. 4.2; any capacity in 1..n_experts (below top_k
- *                        only the most recently touched experts of a token stay: the cache-size sweep of Sec. 4.6)
+ *                        only the most recently touched experts of a token stay: the cache-size sweep of Sec. 4.8)
  *   MOE_POLICY_FARTHEST  evict the resident expert, not needed by the current token, whose next use is farthest
- *                        (never again first, ties to the lowest id): the optimal-eviction bound of Sec. 4.6;
+ *                        (never again first, ties to the lowest id): the optimal-eviction bound of Sec. 4.8;
  *                        needs capacity >= top_k
  * Outputs: *misses; optionally (may be NULL) *lifetime_sum and *evictions as in moe_cache_stats_t.
  * MOE_EINVAL on NULL/out-of-range arguments or a token with repeated experts. */

@@ -8,7 +8,7 @@ experts).  Misses are counted per token against the cache before the token
 
   * lru_list_misses   - a recency list kept literally (front = least recent);
   * belady_misses     - evict the resident expert needed farthest in the
-                        future (the optimal-eviction reference of Sec. 4.6);
+                        future (the optimal-eviction reference of Sec. 4.8);
   * min_misses_search - exhaustive search over every eviction choice, for
                         tiny traces, to check Belady's count is the minimum.
 
@@ -37,7 +37,7 @@ def lru_list_misses(trace, capacity: int, initial=()):
 
 def lru_list_lifetimes(trace, capacity: int, initial=()):
     """Stays in memory under the recency-list LRU: (sum, count) of the lengths in tokens of the stays that ended
-    by eviction, and the still-open stays as {expert: token it was loaded at} (Sec. 4.4, Table 2 'lifetime')."""
+    by eviction, and the still-open stays as {expert: token it was loaded at} (Sec. 4.6, Table 2 'lifetime')."""
     order = list(initial)
     born = {e: 0 for e in order}
     total = count = 0

@@ -108,7 +108,7 @@ class CacheStats:
 
     @property
     def mean_lifetime(self) -> float:
-        """Average number of time steps an expert stays in memory (Sec. 4.4, Table 2), over completed stays."""
+        """Average number of time steps an expert stays in memory (Sec. 4.6, Table 2), over completed stays."""
         return self.lifetime_sum / max(self.evictions, 1)
 
 

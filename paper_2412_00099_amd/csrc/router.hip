@@ -267,7 +267,7 @@ __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_
   }
   int my_evicted = -1;
   int born = cr.born;
-  int cold = 0, evictions = 0, lifetime = 0;  // lifetime: tokens the evicted experts had stayed (Sec. 4.4)
+  int cold = 0, evictions = 0, lifetime = 0;  // lifetime: tokens the evicted experts had stayed (Sec. 4.6)
   for (int q = 0; q < n_miss; ++q) {
     const int ml = (int)__builtin_ctzll(ballot(miss && ordinal == q));
     int s, victim = -1;

@@ -3,8 +3,8 @@
 // A trace lists, token by token, the K distinct experts a layer selected, in the order the cache touches them
 // (descending router weight, Sec. 4.2).  Misses are counted per token against the cache as it was before the token
 // (Eq. 4).  Two eviction policies: least recently used (the policy of Sec. 4.2, also for capacities below K, where
-// only the most recently touched experts of a token stay: the cache-size sweep of Sec. 4.6) and farthest next use
-// (the optimal-eviction bound the paper compares against in Sec. 4.6).
+// only the most recently touched experts of a token stay: the cache-size sweep of Sec. 4.8) and farthest next use
+// (the optimal-eviction bound the paper compares against in Sec. 4.8).
 #include <stdint.h>
 
 #include <limits>

@@ -247,7 +247,7 @@ def test_snapshot_restore_resumes_bit_exactly():
 def test_device_trace_lru_and_optimal_eviction_bound():
     """Record the original routing (lambda = 0) on the device, then replay the trace through the library's offline
     simulator and the oracle's: the device's own miss count equals the simulated LRU count at the same capacity,
-    farthest-next-use eviction (Sec. 4.6) is never worse, and both agree with the oracle at every cache size."""
+    farthest-next-use eviction (Sec. 4.8) is never worse, and both agree with the oracle at every cache size."""
     import paper_2412_00099_amd as pkg
     from oracle import eviction
 

@@ -118,10 +118,10 @@ def test_top_j_always_selected(lam, J):
         res = r.step(z[t])
         assert res.sel[:J].tolist() == plain_topk(z[t], J)
         if lam >= 64 and t > 0:
-            assert sum(res.miss) <= J  # the miss rate bottoms out at the guarantee (Sec. 4.4)
+            assert sum(res.miss) <= J  # the miss rate only the guaranteed top-J can still miss (Sec. 3.3)
 
 
-# ---------------------------------------------------------------- cache-size limits (Sec. 4.6)
+# ---------------------------------------------------------------- cache-size limits (Sec. 4.8)
 
 
 def test_full_cache_has_only_cold_misses():
@@ -228,7 +228,7 @@ def test_lru_stamps_match_recency_list_on_tiny_traces():
 
 
 def test_lifetimes_two_ways_and_occupancy_identity():
-    """Cache lifetime (Sec. 4.4, Table 2): the stamp-table cache and the literal recency list agree on the stays
+    """Cache lifetime (Sec. 4.6, Table 2): the stamp-table cache and the literal recency list agree on the stays
     that ended, and all stays together (open ones closed at the end) add up to the occupancy summed over tokens."""
     r = np.random.default_rng(11)
     for case in range(200):
@@ -289,7 +289,7 @@ def test_k1_equals_textbook_lru():
         assert eviction.lru_list_misses(trace, C)[0] == eviction.sequential_lru_misses(trace, C)
 
 
-# ---------------------------------------------------------------- Belady (Sec. 4.6)
+# ---------------------------------------------------------------- Belady (Sec. 4.8)
 
 
 def test_belady_is_minimum_and_below_lru():
