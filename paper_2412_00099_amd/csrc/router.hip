@@ -18,6 +18,7 @@ namespace moe {
 namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kRecWords = sizeof(moe_route_out_t) / 4;
@@ -145,15 +146,22 @@ struct CacheRegs {
 };
 
 __device__ __forceinline__ CacheRegs load_cache_regs(const LayerState *st, int lane, int N, int C) {
+  // every lane loads (the tables have 64 entries, the counter index is clamped) and masks afterwards: loads
+  // inside branches would make later waits cover all outstanding loads
   CacheRegs cr;
-  cr.my_slot = lane < N ? st->expert_slot[lane] : -1;
-  cr.stamp = lane < N ? st->stamp[lane] : 0;
-  cr.born = lane < N ? st->born[lane] : 0;
-  cr.slot_exp = lane < C ? st->slot_expert[lane] : -1;
+  const int my_slot = st->expert_slot[lane];
+  const int64_t stamp = st->stamp[lane];
+  const int born = st->born[lane];
+  const int slot_exp = st->slot_expert[lane];
+  const int64_t counter = (&st->selections)[lane < 6 ? lane : 5];
   cr.ever_used = st->ever_used;
   cr.dsum_prev = st->delta_sum;
   cr.t = st->count;
-  cr.counter = lane < 6 ? (&st->selections)[lane] : 0;
+  cr.my_slot = lane < N ? my_slot : -1;
+  cr.stamp = lane < N ? stamp : 0;
+  cr.born = lane < N ? born : 0;
+  cr.slot_exp = lane < C ? slot_exp : -1;
+  cr.counter = lane < 6 ? counter : 0;
   return cr;
 }
 
@@ -425,12 +433,61 @@ __device__ __forceinline__ void gate_dot(const GateRegs<R, CH> &g, const uint32_
   for (int r = 0; r < R; ++r) out[r] = wave_sum(acc[r]);
 }
 
+// PER consecutive values for one thread, fetched with one load
+template <int PER>
+__device__ __forceinline__ void load_f32(const float *p, float *out) {
+  if constexpr (PER == 1) {
+    out[0] = p[0];
+  } else if constexpr (PER == 2) {
+    const float2 v = *reinterpret_cast<const float2 *>(p);
+    out[0] = v.x; out[1] = v.y;
+  } else {
+    const float4 v = *reinterpret_cast<const float4 *>(p);
+    out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+  }
+}
+template <int PER>
+__device__ __forceinline__ void load_bf16(const uint16_t *p, float *out) {
+  if constexpr (PER == 1) {
+    out[0] = __uint_as_float((uint32_t)p[0] << 16);
+  } else if constexpr (PER == 2) {
+    const uint32_t v = *reinterpret_cast<const uint32_t *>(p);
+    out[0] = bf16_lo(v); out[1] = bf16_hi(v);
+  } else {
+    const u32x2 v = *reinterpret_cast<const u32x2 *>(p);
+    out[0] = bf16_lo(v.x); out[1] = bf16_hi(v.x); out[2] = bf16_lo(v.y); out[3] = bf16_hi(v.y);
+  }
+}
+template <int PER>
+__device__ __forceinline__ void store_f32(float *p, const float *v) {
+  if constexpr (PER == 1) p[0] = v[0];
+  else if constexpr (PER == 2) *reinterpret_cast<float2 *>(p) = make_float2(v[0], v[1]);
+  else *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+}
+template <int PER>
+__device__ __forceinline__ void store_bf16(uint16_t *p, const float *v) {
+  if constexpr (PER == 1) {
+    p[0] = f32_to_bf16_rne(v[0]);
+  } else if constexpr (PER == 2) {
+    *reinterpret_cast<uint32_t *>(p) = (uint32_t)f32_to_bf16_rne(v[0]) | ((uint32_t)f32_to_bf16_rne(v[1]) << 16);
+  } else {
+    u32x2 o;
+    o.x = (uint32_t)f32_to_bf16_rne(v[0]) | ((uint32_t)f32_to_bf16_rne(v[1]) << 16);
+    o.y = (uint32_t)f32_to_bf16_rne(v[2]) | ((uint32_t)f32_to_bf16_rne(v[3]) << 16);
+    *reinterpret_cast<u32x2 *>(p) = o;
+  }
+}
+
 // Layer boundary of a stack: the residual / perturbation / RMS-normalisation glue and the routing of this layer in
 // one launch of one workgroup (the previous layer's expert output y has been summed by partial_reduce_kernel).
 //   h = carry ? h + y + perturb*a : perturb*a ;  x = h / sqrt(mean(h^2) + 1e-6) -> x_out and LDS ;  route on x.
 // CH > 0: 16-byte chunks per gate row per lane (d = CH*64*VEC); the wavefront's gate rows are then loaded into
 // registers at the very start, so the weight fetch overlaps the glue.  CH == 0: any d, rows loaded afterwards.
-template <int CH>
+// PER > 0: d = 1024*PER and thread t owns the PER consecutive columns t*PER...; all loads of the kernel's first
+// phase (cache state, glue operands, gate rows) are then issued unconditionally and in that order, so each use
+// waits only for the loads ahead of it (a load inside a branch makes the compiler wait for all outstanding loads,
+// which would serialise the memory round trips).  PER == 0: any d, column t, t+1024, ... per thread.
+template <int CH, int PER>
 __global__ __launch_bounds__(1024) void fused_route_kernel(RouteParams p, FusedParams f, const void *gate_w,
                                                            LayerState *st, moe_route_out_t *out_dev,
                                                            HostNote *note) {
@@ -445,60 +502,109 @@ __global__ __launch_bounds__(1024) void fused_route_kernel(RouteParams p, FusedP
   constexpr int R = 4;
   const int rpw = (N + n_waves - 1) / n_waves;  // rows per wavefront (<= 4 by the launch shape)
   const int row0 = wave * rpw, nrows = min(R, N - row0);
-
-  // ---- glue: each thread owns columns tid, tid + 1024, ... (kept in registers between the two sweeps) ----
-  // its loads are issued first: loads complete in order, and the glue must not wait for the gate rows
-  constexpr int kMaxPer = kFusedMaxHidden / 1024;
-  float hv[kMaxPer], yv[kMaxPer], av[kMaxPer];
   const bool with_y = f.y != nullptr && f.carry;
-#pragma unroll
-  for (int i = 0; i < kMaxPer; ++i) {
-    const int j = tid + i * 1024;
-    hv[i] = yv[i] = av[i] = 0.f;
-    if (j < d) {
-      if (f.carry) hv[i] = f.h[j];
-      if (with_y)
-        yv[i] = bf16 ? __uint_as_float((uint32_t) static_cast<const uint16_t *>(f.y)[j] << 16)
-                     : static_cast<const float *>(f.y)[j];
-      if (f.a != nullptr) av[i] = f.a[j];
-    }
-  }
+  constexpr int kMaxPer = PER > 0 ? PER : kFusedMaxHidden / 1024;
+  float hv[kMaxPer], yv[kMaxPer], av[kMaxPer];
   CacheRegs cr{};
-  if (wave == 0) cr = load_cache_regs(st, lane, N, p.capacity);
   GateRegs<R, (CH > 0 ? CH : 1)> greg;
-  if (CH > 0 && nrows > 0) gate_prefetch<R, (CH > 0 ? CH : 1)>(gate_w, row0, nrows, lane, greg);
+
+  if constexpr (PER > 0) {
+    // every wavefront loads the cache state (only wavefront 0 uses it): unconditional, and the oldest loads
+    cr = load_cache_regs(st, lane, N, p.capacity);
+    // operands that are absent are read from h instead (any valid address) and ignored
+    const int j0 = tid * PER;
+    load_f32<PER>(f.h + j0, hv);
+    // y as raw bits (PER bf16 values or PER floats), converted once all loads of this phase are out
+    const uint8_t *yb = with_y ? static_cast<const uint8_t *>(f.y) : reinterpret_cast<const uint8_t *>(f.h);
+    const uint8_t *yp16 = yb + (size_t)j0 * 2, *yp32 = yb + (size_t)j0 * 4;
+    load_f32<PER>(reinterpret_cast<const float *>(bf16 ? reinterpret_cast<const uint8_t *>(f.h) + (size_t)j0 * 4 : yp32), yv);
+    float y16[PER];
+    load_bf16<PER>(reinterpret_cast<const uint16_t *>(bf16 ? yp16 : reinterpret_cast<const uint8_t *>(f.h) + (size_t)j0 * 2), y16);
+    load_f32<PER>((f.a != nullptr ? f.a : f.h) + j0, av);
+    if constexpr (CH > 0) {
+      // wavefronts past the last gate row re-read the last row
+      const int r0 = min(row0, N - 1);
+      gate_prefetch<R, (CH > 0 ? CH : 1)>(gate_w, r0, max(1, min(R, N - r0)), lane, greg);
+    }
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {  // (masks, not a select: see below)
+      const uint32_t mb = bf16 ? 0xffffffffu : 0u;
+      yv[i] = __uint_as_float((__float_as_uint(y16[i]) & mb) | (__float_as_uint(yv[i]) & ~mb));
+    }
+  } else {
+    // each thread owns columns tid, tid + 1024, ...
+#pragma unroll
+    for (int i = 0; i < kMaxPer; ++i) {
+      const int j = tid + i * 1024;
+      hv[i] = yv[i] = av[i] = 0.f;
+      if (j < d) {
+        if (f.carry) hv[i] = f.h[j];
+        if (with_y)
+          yv[i] = bf16 ? __uint_as_float((uint32_t) static_cast<const uint16_t *>(f.y)[j] << 16)
+                       : static_cast<const float *>(f.y)[j];
+        if (f.a != nullptr) av[i] = f.a[j];
+      }
+    }
+    if (wave == 0) cr = load_cache_regs(st, lane, N, p.capacity);
+    if (CH > 0 && nrows > 0) gate_prefetch<R, (CH > 0 ? CH : 1)>(gate_w, row0, nrows, lane, greg);
+  }
 
   float ss = 0.f;
 #pragma unroll
   for (int i = 0; i < kMaxPer; ++i) {
-    const int j = tid + i * 1024;
-    if (j < d) {
-      float v = hv[i];
-      if (with_y) v += yv[i];
-      if (f.a != nullptr) v = __builtin_fmaf(f.perturb, av[i], v);
-      f.h[j] = v;
+    const int j = PER > 0 ? tid * PER + i : tid + i * 1024;
+    if (PER > 0 || j < d) {
+      float v;
+      if constexpr (PER > 0) {
+        // absent operands are masked to +0 with bit masks: a select or a branch lets the compiler sink the load
+        // into it, and a load inside a branch makes the next wait cover all outstanding loads
+        const uint32_t mh = f.carry ? 0xffffffffu : 0u, my = with_y ? 0xffffffffu : 0u,
+                       ma = f.a != nullptr ? 0xffffffffu : 0u;
+        v = __uint_as_float(__float_as_uint(hv[i]) & mh) + __uint_as_float(__float_as_uint(yv[i]) & my);
+        v = __builtin_fmaf(f.perturb, __uint_as_float(__float_as_uint(av[i]) & ma), v);
+      } else {
+        v = hv[i];
+        if (with_y) v += yv[i];
+        if (f.a != nullptr) v = __builtin_fmaf(f.perturb, av[i], v);
+      }
       hv[i] = v;
       ss = __builtin_fmaf(v, v, ss);
+      if (PER == 0) f.h[j] = v;
     }
   }
+  if constexpr (PER > 0) store_f32<PER>(f.h + tid * PER, hv);
   ss = wave_sum(ss);
   if (lane == 0) part_s[wave] = ss;
   __syncthreads();
   float tot = 0.f;
   for (int w = 0; w < n_waves; ++w) tot += part_s[w];
   const float scale = 1.0f / sqrtf(tot / (float)d + 1e-6f);
+  if constexpr (PER > 0) {
+    float xv[PER];
 #pragma unroll
-  for (int i = 0; i < kMaxPer; ++i) {
-    const int j = tid + i * 1024;
-    if (j < d) {
-      const float v = hv[i] * scale;
-      if (bf16) {
-        const uint16_t q = f32_to_bf16_rne(v);
-        static_cast<uint16_t *>(f.x_out)[j] = q;
-        reinterpret_cast<uint16_t *>(x_s)[j] = q;
-      } else {
-        static_cast<float *>(f.x_out)[j] = v;
-        reinterpret_cast<float *>(x_s)[j] = v;
+    for (int i = 0; i < PER; ++i) xv[i] = hv[i] * scale;
+    const int j0 = tid * PER;
+    if (bf16) {
+      store_bf16<PER>(static_cast<uint16_t *>(f.x_out) + j0, xv);
+      store_bf16<PER>(reinterpret_cast<uint16_t *>(x_s) + j0, xv);
+    } else {
+      store_f32<PER>(static_cast<float *>(f.x_out) + j0, xv);
+      store_f32<PER>(reinterpret_cast<float *>(x_s) + j0, xv);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < kMaxPer; ++i) {
+      const int j = tid + i * 1024;
+      if (j < d) {
+        const float v = hv[i] * scale;
+        if (bf16) {
+          const uint16_t q = f32_to_bf16_rne(v);
+          static_cast<uint16_t *>(f.x_out)[j] = q;
+          reinterpret_cast<uint16_t *>(x_s)[j] = q;
+        } else {
+          static_cast<float *>(f.x_out)[j] = v;
+          reinterpret_cast<float *>(x_s)[j] = v;
+        }
       }
     }
   }
@@ -563,13 +669,24 @@ hipError_t launch_fused_route(const RouteParams &p, const FusedParams &f, const 
   // 16 wavefronts, at most four gate rows each (N <= 64)
   const dim3 g(1), b(1024);
   const int vec = p.act_fmt == MOE_A_BF16 ? 8 : 4;
-  const int ch = p.hidden % (kWave * vec) == 0 ? p.hidden / (kWave * vec) : 0;
-  switch (ch) {
-    case 1: hipLaunchKernelGGL(fused_route_kernel<1>, g, b, 0, s, p, f, gate_w, state, out_dev, note_mapped); break;
-    case 2: hipLaunchKernelGGL(fused_route_kernel<2>, g, b, 0, s, p, f, gate_w, state, out_dev, note_mapped); break;
-    case 4: hipLaunchKernelGGL(fused_route_kernel<4>, g, b, 0, s, p, f, gate_w, state, out_dev, note_mapped); break;
-    default: hipLaunchKernelGGL(fused_route_kernel<0>, g, b, 0, s, p, f, gate_w, state, out_dev, note_mapped);
+  int ch = p.hidden % (kWave * vec) == 0 ? p.hidden / (kWave * vec) : 0;
+  if (ch != 1 && ch != 2 && ch != 4) ch = 0;  // more than 4 chunks per row: gate rows are not held in registers
+  const int per = (p.hidden % 1024 == 0 && (p.hidden / 1024 == 1 || p.hidden / 1024 == 2 || p.hidden / 1024 == 4))
+                      ? p.hidden / 1024 : 0;
+#define MOE_FUSED(CH_, PER_)                                                                                    \
+  hipLaunchKernelGGL((fused_route_kernel<CH_, PER_>), g, b, 0, s, p, f, gate_w, state, out_dev, note_mapped)
+  switch (ch * 10 + per) {  // (bf16: d = 512 ch; fp32: d = 256 ch)
+    case 42: MOE_FUSED(4, 2); break;  // bf16 d = 2048
+    case 41: MOE_FUSED(4, 1); break;  // fp32 d = 1024
+    case 21: MOE_FUSED(2, 1); break;  // bf16 d = 1024
+    case 20: MOE_FUSED(2, 0); break;  // fp32 d = 512
+    case 10: MOE_FUSED(1, 0); break;  // bf16 d = 512, fp32 d = 256
+    default:
+      if (per == 2) MOE_FUSED(0, 2);       // fp32 d = 2048
+      else if (per == 4) MOE_FUSED(0, 4);  // d = 4096
+      else MOE_FUSED(0, 0);
   }
+#undef MOE_FUSED
   return hipGetLastError();
 }
 
