@@ -277,8 +277,21 @@ def main():
         cpu = dict(value=round(tok_s, 4), unit="tok/s", cores=int(cores), kind="oracle",
                    sample=f"first {n_tok} tokens of {cfg.name} (all {cfg.n_layers} layers, lambda={HEADLINE_LAMBDA}), "
                           f"numpy fp64, weights already in host memory")
-        del probe
+        del probe, lw
         log(f"cpu oracle: {tok_s:.3f} tok/s on {cores} threads")
+        # the small single-layer fp32 workload on one thread, for scale
+        try:
+            from threadpoolctl import threadpool_limits
+
+            c1 = CONFIGS["c1_single_fp32"]
+            lw1 = LazyWeights(c1, dev)
+            a1 = workloads.ar1_stream(c1, c1.n_tokens, device=dev).cpu().numpy()
+            with threadpool_limits(limits=1):
+                cpu_oracle_baseline(c1, lw1, a1, 16)
+                cpu["c1_single_thread_tok_s"] = round(cpu_oracle_baseline(c1, lw1, a1, c1.n_tokens), 2)
+            log(f"cpu oracle, {c1.name}, 1 thread: {cpu['c1_single_thread_tok_s']} tok/s")
+        except ImportError:
+            pass
 
     out = {
         "metric": "batch1_decode_tok_per_s",
