@@ -40,6 +40,25 @@ struct FusedParams {
   float perturb;
   int32_t carry;    // 0: a new token starts, h = perturb * a
   void *x_out;      // [d] act_fmt, the normalised vector (input of this layer)
+  // When the glue has been done by reduce_glue_kernel: h already holds the new residual stream and ss its sums
+  // of squares over consecutive blocks of 64 columns (n_ss = d / 64 of them); y, a, perturb, carry are unused.
+  const float *ss;
+  int32_t n_ss;
+};
+
+// The layer boundary (x from the new residual stream + routing step, see rt::fused_boundary) when it is run by
+// workgroup 0 of the expert launch itself: the other workgroups compute x for themselves, stream the shared
+// expert's records meanwhile, and wait for a tag before the first routed record.
+struct BoundaryArgs {
+  RouteParams route;
+  FusedParams glue;
+  const void *gate_w;
+  LayerState *state;
+  moe_route_out_t *out_dev;  // the layer's device record (= GemvParams::route)
+  struct HostNote *note;     // the layer's words in mapped host memory
+  uint32_t *tags;            // device words [grid] 64 bytes apart: "routing record published", one copy per
+                             // workgroup (compared with route.seq)
+  uint32_t *gave_up;         // mapped host word set when a wavefront stopped waiting for a tag
 };
 
 struct GemvParams {
@@ -52,6 +71,8 @@ struct GemvParams {
   int64_t slot_bytes;
   int32_t pass;        // 0: shared expert + experts that were resident; 1: experts whose slot was just filled
   int32_t row_offset;  // first partial row this launch writes
+  int32_t fused;       // workgroup 0 runs the layer boundary `b` and writes a zero partial row
+  BoundaryArgs b;
 };
 
 // Blob geometry (see moe_blob_bytes).
@@ -85,12 +106,17 @@ struct GemvPlan {
   bool dot2;  // packed bf16 dot products (bf16 weights and activations)
 };
 GemvPlan gemv_plan(int n_cus, int total_records, int weight_fmt, int act_fmt);
+bool gemv_fused_supported(int weight_fmt, int hidden, const GemvPlan &plan);  // a launch variant with the boundary in workgroup 0
 hipError_t launch_fused_route(const RouteParams &p, const FusedParams &f, const void *gate_w, LayerState *state,
                               moe_route_out_t *out_dev, HostNote *note_mapped, hipStream_t s);
 hipError_t launch_expert_gemv(const GemvParams &p, int weight_fmt, const GemvPlan &plan, hipStream_t s,
                               hipEvent_t start = nullptr, hipEvent_t stop = nullptr);
 hipError_t launch_partial_reduce(const float *partial, int n_partial, void *y, int hidden, int act_fmt,
                                  hipStream_t s);
+// the same plus the residual glue: h = (carry ? h + y : 0) + perturb * a in place, ss[b] = sum of h^2 over columns
+// 64b .. 64b+63 (y may be NULL: not stored; n_partial may be 0: y = nothing)
+hipError_t launch_reduce_glue(const float *partial, int n_partial, void *y, int hidden, int act_fmt, float *h,
+                              const float *a, float perturb, int carry, float *ss, hipStream_t s);
 hipError_t launch_pack(int fmt, int hidden, int inter, const void *gate, const void *up, const void *down,
                        const void *gs, const void *us, const void *ds, void *blob, hipStream_t s);
 hipError_t launch_residual_rmsnorm(float *h, const void *y, const float *a, float perturb, int carry, void *x,
@@ -118,6 +144,22 @@ __device__ __forceinline__ float dpp_f32(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
 }
 // Sum over the 64 lanes, result in every lane, fixed order (rotations inside rows of 16, then rows).
+// Sum of N <= 64 floats in index order, the same in every wavefront that computes it: fetch() has lane i load
+// entry i (clamped: no branch around the load), total() adds the entries one by one through lane reads.  N is a
+// compile-time constant so that neither part ends up inside a branch.
+template <int N>
+struct OrderedSum {
+  static_assert(N >= 1 && N <= 64, "one entry per lane");
+  float s;
+  __device__ __forceinline__ void fetch(const float *v, int lane) { s = v[lane < N ? lane : 0]; }
+  __device__ __forceinline__ float total() const {
+    float tot = 0.f;
+#pragma unroll
+    for (int i = 0; i < N; ++i) tot += __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s), i));
+    return tot;
+  }
+};
+
 __device__ __forceinline__ float wave_sum(float v) {
   v += dpp_f32<0x128>(v);  // row_ror:8
   v += dpp_f32<0x124>(v);  // row_ror:4

@@ -16,6 +16,7 @@
 
 #include "common.h"
 #include "gemv_common.h"
+#include "route_device.h"
 
 namespace moe {
 namespace {
@@ -29,14 +30,27 @@ struct Chunk;
 template <>
 struct Chunk<MOE_W_FP32, false> {
   static constexpr int VEC = 4, XW = 4;
+  template <bool COH>
   static __device__ __forceinline__ void load_x(const void *x, int act_fmt, int col, float *xr) {
     if (act_fmt == MOE_A_BF16) {
-      const u32x2 v = *reinterpret_cast<const u32x2 *>(static_cast<const uint16_t *>(x) + col);
+      const u32x2 v = ld64<COH>(static_cast<const uint16_t *>(x) + col);
       xr[0] = bf16_lo(v.x); xr[1] = bf16_hi(v.x); xr[2] = bf16_lo(v.y); xr[3] = bf16_hi(v.y);
     } else {
-      const float4 v = *reinterpret_cast<const float4 *>(static_cast<const float *>(x) + col);
-      xr[0] = v.x; xr[1] = v.y; xr[2] = v.z; xr[3] = v.w;
+      const u32x4 v = ld128<COH>(static_cast<const float *>(x) + col);
+      xr[0] = __uint_as_float(v.x); xr[1] = __uint_as_float(v.y); xr[2] = __uint_as_float(v.z);
+      xr[3] = __uint_as_float(v.w);
     }
+  }
+  // x entries of VEC consecutive columns from the residual stream: h * scale, rounded to the activation type
+  static __device__ __forceinline__ void load_h(const float *h, int col, float *out) {
+    const float4 v = *reinterpret_cast<const float4 *>(h + col);
+    out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+  }
+  static __device__ __forceinline__ void make_x(const float *hv, float scale, int act_fmt, float *xr) {
+    const float t[4] = {hv[0] * scale, hv[1] * scale, hv[2] * scale, hv[3] * scale};
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      xr[i] = act_fmt == MOE_A_BF16 ? __uint_as_float((uint32_t)f32_to_bf16_rne(t[i]) << 16) : t[i];
   }
   static __device__ __forceinline__ void dot(const u32x4 &w, const float *xr, float &a0, float &a1) {
     a0 = __builtin_fmaf(__uint_as_float(w.x), xr[0], a0);
@@ -55,16 +69,32 @@ struct Chunk<MOE_W_FP32, false> {
 template <>
 struct Chunk<MOE_W_BF16, false> {
   static constexpr int VEC = 8, XW = 8;
+  template <bool COH>
   static __device__ __forceinline__ void load_x(const void *x, int act_fmt, int col, float *xr) {
     if (act_fmt == MOE_A_BF16) {
-      const u32x4 v = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(x) + col);
+      const u32x4 v = ld128<COH>(static_cast<const uint16_t *>(x) + col);
       xr[0] = bf16_lo(v.x); xr[1] = bf16_hi(v.x); xr[2] = bf16_lo(v.y); xr[3] = bf16_hi(v.y);
       xr[4] = bf16_lo(v.z); xr[5] = bf16_hi(v.z); xr[6] = bf16_lo(v.w); xr[7] = bf16_hi(v.w);
     } else {
-      const float4 *p = reinterpret_cast<const float4 *>(static_cast<const float *>(x) + col);
-      const float4 a = p[0], b = p[1];
-      xr[0] = a.x; xr[1] = a.y; xr[2] = a.z; xr[3] = a.w; xr[4] = b.x; xr[5] = b.y; xr[6] = b.z; xr[7] = b.w;
+      const float *p = static_cast<const float *>(x) + col;
+      const u32x4 a = ld128<COH>(p), b = ld128<COH>(p + 4);
+      xr[0] = __uint_as_float(a.x); xr[1] = __uint_as_float(a.y); xr[2] = __uint_as_float(a.z);
+      xr[3] = __uint_as_float(a.w); xr[4] = __uint_as_float(b.x); xr[5] = __uint_as_float(b.y);
+      xr[6] = __uint_as_float(b.z); xr[7] = __uint_as_float(b.w);
     }
+  }
+  static __device__ __forceinline__ void load_h(const float *h, int col, float *out) {
+    const float4 *q = reinterpret_cast<const float4 *>(h + col);
+    const float4 a = q[0], b = q[1];
+    out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w; out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
+  }
+  static __device__ __forceinline__ void make_x(const float *hv, float scale, int act_fmt, float *xr) {
+    float t[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) t[i] = hv[i] * scale;
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      xr[i] = act_fmt == MOE_A_BF16 ? __uint_as_float((uint32_t)f32_to_bf16_rne(t[i]) << 16) : t[i];
   }
   static __device__ __forceinline__ void dot(const u32x4 &w, const float *xr, float &a0, float &a1) {
     a0 = __builtin_fmaf(bf16_lo(w.x), xr[0], a0);
@@ -93,9 +123,21 @@ struct Chunk<MOE_W_BF16, false> {
 template <>
 struct Chunk<MOE_W_BF16, true> {
   static constexpr int VEC = 8, XW = 4;
+  template <bool COH>
   static __device__ __forceinline__ void load_x(const void *x, int, int col, float *xr) {
-    const u32x4 v = *reinterpret_cast<const u32x4 *>(static_cast<const uint16_t *>(x) + col);
+    const u32x4 v = ld128<COH>(static_cast<const uint16_t *>(x) + col);
     xr[0] = __uint_as_float(v.x); xr[1] = __uint_as_float(v.y); xr[2] = __uint_as_float(v.z); xr[3] = __uint_as_float(v.w);
+  }
+  static __device__ __forceinline__ void load_h(const float *h, int col, float *out) {
+    Chunk<MOE_W_BF16, false>::load_h(h, col, out);
+  }
+  static __device__ __forceinline__ void make_x(const float *hv, float scale, int, float *xr) {
+    float t[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) t[i] = hv[i] * scale;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      xr[i] = __uint_as_float((uint32_t)f32_to_bf16_rne(t[2 * i]) | ((uint32_t)f32_to_bf16_rne(t[2 * i + 1]) << 16));
   }
   static __device__ __forceinline__ void dot(const u32x4 &w, const float *xr, float &a0, float &a1) {
     a0 = dot2_bf16(w.x, __float_as_uint(xr[0]), a0);
@@ -116,20 +158,51 @@ struct RecRegs {
 
 // FMT: weight format; LPR: 16-byte loads per row per lane (d = LPR*64*VEC); NW: wavefronts per workgroup;
 // DEPTH: records in flight per wavefront; DOT2: packed bf16 dot products.
-template <int FMT, int LPR, int NW, int DEPTH, bool DOT2>
+// FUSED: workgroup 0 runs the layer boundary (x, gate GEMV, routing: rt::fused_boundary) instead of streaming
+// records.  The residual glue has been done by reduce_glue_kernel; every workgroup forms x for itself from the
+// new residual stream and its sums of squares (same operations in the same order everywhere, so all copies are
+// bit-identical), starts on the shared expert's records at once, and waits for the tag of the routing record only
+// before its first routed record (the shared records take longer than the routing), so the boundary costs the
+// launch next to nothing.  The wait is on workgroup 0 only, which is dispatched first, and is bounded.
+template <int FMT, int LPR, int NW, int DEPTH, bool DOT2, bool FUSED>
 __global__ __launch_bounds__(NW *kWave) void expert_gemv_kernel(GemvParams p) {
   using F = Chunk<FMT, DOT2>;
   constexpr int VEC = F::VEC, XW = F::XW;
   constexpr int CPL = LPR * VEC;  // columns per lane
-  __shared__ float red[kRedFloats];
+  __shared__ __attribute__((aligned(16))) float red[kRedFloats];
+  static_assert(rt::kBoundaryLdsWords <= kRedFloats, "the boundary borrows the reduction buffer");
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wavefront-uniform: keeps record addressing scalar
   const int d = p.hidden;
+  if constexpr (FUSED) {
+    if (blockIdx.x == 0) {
+      // with packed bf16 arithmetic the gate matrix has LPR 16-byte chunks per row per lane, and with NW = 8 each
+      // thread owns d / 512 = LPR columns of the glue; other cases take the general path
+      constexpr bool fast = DOT2 && NW == 8 && LPR <= 4;
+      static_assert(fast, "the launch variant with the boundary exists for packed bf16 arithmetic only");
+      rt::fused_boundary<NW, LPR, LPR, true>(p.b.route, p.b.glue, p.b.gate_w, p.b.state, p.b.out_dev, p.b.note,
+                                             rt::BoundaryFlags{p.b.tags, (int)gridDim.x},
+                                             rt::carve_boundary_lds(reinterpret_cast<uint32_t *>(red)));
+      float *row = p.partial + (int64_t)p.row_offset * d;  // this workgroup's partial row: nothing to add
+      for (int j = tid; j < d; j += NW * kWave) row[j] = 0.f;
+      return;
+    }
+  }
   const int64_t row16 = (int64_t)d / VEC;  // 16-byte chunks per row
   const int64_t rec_bytes = 3 * row16 * 16;
-  RecordWalker<NW> walk;
+  RecordWalker<NW, FUSED> walk;
   walk.init(p, wave);
+  // FUSED: the operands of x (this lane's columns of the residual stream, its sums of squares per 64 columns) are
+  // fetched first: a few small loads that complete before the weights queued behind them
+  OrderedSum<(FUSED && CPL <= 64) ? CPL : 1> blocks;  // d / 64 = CPL blocks of 64 columns
+  float hraw[FUSED ? CPL : 1];
+  if constexpr (FUSED) {
+    blocks.fetch(p.b.glue.ss, lane);
+#pragma unroll
+    for (int c = 0; c < LPR; ++c) F::load_h(p.b.glue.h, (c * kWave + lane) * VEC, &hraw[c * VEC]);
+    __builtin_amdgcn_sched_barrier(0);  // ... and stay ahead of them in the instruction stream
+  }
 
   auto issue = [&](RecRegs<LPR> &R) {
     R.wt = walk.wt;
@@ -170,8 +243,14 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_kernel(GemvParams p) {
 
   // activations: the lane keeps the x entries of its own columns in registers
   float xr[LPR * XW];
+  if constexpr (FUSED) {
+    const float scale = 1.0f / sqrtf(blocks.total() / (float)d + 1e-6f);
 #pragma unroll
-  for (int c = 0; c < LPR; ++c) F::load_x(p.x, p.act_fmt, (c * kWave + lane) * VEC, &xr[c * XW]);
+    for (int c = 0; c < LPR; ++c) F::make_x(&hraw[c * VEC], scale, p.act_fmt, &xr[c * XW]);
+  } else {
+#pragma unroll
+    for (int c = 0; c < LPR; ++c) F::template load_x<false>(p.x, p.act_fmt, (c * kWave + lane) * VEC, &xr[c * XW]);
+  }
 
   float y[CPL];
 #pragma unroll
@@ -260,15 +339,99 @@ __global__ __launch_bounds__(256) void partial_reduce_kernel(const float *partia
   }
 }
 
-template <int FMT, int LPR, int NW, int DEPTH, bool DOT2>
+// partial_reduce_kernel plus the residual glue of a stack for the same 64 columns:
+//   y = sum of the partial rows, rounded to the activation type (stored if y != nullptr)
+//   h = (carry ? h + y : 0) + perturb * a   (in place; y taken as 0 when there are no partial rows; a may be null)
+//   ss[block] = sum of h^2 over the block's 64 columns, in a fixed order
+__global__ __launch_bounds__(256) void reduce_glue_kernel(const float *partial, int n_partial, void *y, int d,
+                                                          int act_fmt, float *h, const float *a, float perturb,
+                                                          int carry, float *ss) {
+  __shared__ float4 acc_s[16][16];
+  __shared__ float sq_s[16];
+  const int tid = threadIdx.x, cl = tid & 15, rg = tid >> 4;
+  const int col = blockIdx.x * 64 + cl * 4;
+  float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+  const int chunk = (n_partial + 15) / 16;
+  const int b0 = rg * chunk, b1 = min(n_partial, b0 + chunk);
+#pragma unroll 8
+  for (int b = b0; b < b1; ++b) {
+    const float4 t = *reinterpret_cast<const float4 *>(partial + (int64_t)b * d + col);
+    acc.x += t.x;
+    acc.y += t.y;
+    acc.z += t.z;
+    acc.w += t.w;
+  }
+  acc_s[rg][cl] = acc;
+  __syncthreads();
+  if (rg == 0) {
+    float4 s = acc_s[0][cl];
+#pragma unroll
+    for (int g = 1; g < 16; ++g) {
+      const float4 t = acc_s[g][cl];
+      s.x += t.x;
+      s.y += t.y;
+      s.z += t.z;
+      s.w += t.w;
+    }
+    float yv[4] = {s.x, s.y, s.z, s.w};
+    if (act_fmt == MOE_A_BF16) {
+      uint16_t q[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        q[i] = f32_to_bf16_rne(yv[i]);
+        yv[i] = __uint_as_float((uint32_t)q[i] << 16);
+      }
+      if (y != nullptr) {
+        uint2 o;
+        o.x = (uint32_t)q[0] | ((uint32_t)q[1] << 16);
+        o.y = (uint32_t)q[2] | ((uint32_t)q[3] << 16);
+        *reinterpret_cast<uint2 *>(static_cast<uint16_t *>(y) + col) = o;
+      }
+    } else if (y != nullptr) {
+      *reinterpret_cast<float4 *>(static_cast<float *>(y) + col) = s;
+    }
+    const bool with_y = carry && n_partial > 0;
+    const float4 hv = carry ? *reinterpret_cast<const float4 *>(h + col) : make_float4(0.f, 0.f, 0.f, 0.f);
+    const float4 av = a != nullptr ? *reinterpret_cast<const float4 *>(a + col) : make_float4(0.f, 0.f, 0.f, 0.f);
+    float v[4] = {hv.x, hv.y, hv.z, hv.w};
+    const float aa[4] = {av.x, av.y, av.z, av.w};
+    float sq = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (with_y) v[i] += yv[i];
+      if (a != nullptr) v[i] = __builtin_fmaf(perturb, aa[i], v[i]);
+      sq = __builtin_fmaf(v[i], v[i], sq);
+    }
+    *reinterpret_cast<float4 *>(h + col) = make_float4(v[0], v[1], v[2], v[3]);
+    sq_s[cl] = sq;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) t += sq_s[i];
+    ss[blockIdx.x] = t;
+  }
+}
+
+template <int FMT, int LPR, int NW, int DEPTH, bool DOT2, bool FUSED = false>
 void launch_one(const GemvParams &p, int grid, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
-  hipExtLaunchKernelGGL((expert_gemv_kernel<FMT, LPR, NW, DEPTH, DOT2>), dim3(grid), dim3(NW * kWave), 0, s, e0, e1,
-                        0, p);
+  hipExtLaunchKernelGGL((expert_gemv_kernel<FMT, LPR, NW, DEPTH, DOT2, FUSED>), dim3(grid), dim3(NW * kWave), 0, s,
+                        e0, e1, 0, p);
 }
 
 template <int FMT, int LPR, bool DOT2>
 hipError_t launch_plan(const GemvParams &p, const GemvPlan &plan, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
   const int key = plan.waves * 10 + plan.depth;
+  if (p.fused) {  // only the default launch shape has the variant with the boundary in workgroup 0
+    if constexpr (LPR <= 4 && DOT2) {
+      if (key != 82 || plan.grid < 2) return hipErrorInvalidValue;
+      launch_one<FMT, LPR, 8, 2, DOT2, true>(p, plan.grid, s, e0, e1);
+      return hipGetLastError();
+    } else {
+      return hipErrorInvalidValue;
+    }
+  }
   switch (key) {
     case 42: launch_one<FMT, LPR, 4, 2, DOT2>(p, plan.grid, s, e0, e1); break;
     case 43: launch_one<FMT, LPR, 4, 3, DOT2>(p, plan.grid, s, e0, e1); break;
@@ -336,6 +499,12 @@ GemvPlan gemv_plan(int n_cus, int total_records, int weight_fmt, int act_fmt) {
   return pl;
 }
 
+bool gemv_fused_supported(int weight_fmt, int hidden, const GemvPlan &plan) {
+  if (weight_fmt != MOE_W_BF16 || !plan.dot2) return false;  // bf16 weights with bf16 activations
+  const int lpr = hidden / (kWave * 8);
+  return lpr <= 4 && plan.waves == 8 && plan.depth == 2 && plan.grid >= 2;  // (8 loads per row: out of registers)
+}
+
 hipError_t launch_expert_gemv(const GemvParams &p, int weight_fmt, const GemvPlan &plan, hipStream_t s,
                               hipEvent_t e0, hipEvent_t e1) {
   if (!gemv_shape_supported(weight_fmt, p.hidden)) return hipErrorInvalidValue;
@@ -355,6 +524,14 @@ hipError_t launch_partial_reduce(const float *partial, int n_partial, void *y, i
   if (hidden % 64 != 0) return hipErrorInvalidValue;
   hipLaunchKernelGGL(partial_reduce_kernel, dim3(hidden / 64), dim3(256), 0, s, partial, n_partial, y, hidden,
                      act_fmt);
+  return hipGetLastError();
+}
+
+hipError_t launch_reduce_glue(const float *partial, int n_partial, void *y, int hidden, int act_fmt, float *h,
+                              const float *a, float perturb, int carry, float *ss, hipStream_t s) {
+  if (hidden % 64 != 0 || hidden / 64 > 128) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(reduce_glue_kernel, dim3(hidden / 64), dim3(256), 0, s, partial, n_partial, y, hidden, act_fmt, h,
+                     a, perturb, carry, ss);
   return hipGetLastError();
 }
 

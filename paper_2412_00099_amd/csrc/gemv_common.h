@@ -58,7 +58,53 @@ __device__ __forceinline__ void wave_sum2(float &a, float &b) {
 // skewed by XCD parity) leave the kernel time unchanged - the XCDs that finish early free bandwidth for the
 // late ones, so the spread is not lost time.  Fixed shares keep the summation order of y, hence y itself,
 // identical from run to run.
-template <int NW>
+// Bounded wait for a tag another workgroup of the same launch publishes after an agent-scope release fence.
+// False if it did not appear within about a tenth of a second (the caller then skips its work and reports).
+// No agent-scope acquire follows: it would invalidate the XCD's L2 under thirty-two streaming compute units
+// (measured: the launch ran at half speed).  What the tag announces is read with ld128<true> / ld64<true> instead.
+constexpr int kTagSpins = 1 << 18;
+__device__ __forceinline__ bool wait_tag(const uint32_t *word, uint32_t tag) {
+  for (int i = 0; i < kTagSpins; ++i) {
+    const uint32_t v = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if ((uint32_t)__builtin_amdgcn_readfirstlane((int)v) == tag) {
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // keeps the loads that follow behind the poll
+      return true;
+    }
+    __builtin_amdgcn_s_sleep(2);
+  }
+  return false;
+}
+
+// 16 / 8 bytes; COH: with agent-scope atomic loads, which see what another workgroup of the same launch wrote
+// before its release fence whatever this XCD's L2 holds for the address
+template <bool COH>
+__device__ __forceinline__ u32x4 ld128(const void *p) {
+  if constexpr (COH) {
+    const uint64_t *q = static_cast<const uint64_t *>(p);
+    const uint64_t a = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint64_t b = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    u32x4 v;
+    v.x = (uint32_t)a; v.y = (uint32_t)(a >> 32); v.z = (uint32_t)b; v.w = (uint32_t)(b >> 32);
+    return v;
+  } else {
+    return *static_cast<const u32x4 *>(p);
+  }
+}
+template <bool COH>
+__device__ __forceinline__ u32x2 ld64(const void *p) {
+  if constexpr (COH) {
+    const uint64_t a = __hip_atomic_load(static_cast<const uint64_t *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    u32x2 v;
+    v.x = (uint32_t)a; v.y = (uint32_t)(a >> 32);
+    return v;
+  } else {
+    return *static_cast<const u32x2 *>(p);
+  }
+}
+
+// FUSED: workgroup 0 of the launch runs the layer boundary; the records are shared among workgroups 1..G-1 and
+// the routing record is loaded only when the first routed entry comes up, after its tag has appeared.
+template <int NW, bool FUSED = false>
 struct RecordWalker {
   int s0, q0, ns, nl;  // this workgroup's shared rows start at s0 (ns of them), routed records at q0; nl entries
   int idx;             // next list entry of this wavefront
@@ -75,13 +121,17 @@ struct RecordWalker {
   // start of workgroup b's share of n records
   static __device__ __forceinline__ int bound(int b, int n, int G) { return (int)((int64_t)b * n / G); }
 
-  __device__ __forceinline__ void init(const GemvParams &p, int wave) {
-    const int G = gridDim.x, b = blockIdx.x;
-    // the routing record first: these loads return before any weight load issued after them
+  __device__ __forceinline__ void load_record(const GemvParams &p) {
     const u32x4 *rr = reinterpret_cast<const u32x4 *>(p.route);
-    rw0 = rr[offsetof(moe_route_out_t, sel_weight) / 16];
-    rw1 = rr[offsetof(moe_route_out_t, sel_weight) / 16 + 1];
-    rd = rr[offsetof(moe_route_out_t, seq) / 16];
+    rw0 = ld128<FUSED>(rr + offsetof(moe_route_out_t, sel_weight) / 16);
+    rw1 = ld128<FUSED>(rr + offsetof(moe_route_out_t, sel_weight) / 16 + 1);
+    rd = ld128<FUSED>(rr + offsetof(moe_route_out_t, seq) / 16);
+  }
+
+  __device__ __forceinline__ void init(const GemvParams &p, int wave) {
+    const int G = FUSED ? (int)gridDim.x - 1 : (int)gridDim.x, b = FUSED ? (int)blockIdx.x - 1 : (int)blockIdx.x;
+    // the routing record first: these loads return before any weight load issued after them
+    if constexpr (!FUSED) load_record(p);
     const int routed = p.top_k * p.inter;
     const int shared = p.pass == 0 ? p.shared_inter : 0;
     s0 = bound(b, shared, G);
@@ -125,9 +175,19 @@ struct RecordWalker {
       return true;
     }
     if (seg < 0) {  // first routed entry: unpack the routing record, locate the entry
+      bool ok = true;
+      if constexpr (FUSED) {
+        ok = wait_tag(p.b.tags + 16 * (int)blockIdx.x, p.b.route.seq);
+        load_record(p);
+      }
       slots = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)rd.y) |
               ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)rd.z) << 32);
       miss_mask = (uint32_t)__builtin_amdgcn_readfirstlane((int)rd.w);
+      if (!ok) {  // no record: read slot 0 and use nothing of it
+        slots = 0;
+        miss_mask = p.pass == 1 ? 0u : ~0u;
+        *p.b.gave_up = 1u;
+      }
       const int r = q0 + (idx - ns);
       seg = r / I;
       row = r - seg * I;

@@ -60,6 +60,13 @@ struct moe_cache {
     uint8_t expert[MOE_MAX_TOPK] = {}, slot[MOE_MAX_TOPK] = {};
   };
   std::vector<Decision> decided;
+  // layer boundaries deferred into the expert launch (see BoundaryArgs)
+  std::vector<BoundaryArgs> boundary;
+  uint32_t *d_tags = nullptr;       // [grid] publication tags, 64 bytes apart
+  float *d_ss = nullptr;            // [128] sums of squares of the residual stream per 64 columns
+  uint32_t *h_gave_up = nullptr;    // pinned, mapped: set by a wavefront that stopped waiting for a tag
+  uint32_t *h_gave_up_dev = nullptr;
+  bool fuse_boundary = true;        // MOE_FUSE_BOUNDARY=0 keeps the boundary a launch of its own
   int32_t *d_initial = nullptr;
   float *d_partial = nullptr;
   int pending_rows = 0;            // partial rows of an expert output not reduced yet (y_dev was NULL)
@@ -67,7 +74,8 @@ struct moe_cache {
   GemvPlan plan{};
   hipEvent_t ev_route = nullptr;
   std::vector<hipEvent_t> ev_copy;
-  std::vector<uint8_t> routed;        // per layer: 0 idle, 1 routed (decision on the host), 2 routed (not collected yet)
+  std::vector<uint8_t> routed;        // per layer: 0 idle, 1 routed (decision on the host), 2 routed (not collected
+                                      // yet), 3 boundary deferred into the expert launch
   std::vector<uint32_t> route_seq;    // per layer: completion tag of the pending route step
   std::vector<int64_t> bytes_filled;
   uint32_t seq = 0;
@@ -85,6 +93,8 @@ namespace {
 int check_layer(const moe_cache_t *ctx, int32_t layer) {
   if (!ctx) return fail(MOE_EINVAL, "context is NULL");
   if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(MOE_EINVAL, "layer %d out of range [0,%d)", layer, ctx->cfg.n_layers);
+  if (ctx->h_gave_up && __atomic_load_n(ctx->h_gave_up, __ATOMIC_RELAXED) != 0)
+    return fail(MOE_EHIP, "an expert kernel gave up waiting for the layer boundary of its own launch: outputs since then are invalid");
   return MOE_OK;
 }
 
@@ -198,6 +208,7 @@ int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, 
   c->routed.assign(L, 0);
   c->route_seq.assign(L, 0);
   c->decided.assign(L, {});
+  c->boundary.assign(L, BoundaryArgs{});
   c->bytes_filled.assign(L, 0);
   c->ev_copy.assign(L, nullptr);
 
@@ -231,6 +242,15 @@ int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, 
                          hipHostMallocMapped | hipHostMallocCoherent));
   memset(c->h_note, 0, sizeof(HostNote) * L);
   HIP_INIT(hipHostGetDevicePointer(reinterpret_cast<void **>(&c->h_note_dev), c->h_note, 0));
+  HIP_INIT(hipMalloc(&c->d_tags, sizeof(uint32_t) * 16 * (size_t)c->plan.grid));
+  HIP_INIT(hipMemset(c->d_tags, 0, sizeof(uint32_t) * 16 * (size_t)c->plan.grid));
+  HIP_INIT(hipMalloc(&c->d_ss, sizeof(float) * 128));
+  HIP_INIT(hipMemset(c->d_ss, 0, sizeof(float) * 128));
+  HIP_INIT(hipHostMalloc(reinterpret_cast<void **>(&c->h_gave_up), sizeof(uint32_t),
+                         hipHostMallocMapped | hipHostMallocCoherent));
+  *c->h_gave_up = 0;
+  HIP_INIT(hipHostGetDevicePointer(reinterpret_cast<void **>(&c->h_gave_up_dev), c->h_gave_up, 0));
+  if (const char *s = getenv("MOE_FUSE_BOUNDARY")) c->fuse_boundary = atoi(s) != 0;
   HIP_INIT(hipMalloc(&c->d_initial, sizeof(int32_t) * (size_t)L * (b->n_initial > 0 ? b->n_initial : 1)));
   HIP_INIT(hipMalloc(&c->d_partial, sizeof(float) * 2 * (size_t)c->plan.grid * cfg->hidden));
   HIP_INIT(hipMalloc(&c->d_y, sizeof(float) * (size_t)cfg->hidden));
@@ -250,6 +270,9 @@ void moe_cache_destroy(moe_cache_t *c) {
   if (c->d_state) (void)hipFree(c->d_state);
   if (c->d_route) (void)hipFree(c->d_route);
   if (c->h_note) (void)hipHostFree(c->h_note);
+  if (c->d_tags) (void)hipFree(c->d_tags);
+  if (c->d_ss) (void)hipFree(c->d_ss);
+  if (c->h_gave_up) (void)hipHostFree(c->h_gave_up);
   if (c->d_initial) (void)hipFree(c->d_initial);
   if (c->d_partial) (void)hipFree(c->d_partial);
   if (c->d_y) (void)hipFree(c->d_y);
@@ -378,22 +401,44 @@ int moe_stack_route_step(moe_cache_t *c, int32_t layer, float *h_dev, const floa
   if (c->cfg.hidden > kFusedMaxHidden) return fail(MOE_EINVAL, "hidden exceeds %d", kFusedMaxHidden);
   if (c->routed[layer]) return fail(MOE_ESTATE, "layer %d: previous route step not followed by moe_expert_forward", layer);
   const RouteParams p = make_route_params(c);
+  const bool in_launch = !out_host && c->fuse_boundary &&
+                         gemv_fused_supported(c->cfg.weight_fmt, c->cfg.hidden, c->plan) && c->cfg.hidden % 64 == 0;
   // the pending expert output is summed first (into y_dev if given, else into the library's own buffer)
   void *y = nullptr;
-  if (c->pending_rows > 0) {
-    y = y_dev ? y_dev : c->d_y;
-    HIP_TRY(launch_partial_reduce(c->d_partial, c->pending_rows, y, c->cfg.hidden, c->cfg.act_fmt, c->compute));
-  }
+  if (c->pending_rows > 0) y = y_dev ? y_dev : c->d_y;
   FusedParams f{};
-  f.y = y;
   f.h = h_dev;
+  f.x_out = x_dev;
+  if (in_launch) {
+    // nobody waits for the decision here: the sum of the pending output and the residual glue are one launch, and
+    // the rest of the boundary (x, gate GEMV, routing) runs in workgroup 0 of the layer's expert launch
+    HIP_TRY(launch_reduce_glue(c->d_partial, c->pending_rows, y, c->cfg.hidden, c->cfg.act_fmt, h_dev, a_dev, perturb,
+                               carry, c->d_ss, c->compute));
+    c->pending_rows = 0;
+    f.ss = c->d_ss;
+    f.n_ss = c->cfg.hidden / 64;
+    BoundaryArgs &b = c->boundary[layer];
+    b.route = p;
+    b.glue = f;
+    b.gate_w = c->gate_w[layer];
+    b.state = c->d_state + layer;
+    b.out_dev = c->d_route + layer;
+    b.note = c->h_note_dev + layer;
+    b.tags = c->d_tags;
+    b.gave_up = c->h_gave_up_dev;
+    c->route_seq[layer] = p.seq;
+    c->routed[layer] = 3;
+    return MOE_OK;
+  }
+  if (c->pending_rows > 0)
+    HIP_TRY(launch_partial_reduce(c->d_partial, c->pending_rows, y, c->cfg.hidden, c->cfg.act_fmt, c->compute));
+  c->pending_rows = 0;
+  f.y = y;
   f.a = a_dev;
   f.perturb = perturb;
   f.carry = carry;
-  f.x_out = x_dev;
   HIP_TRY(launch_fused_route(p, f, c->gate_w[layer], c->d_state + layer, c->d_route + layer, c->h_note_dev + layer,
                              c->compute));
-  c->pending_rows = 0;
   return finish_route_call(c, layer, p.seq, out_host);
 }
 
@@ -419,6 +464,12 @@ int moe_expert_forward(moe_cache_t *c, int32_t layer, const void *x_dev, void *y
   // the device record, so it is launched before the host knows the decision
   p.pass = 0;
   p.row_offset = 0;
+  if (c->routed[layer] == 3) {
+    if (x_dev != c->boundary[layer].glue.x_out)
+      return fail(MOE_EINVAL, "layer %d: x_dev must be the vector moe_stack_route_step wrote", layer);
+    p.fused = 1;
+    p.b = c->boundary[layer];
+  }
   const bool prof = c->profiling && c->prof_used < (1u << 16);
   if (prof) {
     if (c->prof_used == c->prof_events.size()) {
@@ -433,8 +484,9 @@ int moe_expert_forward(moe_cache_t *c, int32_t layer, const void *x_dev, void *y
   } else {
     HIP_TRY(launch_expert_gemv(p, g.weight_fmt, c->plan, c->compute));
   }
+  p.fused = 0;
   int n_miss = c->decided[layer].n_miss;
-  if (c->routed[layer] == 2) {
+  if (c->routed[layer] >= 2) {
     if (int rc = collect_route(c, layer, c->route_seq[layer], &n_miss)) return rc;
   }
   if (prof) c->prof_full[c->prof_used++] = n_miss == 0;
@@ -458,7 +510,7 @@ int moe_expert_forward(moe_cache_t *c, int32_t layer, const void *x_dev, void *y
 int moe_cache_last_route(moe_cache_t *c, int32_t layer, moe_route_out_t *out) {
   if (int rc = check_layer(c, layer)) return rc;
   if (!out) return fail(MOE_EINVAL, "out is NULL");
-  if (c->routed[layer] == 2) return fail(MOE_ESTATE, "layer %d: routing decision not collected yet", layer);
+  if (c->routed[layer] >= 2) return fail(MOE_ESTATE, "layer %d: routing decision not collected yet", layer);
   return fetch_record(c, layer, out);
 }
 

@@ -162,9 +162,21 @@ __device__ __forceinline__ CacheRegs load_cache_regs(const LayerState *st, int l
   return cr;
 }
 
+// Where a layer-boundary step announces its routing record to the other workgroups of the same launch (expert
+// kernels that run the boundary in their first workgroup): every waiting workgroup b polls a word of its own,
+// 64 bytes apart (thousands of wavefronts polling one address serialise in the memory system):
+//   words[16*b] = tag once the routing record is in memory, b < n.
+// words = nullptr when nobody waits (separate router launch).
+struct BoundaryFlags {
+  uint32_t *words;
+  int n;
+};
+constexpr int kTagStride = 16;  // dwords
+
 // Everything after the logits (Eq. 3 softmax, Eq. 10, Eq. 9, Eq. 2, Eq. 4, Sec. 4.2), run by one wavefront.
 __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_s, const CacheRegs &cr, LayerState *st,
-                                           moe_route_out_t *out_dev, HostNote *note, uint32_t *rec_s, int lane) {
+                                           moe_route_out_t *out_dev, HostNote *note, uint32_t *rec_s, int lane,
+                                           BoundaryFlags flags = BoundaryFlags{nullptr, 0}) {
 #pragma clang fp contract(off)
   const int N = p.n_experts, K = p.top_k, C = p.capacity;
   int my_slot = cr.my_slot, slot_exp = cr.slot_exp;
@@ -204,25 +216,21 @@ __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_
   int rank_p;    // position in the altered ranking r' (exact for the first K positions, >= K otherwise)
   float zp = z;  // altered logits (Cache-Prior only)
   float margin = INFINITY;  // between the K-th and (K+1)-th altered logit (tie logging)
+  uint64_t taken = 0;       // Cache-Prior: the experts placed so far
+  float kth = 0.f;
   if (p.route_mode == MOE_ROUTE_CACHE_PRIOR) {
     const float bias = p.lambda * delta;               // one rounding
     if (active && (resident || top_j)) zp = z + bias;  // one rounding (Eq. 9)
-    // only the head of r' matters: K (+1 for the margin) rounds of arg-max, ties -> lower index
+    // only the head of r' matters: K rounds of arg-max, ties -> lower index (one more round, for the margin,
+    // follows once the decision has been handed on)
     rank_p = N;
-    uint64_t taken = 0;
-    float kth = 0.f;
-    const int rounds = K < N ? K + 1 : K;
-    for (int k = 0; k < rounds; ++k) {
+    for (int k = 0; k < K; ++k) {
       const bool cand = active && !((taken >> lane) & 1);
       const float m = wave_max(cand ? zp : -INFINITY);
       const int l = (int)__builtin_ctzll(ballot(cand && zp == m));
-      if (k < K) {
-        taken |= 1ull << l;
-        if (lane == l) rank_p = k;
-        kth = m;
-      } else {
-        margin = kth - m;
-      }
+      taken |= 1ull << l;
+      if (lane == l) rank_p = k;
+      kth = m;
     }
   } else {
     // Max-Rank (Eq. 6-7) / Cumsum-Threshold (Eq. 8): two promote() passes = a three-class stable partition
@@ -315,6 +323,36 @@ __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_
     const uint64_t w0 = (uint64_t)p.seq | ((uint64_t)n_miss << 32) | ((uint64_t)mm << 40);
     const uint64_t v = lane == 0 ? w0 : (tag | (lane == 1 ? ew : sw));
     __hip_atomic_store(&note->w[lane], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+  }
+
+  // ---- expert kernels waiting in the same launch need weights, slots and miss flags: those parts of the record
+  // go out first, followed by one release fence and the tags
+  if (flags.words != nullptr) {
+    if (lane < MOE_MAX_TOPK) rec_s[W_WEIGHT + lane] = 0u;
+    __builtin_amdgcn_wave_barrier();
+    if (sel) rec_s[W_WEIGHT + rank_p] = __float_as_uint(w);
+    if (lane == 0) {
+      rec_s[W_SEQ] = p.seq;
+      rec_s[W_SEQ + 1] = lo;
+      rec_s[W_SEQ + 2] = hi;
+      rec_s[W_SEQ + 3] = mm;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    if (lane < 3) {
+      const int chunk = lane < 2 ? W_WEIGHT / 4 + lane : W_SEQ / 4;
+      reinterpret_cast<u32x4 *>(out_dev)[chunk] = reinterpret_cast<const u32x4 *>(rec_s)[chunk];
+    }
+    __threadfence();
+    for (int b = lane; b < flags.n; b += kWave)
+      __hip_atomic_store(flags.words + kTagStride * b, p.seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+
+  // margin between the K-th and (K+1)-th altered logit: one more arg-max round
+  if (p.route_mode == MOE_ROUTE_CACHE_PRIOR && K < N) {
+    const bool cand = active && !((taken >> lane) & 1);
+    margin = kth - wave_max(cand ? zp : -INFINITY);
   }
 
   // ---- state back to device memory ------------------------------------------------------------
@@ -454,13 +492,6 @@ __device__ __forceinline__ void store_bf16(uint16_t *p, const float *v) {
 }
 
 
-// Where a layer-boundary step publishes its two results for the other workgroups of the same launch (expert
-// kernels that run the boundary in their first workgroup): word 0 = tag once x is in memory, word 1 = tag once the
-// routing record is.  nullptr when nobody waits (separate router launch).
-struct BoundaryFlags {
-  uint32_t *words;
-};
-
 // LDS the boundary needs (the caller provides it): logits, record staging, per-wavefront partial sums, x.
 struct BoundaryLds {
   float *z_s;        // [MOE_MAX_EXPERTS]
@@ -488,8 +519,11 @@ __device__ __forceinline__ BoundaryLds carve_boundary_lds(uint32_t *base) {  // 
 // (cache state, glue operands, gate rows) are then issued unconditionally and in that order, so each use waits
 // only for the loads ahead of it (a load inside a branch makes the compiler wait for all outstanding loads,
 // which would serialise the memory round trips).  PER == 0: any d, columns t, t + NW*64, ... per thread.
+// PRE: the glue has been done by reduce_glue_kernel (f.h is the new residual stream, f.ss its sums of squares
+// per 64 columns); only x is formed here, with the same operations in the same order as the expert kernels use
+// to form their own copy of x, so that both are bit-identical.
 // All threads of the workgroup must call it; only wavefront 0 returns late (after the routing).
-template <int NW, int CH, int PER>
+template <int NW, int CH, int PER, bool PRE = false>
 __device__ __forceinline__ void fused_boundary(const RouteParams &p, const FusedParams &f, const void *gate_w,
                                                LayerState *st, moe_route_out_t *out_dev, HostNote *note,
                                                BoundaryFlags flags, const BoundaryLds &lds) {
@@ -510,7 +544,20 @@ __device__ __forceinline__ void fused_boundary(const RouteParams &p, const Fused
   CacheRegs cr{};
   GateRegs<R, (CH > 0 ? CH : 1)> greg;
 
-  if constexpr (PER > 0) {
+  float tot_pre = 0.f;
+  if constexpr (PRE) {
+    static_assert(PER > 0, "the precomputed-glue path is only built for the vectorised column split");
+    cr = load_cache_regs(st, lane, N, p.capacity);
+    load_f32<PER>(f.h + tid * PER, hv);
+    OrderedSum<NW * PER> blocks;  // d / 64 = NW * PER blocks of 64 columns
+    blocks.fetch(f.ss, lane);
+    __builtin_amdgcn_sched_barrier(0);  // the small loads stay ahead of the gate rows
+    if constexpr (CH > 0) {
+      const int r0 = min(row0, N - 1);
+      gate_prefetch<R, (CH > 0 ? CH : 1)>(gate_w, r0, max(1, min(R, N - r0)), lane, greg);
+    }
+    tot_pre = blocks.total();
+  } else if constexpr (PER > 0) {
     // every wavefront loads the cache state (only wavefront 0 uses it): unconditional, and the oldest loads
     cr = load_cache_regs(st, lane, N, p.capacity);
     // operands that are absent are read from h instead (any valid address) and masked out below
@@ -552,7 +599,7 @@ __device__ __forceinline__ void fused_boundary(const RouteParams &p, const Fused
 
   float ss = 0.f;
 #pragma unroll
-  for (int i = 0; i < kMaxPer; ++i) {
+  for (int i = 0; i < (PRE ? 0 : kMaxPer); ++i) {
     const int j = PER > 0 ? tid * PER + i : tid + i * NT;
     if (PER > 0 || j < d) {
       float v;
@@ -573,12 +620,14 @@ __device__ __forceinline__ void fused_boundary(const RouteParams &p, const Fused
       if (PER == 0) f.h[j] = v;
     }
   }
-  if constexpr (PER > 0) store_f32<PER>(f.h + tid * PER, hv);
-  ss = wave_sum(ss);
-  if (lane == 0) part_s[wave] = ss;
-  __syncthreads();
-  float tot = 0.f;
-  for (int w = 0; w < NW; ++w) tot += part_s[w];
+  float tot = tot_pre;
+  if constexpr (!PRE) {
+    if constexpr (PER > 0) store_f32<PER>(f.h + tid * PER, hv);
+    ss = wave_sum(ss);
+    if (lane == 0) part_s[wave] = ss;
+    __syncthreads();
+    for (int w = 0; w < NW; ++w) tot += part_s[w];
+  }
   const float scale = 1.0f / sqrtf(tot / (float)d + 1e-6f);
   if constexpr (PER > 0) {
     float xv[PER];
@@ -609,10 +658,9 @@ __device__ __forceinline__ void fused_boundary(const RouteParams &p, const Fused
       }
     }
   }
-  if (flags.words != nullptr) __threadfence();  // x (and h) on their way to memory before the barrier
-  __syncthreads();
-  if (flags.words != nullptr && tid == 0)
-    __hip_atomic_store(flags.words, p.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+  // x is in LDS: a workgroup barrier that waits for the LDS writes only (__syncthreads would also wait for the gate
+  // rows still on their way and for the stores of x)
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
   // ---- gate GEMV on x in LDS ----------------------------------------------------------------------
   if (nrows > 0) {
@@ -627,11 +675,7 @@ __device__ __forceinline__ void fused_boundary(const RouteParams &p, const Fused
   }
   __syncthreads();
   if (wave != 0) return;
-  route_wave(p, z_s, cr, st, out_dev, note, lds.rec_s, lane);
-  if (flags.words != nullptr) {
-    __threadfence();  // the record before its tag
-    if (lane == 0) __hip_atomic_store(flags.words + 1, p.seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-  }
+  route_wave(p, z_s, cr, st, out_dev, note, lds.rec_s, lane, flags);
 }
 
 }  // namespace rt
