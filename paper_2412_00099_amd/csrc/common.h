@@ -59,6 +59,11 @@ struct BoundaryArgs {
   uint32_t *tags;            // device words [grid] 64 bytes apart: "routing record published", one copy per
                              // workgroup (compared with route.seq)
   uint32_t *gave_up;         // mapped host word set when a wavefront stopped waiting for a tag
+  // what the boundary of the layer that follows will read first (its gate matrix and cache state): workgroup 0
+  // touches it once its own work is done, which measurably shortens that boundary (nullptr: don't)
+  const void *next_gate_w;
+  const LayerState *next_state;
+  int64_t gate_bytes;
 };
 
 struct GemvParams {

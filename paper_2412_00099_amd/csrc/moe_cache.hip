@@ -67,6 +67,7 @@ struct moe_cache {
   uint32_t *h_gave_up = nullptr;    // pinned, mapped: set by a wavefront that stopped waiting for a tag
   uint32_t *h_gave_up_dev = nullptr;
   bool fuse_boundary = true;        // MOE_FUSE_BOUNDARY=0 keeps the boundary a launch of its own
+  bool prefetch_gate = true;        // MOE_PREFETCH_GATE=0: workgroup 0 does not touch the next layer's gate matrix
   int32_t *d_initial = nullptr;
   float *d_partial = nullptr;
   int pending_rows = 0;            // partial rows of an expert output not reduced yet (y_dev was NULL)
@@ -251,6 +252,7 @@ int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, 
   *c->h_gave_up = 0;
   HIP_INIT(hipHostGetDevicePointer(reinterpret_cast<void **>(&c->h_gave_up_dev), c->h_gave_up, 0));
   if (const char *s = getenv("MOE_FUSE_BOUNDARY")) c->fuse_boundary = atoi(s) != 0;
+  if (const char *s = getenv("MOE_PREFETCH_GATE")) c->prefetch_gate = atoi(s) != 0;
   HIP_INIT(hipMalloc(&c->d_initial, sizeof(int32_t) * (size_t)L * (b->n_initial > 0 ? b->n_initial : 1)));
   HIP_INIT(hipMalloc(&c->d_partial, sizeof(float) * 2 * (size_t)c->plan.grid * cfg->hidden));
   HIP_INIT(hipMalloc(&c->d_y, sizeof(float) * (size_t)cfg->hidden));
@@ -426,6 +428,9 @@ int moe_stack_route_step(moe_cache_t *c, int32_t layer, float *h_dev, const floa
     b.note = c->h_note_dev + layer;
     b.tags = c->d_tags;
     b.gave_up = c->h_gave_up_dev;
+    b.next_gate_w = c->prefetch_gate ? c->gate_w[(layer + 1) % c->cfg.n_layers] : nullptr;
+    b.next_state = c->d_state + (layer + 1) % c->cfg.n_layers;
+    b.gate_bytes = (int64_t)c->cfg.n_experts * c->cfg.hidden * (c->cfg.act_fmt == MOE_A_BF16 ? 2 : 4);
     c->route_seq[layer] = p.seq;
     c->routed[layer] = 3;
     return MOE_OK;
