@@ -37,7 +37,7 @@ GEMV_TRAFFIC = {
     "fetch_kib": 67717.1, "fetch_scale": 2.0,
     "write_kib": 2048.0, "write_scale": 1.0,
 }
-GEMV_SOURCES = ("expert_gemv.hip", "gemv_common.h", "common.h")
+GEMV_SOURCES = ("expert_gemv.hip", "gemv_common.h", "route_device.h", "common.h")
 
 
 def gemv_sources_hash():
@@ -255,6 +255,23 @@ def main():
         log(f"miss-free: {r['tok_s']:.1f} tok/s")
         dec.set_lambda(HEADLINE_LAMBDA)
 
+    # the expert kernel as a launch of its own (layer boundary in a separate launch), for comparison: a second context
+    # on the same store, created with the in-launch boundary switched off, over the same tokens
+    alone = None
+    if not args.no_sweep:
+        os.environ["MOE_FUSE_BOUNDARY"] = "0"
+        dec2 = pkg.MoEDecoder(store, top_k=cfg.top_k, top_j=cfg.top_j, lam=HEADLINE_LAMBDA, renormalize=cfg.renormalize)
+        del os.environ["MOE_FUSE_BOUNDARY"]
+        r2 = timed_run(dec2, a, h, x, y, args.warmup, args.steps)
+        dec2.profile(True, reset=True)
+        timed_run(dec2, a, h, x, y, args.warmup, args.steps)
+        us2, n2 = dec2.profile(False, reset=True)
+        dec2.close()
+        alone = dict(tok_s=round(r2["tok_s"], 2), expert_kernel_us=round(us2, 3), launches=n2,
+                     GBps=round(algo_bytes / (us2 * 1e-6) / 1e9, 1) if us2 > 0 else 0.0,
+                     frac=round(algo_bytes / (us2 * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if us2 > 0 else 0.0)
+        log(f"boundary as its own launch: {r2['tok_s']:.1f} tok/s, expert kernel {us2:.2f} us")
+
     link_gbs = host_link_rate(store)
     log(f"miss fill copy: {link_gbs:.1f} GB/s")
 
@@ -321,10 +338,12 @@ def main():
         "roofline": {
             "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(cfg.name),
-            "kernel": "expert_gemv_kernel", "algorithmic_bytes_per_launch": algo_bytes,
+            "kernel": "expert_gemv_kernel (layer boundary in its first workgroup)",
+            "algorithmic_bytes_per_launch": algo_bytes,
             "avg_launch_us": round(gemv_us, 3), "launches": gemv_launches,
             "tok_s_while_profiled": round(prof["tok_s"], 2),
         },
+        "boundary_as_separate_launch": alone,
         "cpu_baseline": cpu,
         "lambda_sweep": sweep,
     }
