@@ -207,6 +207,15 @@ int moe_trace_misses(const int32_t *trace, int64_t n_tokens, int32_t top_k, int3
                      int32_t policy, const int32_t *initial, int32_t n_initial, int64_t *misses,
                      int64_t *lifetime_sum, int64_t *evictions);
 
+/* The launch shape the context chose for the expert kernels, and whether a moe_stack_route_step without out_host
+ * runs its routing inside the layer's expert launch (bf16 activations, a supported shape, and a shared expert of at
+ * least a third of the layer's records; MOE_FUSE_BOUNDARY=0 or 1 in the environment at moe_cache_init overrides
+ * the last condition). */
+typedef struct moe_cache_plan {
+  int32_t grid, wavefronts, depth, packed_bf16_dot, boundary_in_expert_launch;
+} moe_cache_plan_t;
+int moe_cache_plan(moe_cache_t *ctx, moe_cache_plan_t *out_host);
+
 /* Average duration in microseconds of the expert-GEMV launches that covered a whole layer (no expert missing)
  * since the last call with reset != 0, and their count; measured with start/stop events attached to the
  * launches on compute_stream while profiling is enabled. */

@@ -88,6 +88,10 @@ class moe_cache_stats_t(C.Structure):
     ]
 
 
+class moe_cache_plan_t(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("grid", "wavefronts", "depth", "packed_bf16_dot", "boundary_in_expert_launch")]
+
+
 class moe_cache_tables_t(C.Structure):
     _fields_ = [
         ("expert_slot", C.c_int32 * MOE_MAX_EXPERTS),
@@ -126,6 +130,8 @@ lib.moe_cache_restore.argtypes = [_vp, C.c_int32, _vp, C.c_size_t]
 lib.moe_trace_misses.restype = C.c_int
 lib.moe_trace_misses.argtypes = [_vp, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _vp, C.c_int32,
                                  C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+lib.moe_cache_plan.restype = C.c_int
+lib.moe_cache_plan.argtypes = [_vp, C.POINTER(moe_cache_plan_t)]
 lib.moe_cache_set_lambda.restype = C.c_int
 lib.moe_cache_set_lambda.argtypes = [_vp, C.c_float]
 lib.moe_cache_set_baseline.restype = C.c_int
@@ -142,7 +148,7 @@ lib.moe_last_error.argtypes = []
 EXPORTS = [
     "moe_blob_bytes", "moe_pack_expert", "moe_cache_init", "moe_cache_destroy", "moe_route_step", "moe_stack_route_step",
     "moe_expert_forward", "moe_cache_last_route", "moe_cache_stats", "moe_cache_tables", "moe_cache_snapshot",
-    "moe_cache_restore", "moe_trace_misses", "moe_cache_set_lambda",
+    "moe_cache_restore", "moe_trace_misses", "moe_cache_plan", "moe_cache_set_lambda",
     "moe_cache_set_baseline", "moe_cache_reset", "moe_residual_rmsnorm", "moe_cache_profile", "moe_last_error",
 ]
 
@@ -250,6 +256,12 @@ def moe_trace_misses(trace, n_experts: int, capacity: int, policy: int = MOE_POL
                                 init.ctypes.data if init.size else None, init.size,
                                 C.byref(m), C.byref(life), C.byref(ev)), "moe_trace_misses")
     return m.value, life.value, ev.value
+
+
+def moe_cache_plan(ctx) -> moe_cache_plan_t:
+    out = moe_cache_plan_t()
+    _check(lib.moe_cache_plan(ctx, C.byref(out)), "moe_cache_plan")
+    return out
 
 
 def moe_cache_set_lambda(ctx, lam: float) -> None:

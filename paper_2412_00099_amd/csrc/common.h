@@ -111,7 +111,7 @@ struct GemvPlan {
   bool dot2;  // packed bf16 dot products (bf16 weights and activations)
 };
 GemvPlan gemv_plan(int n_cus, int total_records, int weight_fmt, int act_fmt);
-bool gemv_fused_supported(int weight_fmt, int hidden, const GemvPlan &plan);  // a launch variant with the boundary in workgroup 0
+bool gemv_fused_supported(int weight_fmt, int act_fmt, int hidden, const GemvPlan &plan);  // a launch variant with the boundary in workgroup 0
 hipError_t launch_fused_route(const RouteParams &p, const FusedParams &f, const void *gate_w, LayerState *state,
                               moe_route_out_t *out_dev, HostNote *note_mapped, hipStream_t s);
 hipError_t launch_expert_gemv(const GemvParams &p, int weight_fmt, const GemvPlan &plan, hipStream_t s,

@@ -178,26 +178,9 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_kernel(GemvParams p) {
   if constexpr (FUSED) {
     if (blockIdx.x == 0) {
       // with packed bf16 arithmetic the gate matrix has LPR 16-byte chunks per row per lane, and with NW = 8 each
-      // thread owns d / 512 = LPR columns of the glue; other cases take the general path
-      constexpr bool fast = DOT2 && NW == 8 && LPR <= 4;
-      static_assert(fast, "the launch variant with the boundary exists for packed bf16 arithmetic only");
-      rt::fused_boundary<NW, LPR, LPR, true>(p.b.route, p.b.glue, p.b.gate_w, p.b.state, p.b.out_dev, p.b.note,
-                                             rt::BoundaryFlags{p.b.tags, (int)gridDim.x},
-                                             rt::carve_boundary_lds(reinterpret_cast<uint32_t *>(red)));
-      float *row = p.partial + (int64_t)p.row_offset * d;  // this workgroup's partial row: nothing to add
-      for (int j = tid; j < d; j += NW * kWave) row[j] = 0.f;
-      if (p.b.next_gate_w != nullptr) {
-        // this compute unit is idle for the rest of the launch: pull what the next boundary reads first towards it
-        const u32x4 *g = static_cast<const u32x4 *>(p.b.next_gate_w);
-        uint32_t acc = 0;
-        for (int64_t i = tid; i < p.b.gate_bytes / 16; i += NW * kWave) {
-          const u32x4 v = g[i];
-          acc ^= v.x ^ v.y ^ v.z ^ v.w;
-        }
-        for (int i = tid; i < (int)(sizeof(LayerState) / 4); i += NW * kWave)
-          acc ^= reinterpret_cast<const uint32_t *>(p.b.next_state)[i];
-        if (acc == 0x9e3779b9u && p.b.gate_bytes < 0) row[0] = 1.f;  // never true: keeps the loads
-      }
+      // thread owns d / 512 = LPR columns
+      static_assert(DOT2 && NW == 8 && LPR <= 4, "the launch variant with the boundary exists for this case only");
+      rt::boundary_workgroup<NW, LPR, LPR>(p, red);
       return;
     }
   }
@@ -511,10 +494,15 @@ GemvPlan gemv_plan(int n_cus, int total_records, int weight_fmt, int act_fmt) {
   return pl;
 }
 
-bool gemv_fused_supported(int weight_fmt, int hidden, const GemvPlan &plan) {
-  if (weight_fmt != MOE_W_BF16 || !plan.dot2) return false;  // bf16 weights with bf16 activations
-  const int lpr = hidden / (kWave * 8);
-  return lpr <= 4 && plan.waves == 8 && plan.depth == 2 && plan.grid >= 2;  // (8 loads per row: out of registers)
+bool gemv_fused_supported(int weight_fmt, int act_fmt, int hidden, const GemvPlan &plan) {
+  if (act_fmt != MOE_A_BF16 || plan.grid < 2 || hidden % 512 != 0) return false;
+  switch (weight_fmt) {
+    case MOE_W_BF16:  // packed bf16 arithmetic, default launch shape, up to 4 loads per row per lane
+      return plan.dot2 && hidden / (kWave * 8) <= 4 && plan.waves == 8 && plan.depth == 2;
+    case MOE_W_INT8_PC:
+    case MOE_W_INT4_G128: return hidden <= 4096;  // 8 wavefronts, at most 8 columns per thread of workgroup 0
+    default: return false;
+  }
 }
 
 hipError_t launch_expert_gemv(const GemvParams &p, int weight_fmt, const GemvPlan &plan, hipStream_t s,

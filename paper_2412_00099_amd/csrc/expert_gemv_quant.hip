@@ -22,6 +22,7 @@
 
 #include "common.h"
 #include "gemv_common.h"
+#include "route_device.h"
 
 namespace moe {
 namespace {
@@ -79,6 +80,34 @@ __device__ __forceinline__ void unpack_x(const XRaw<N> &r, int act_fmt, float *o
   }
 }
 
+// FUSED launches (layer boundary in workgroup 0, see expert_gemv_kernel): N consecutive columns of the residual
+// stream, fetched early, and the activations made of them - h * scale rounded to the activation type - with the
+// same operations as workgroup 0 uses for the copy of x it writes to memory.
+template <int N>
+struct HRaw {
+  float4 v[N / 4];
+};
+template <int N>
+__device__ __forceinline__ void fetch_h(const float *h, int col, HRaw<N> &r) {
+  const float4 *q = reinterpret_cast<const float4 *>(h + col);
+#pragma unroll
+  for (int i = 0; i < N / 4; ++i) r.v[i] = q[i];
+}
+template <int N>
+__device__ __forceinline__ void x_from_h(const HRaw<N> &r, float scale, int act_fmt, float *out) {
+#pragma unroll
+  for (int i = 0; i < N / 4; ++i) {
+    const float t[4] = {r.v[i].x * scale, r.v[i].y * scale, r.v[i].z * scale, r.v[i].w * scale};
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      out[4 * i + k] = act_fmt == MOE_A_BF16 ? __uint_as_float((uint32_t)f32_to_bf16_rne(t[k]) << 16) : t[k];
+  }
+}
+// gate-matrix chunks per row per lane / columns per thread of workgroup 0 for hidden size d (bf16 activations,
+// 8 wavefronts): d = 512 * PER; the gate rows are held in registers (CH = PER) up to d = 2048
+constexpr int boundary_per(int d) { return d / 512; }
+constexpr int boundary_ch(int d) { return d / 512 <= 4 ? d / 512 : 0; }
+
 // =================================================================================================
 // int8
 // =================================================================================================
@@ -92,16 +121,22 @@ struct RecI8 {
 
 // PRE: the per-column scales of W_down are fetched when the wavefront enters an expert, so that the flush at the
 // next change finds them in registers (costs 2*LPR 16-byte registers per lane)
-template <int LPR, int NW, int DEPTH, bool PRE>
+template <int LPR, int NW, int DEPTH, bool PRE, bool FUSED>
 __global__ __launch_bounds__(NW *kWave) void expert_gemv_int8_kernel(GemvParams p) {
   constexpr int VEC = 16, CPL = LPR * VEC;
-  __shared__ float red[kRedFloats];
+  __shared__ __attribute__((aligned(16))) float red[kRedFloats];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int d = p.hidden;
+  if constexpr (FUSED) {
+    if (blockIdx.x == 0) {
+      rt::boundary_workgroup<NW, boundary_ch(CPL * kWave), boundary_per(CPL * kWave)>(p, red);
+      return;
+    }
+  }
   const int64_t row16 = d / VEC;
   const int64_t rec_bytes = 3 * row16 * 16;
-  RecordWalker<NW> walk;
+  RecordWalker<NW, FUSED> walk;
   walk.init(p, wave);
 
   auto issue = [&](RecI8<LPR> &R) {
@@ -124,9 +159,18 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int8_kernel(GemvParams 
 
   // the activations' few loads go out ahead of the weights (loads complete in order, and the first routed record
   // has to wait for the routing record); they are converted after the ring has been filled
-  XRaw<VEC> xraw[LPR];
+  XRaw<VEC> xraw[FUSED ? 1 : LPR];
+  HRaw<VEC> hraw[FUSED ? LPR : 1];
+  OrderedSum<FUSED ? CPL : 1> blocks;  // FUSED: d / 64 = CPL sums of squares of the residual stream
+  if constexpr (FUSED) {
+    blocks.fetch(p.b.glue.ss, lane);
 #pragma unroll
-  for (int c = 0; c < LPR; ++c) fetch_x<VEC>(p.x, p.act_fmt, (c * kWave + lane) * VEC, xraw[c]);
+    for (int c = 0; c < LPR; ++c) fetch_h<VEC>(p.b.glue.h, (c * kWave + lane) * VEC, hraw[c]);
+    __builtin_amdgcn_sched_barrier(0);
+  } else {
+#pragma unroll
+    for (int c = 0; c < LPR; ++c) fetch_x<VEC>(p.x, p.act_fmt, (c * kWave + lane) * VEC, xraw[c]);
+  }
 
   RecI8<LPR> ring[DEPTH];
   bool live[DEPTH];
@@ -139,10 +183,13 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int8_kernel(GemvParams 
   // activations as packed fp16 pairs in column order, and their sum over this lane's columns
   uint32_t xh[CPL / 2];
   float xsum = 0.f;
+  float x_scale = 0.f;
+  if constexpr (FUSED) x_scale = 1.0f / sqrtf(blocks.total() / (float)d + 1e-6f);
 #pragma unroll
   for (int c = 0; c < LPR; ++c) {
     float xf[VEC];
-    unpack_x<VEC>(xraw[c], p.act_fmt, xf);
+    if constexpr (FUSED) x_from_h<VEC>(hraw[c], x_scale, p.act_fmt, xf);
+    else unpack_x<VEC>(xraw[c], p.act_fmt, xf);
 #pragma unroll
     for (int v = 0; v < VEC; v += 2) {
       const uint32_t pr = pack_f16(xf[v], xf[v + 1]);
@@ -261,16 +308,22 @@ struct RecI4 {
   int rows, grp;
 };
 
-template <int LPR, int NW, int DEPTH, bool PRE>
+template <int LPR, int NW, int DEPTH, bool PRE, bool FUSED>
 __global__ __launch_bounds__(NW *kWave) void expert_gemv_int4_kernel(GemvParams p) {
   constexpr int VEC = 32, CPL = LPR * VEC;
-  __shared__ float red[kRedFloats];
+  __shared__ __attribute__((aligned(16))) float red[kRedFloats];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int d = p.hidden;
+  if constexpr (FUSED) {
+    if (blockIdx.x == 0) {
+      rt::boundary_workgroup<NW, boundary_ch(CPL * kWave), boundary_per(CPL * kWave)>(p, red);
+      return;
+    }
+  }
   const int64_t row16 = d / VEC;                             // 16-byte chunks per row of nibbles
   const int64_t rec_bytes = 3 * row16 * 16 + (d / 128) * 4;  // three rows + (gate, up) scale pairs
-  RecordWalker<NW> walk;
+  RecordWalker<NW, FUSED> walk;
   walk.init(p, wave);
 
   auto issue = [&](RecI4<LPR> &R) {
@@ -293,9 +346,18 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int4_kernel(GemvParams 
     for (int c = 0; c < LPR; ++c) R.sc[c] = sc[(c * kWave + lane) >> 2];  // 4 lanes (128 columns) per group
   };
 
-  XRaw<VEC> xraw[LPR];  // fetched ahead of the weights, converted after the ring has been filled (see int8)
+  XRaw<VEC> xraw[FUSED ? 1 : LPR];  // fetched ahead of the weights, converted after the ring has been filled
+  HRaw<VEC> hraw[FUSED ? LPR : 1];
+  OrderedSum<FUSED ? CPL : 1> blocks;
+  if constexpr (FUSED) {
+    blocks.fetch(p.b.glue.ss, lane);
 #pragma unroll
-  for (int c = 0; c < LPR; ++c) fetch_x<VEC>(p.x, p.act_fmt, (c * kWave + lane) * VEC, xraw[c]);
+    for (int c = 0; c < LPR; ++c) fetch_h<VEC>(p.b.glue.h, (c * kWave + lane) * VEC, hraw[c]);
+    __builtin_amdgcn_sched_barrier(0);
+  } else {
+#pragma unroll
+    for (int c = 0; c < LPR; ++c) fetch_x<VEC>(p.x, p.act_fmt, (c * kWave + lane) * VEC, xraw[c]);
+  }
 
   RecI4<LPR> ring[DEPTH];
   bool live[DEPTH];
@@ -308,10 +370,13 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int4_kernel(GemvParams 
   // activations as packed bf16 pairs (column t, column t+4) per dword of 8 nibbles, and per-chunk sums
   uint32_t xp[CPL / 2];
   float xoff[LPR];
+  float x_scale = 0.f;
+  if constexpr (FUSED) x_scale = 1.0f / sqrtf(blocks.total() / (float)d + 1e-6f);
 #pragma unroll
   for (int c = 0; c < LPR; ++c) {
     float xf[VEC];
-    unpack_x<VEC>(xraw[c], p.act_fmt, xf);
+    if constexpr (FUSED) x_from_h<VEC>(hraw[c], x_scale, p.act_fmt, xf);
+    else unpack_x<VEC>(xraw[c], p.act_fmt, xf);
     float s = 0.f;
 #pragma unroll
     for (int w = 0; w < 4; ++w)
@@ -435,22 +500,29 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int4_kernel(GemvParams 
 hipError_t launch_expert_gemv_quant(const GemvParams &p, int weight_fmt, const GemvPlan &plan, hipStream_t s,
                                     hipEvent_t e0, hipEvent_t e1) {
   const dim3 g(plan.grid), b(8 * kWave);
+#define MOE_Q(KERNEL, ...)                                                                      \
+  do {                                                                                          \
+    if (p.fused) hipExtLaunchKernelGGL((KERNEL<__VA_ARGS__, true>), g, b, 0, s, e0, e1, 0, p);  \
+    else hipExtLaunchKernelGGL((KERNEL<__VA_ARGS__, false>), g, b, 0, s, e0, e1, 0, p);         \
+  } while (0)
+  if (p.fused && (plan.grid < 2 || p.act_fmt != MOE_A_BF16)) return hipErrorInvalidValue;
   if (weight_fmt == MOE_W_INT8_PC) {
     switch (p.hidden / (kWave * 16)) {
-      case 1: hipExtLaunchKernelGGL((expert_gemv_int8_kernel<1, 8, 2, true>), g, b, 0, s, e0, e1, 0, p); break;
-      case 2: hipExtLaunchKernelGGL((expert_gemv_int8_kernel<2, 8, 2, false>), g, b, 0, s, e0, e1, 0, p); break;
-      case 4: hipExtLaunchKernelGGL((expert_gemv_int8_kernel<4, 8, 1, false>), g, b, 0, s, e0, e1, 0, p); break;
+      case 1: MOE_Q(expert_gemv_int8_kernel, 1, 8, 2, true); break;
+      case 2: MOE_Q(expert_gemv_int8_kernel, 2, 8, 2, false); break;
+      case 4: MOE_Q(expert_gemv_int8_kernel, 4, 8, 1, false); break;
       default: return hipErrorInvalidValue;
     }
   } else if (weight_fmt == MOE_W_INT4_G128) {
     switch (p.hidden / (kWave * 32)) {
-      case 1: hipExtLaunchKernelGGL((expert_gemv_int4_kernel<1, 8, 4, true>), g, b, 0, s, e0, e1, 0, p); break;
-      case 2: hipExtLaunchKernelGGL((expert_gemv_int4_kernel<2, 8, 2, false>), g, b, 0, s, e0, e1, 0, p); break;
+      case 1: MOE_Q(expert_gemv_int4_kernel, 1, 8, 4, true); break;
+      case 2: MOE_Q(expert_gemv_int4_kernel, 2, 8, 2, false); break;
       default: return hipErrorInvalidValue;
     }
   } else {
     return hipErrorInvalidValue;
   }
+#undef MOE_Q
   return hipGetLastError();
 }
 

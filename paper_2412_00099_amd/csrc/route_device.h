@@ -455,8 +455,11 @@ __device__ __forceinline__ void load_f32(const float *p, float *out) {
     const float2 v = *reinterpret_cast<const float2 *>(p);
     out[0] = v.x; out[1] = v.y;
   } else {
-    const float4 v = *reinterpret_cast<const float4 *>(p);
-    out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+#pragma unroll
+    for (int i = 0; i < PER / 4; ++i) {
+      const float4 v = reinterpret_cast<const float4 *>(p)[i];
+      out[4 * i] = v.x; out[4 * i + 1] = v.y; out[4 * i + 2] = v.z; out[4 * i + 3] = v.w;
+    }
   }
 }
 template <int PER>
@@ -467,15 +470,23 @@ __device__ __forceinline__ void load_bf16(const uint16_t *p, float *out) {
     const uint32_t v = *reinterpret_cast<const uint32_t *>(p);
     out[0] = bf16_lo(v); out[1] = bf16_hi(v);
   } else {
-    const u32x2 v = *reinterpret_cast<const u32x2 *>(p);
-    out[0] = bf16_lo(v.x); out[1] = bf16_hi(v.x); out[2] = bf16_lo(v.y); out[3] = bf16_hi(v.y);
+#pragma unroll
+    for (int i = 0; i < PER / 4; ++i) {
+      const u32x2 v = reinterpret_cast<const u32x2 *>(p)[i];
+      out[4 * i] = bf16_lo(v.x); out[4 * i + 1] = bf16_hi(v.x); out[4 * i + 2] = bf16_lo(v.y);
+      out[4 * i + 3] = bf16_hi(v.y);
+    }
   }
 }
 template <int PER>
 __device__ __forceinline__ void store_f32(float *p, const float *v) {
   if constexpr (PER == 1) p[0] = v[0];
   else if constexpr (PER == 2) *reinterpret_cast<float2 *>(p) = make_float2(v[0], v[1]);
-  else *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+  else {
+#pragma unroll
+    for (int i = 0; i < PER / 4; ++i)
+      reinterpret_cast<float4 *>(p)[i] = make_float4(v[4 * i], v[4 * i + 1], v[4 * i + 2], v[4 * i + 3]);
+  }
 }
 template <int PER>
 __device__ __forceinline__ void store_bf16(uint16_t *p, const float *v) {
@@ -484,10 +495,13 @@ __device__ __forceinline__ void store_bf16(uint16_t *p, const float *v) {
   } else if constexpr (PER == 2) {
     *reinterpret_cast<uint32_t *>(p) = (uint32_t)f32_to_bf16_rne(v[0]) | ((uint32_t)f32_to_bf16_rne(v[1]) << 16);
   } else {
-    u32x2 o;
-    o.x = (uint32_t)f32_to_bf16_rne(v[0]) | ((uint32_t)f32_to_bf16_rne(v[1]) << 16);
-    o.y = (uint32_t)f32_to_bf16_rne(v[2]) | ((uint32_t)f32_to_bf16_rne(v[3]) << 16);
-    *reinterpret_cast<u32x2 *>(p) = o;
+#pragma unroll
+    for (int i = 0; i < PER / 4; ++i) {
+      u32x2 o;
+      o.x = (uint32_t)f32_to_bf16_rne(v[4 * i]) | ((uint32_t)f32_to_bf16_rne(v[4 * i + 1]) << 16);
+      o.y = (uint32_t)f32_to_bf16_rne(v[4 * i + 2]) | ((uint32_t)f32_to_bf16_rne(v[4 * i + 3]) << 16);
+      reinterpret_cast<u32x2 *>(p)[i] = o;
+    }
   }
 }
 
@@ -676,6 +690,31 @@ __device__ __forceinline__ void fused_boundary(const RouteParams &p, const Fused
   __syncthreads();
   if (wave != 0) return;
   route_wave(p, z_s, cr, st, out_dev, note, lds.rec_s, lane, flags);
+}
+
+// Workgroup 0 of an expert launch that carries the layer boundary (NW wavefronts; d = NW*64*PER with bf16
+// activations): forms x, routes, hands the record on, writes its (empty) partial row, then touches what the next
+// layer's boundary will read first.  `red` is the launch's reduction buffer in LDS, borrowed.
+template <int NW, int CH, int PER>
+__device__ __forceinline__ void boundary_workgroup(const GemvParams &p, float *red) {
+  const int tid = threadIdx.x, d = p.hidden;
+  fused_boundary<NW, CH, PER, true>(p.b.route, p.b.glue, p.b.gate_w, p.b.state, p.b.out_dev, p.b.note,
+                                    BoundaryFlags{p.b.tags, (int)gridDim.x},
+                                    carve_boundary_lds(reinterpret_cast<uint32_t *>(red)));
+  float *row = p.partial + (int64_t)p.row_offset * d;  // this workgroup's partial row: nothing to add
+  for (int j = tid; j < d; j += NW * kWave) row[j] = 0.f;
+  if (p.b.next_gate_w != nullptr) {
+    // this compute unit is idle for the rest of the launch: pull what the next boundary reads first towards it
+    const u32x4 *g = static_cast<const u32x4 *>(p.b.next_gate_w);
+    uint32_t acc = 0;
+    for (int64_t i = tid; i < p.b.gate_bytes / 16; i += NW * kWave) {
+      const u32x4 v = g[i];
+      acc ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
+    for (int i = tid; i < (int)(sizeof(LayerState) / 4); i += NW * kWave)
+      acc ^= reinterpret_cast<const uint32_t *>(p.b.next_state)[i];
+    if (acc == 0x9e3779b9u && p.b.gate_bytes < 0) row[0] = 1.f;  // never true: keeps the loads
+  }
 }
 
 }  // namespace rt

@@ -153,6 +153,9 @@ class MoEDecoder:
     def restore(self, layer, blob: bytes):
         B.moe_cache_restore(self.ctx, layer, blob)
 
+    def plan(self):
+        return B.moe_cache_plan(self.ctx)
+
     def set_lambda(self, lam):
         B.moe_cache_set_lambda(self.ctx, lam)
 

@@ -104,3 +104,74 @@ def test_fused_boundary_single_step(name, hidden):
     sel_gpu = list(r1.sel_expert[:K])
     assert sorted(sel_gpu) == sorted(routing.ranking(z_gpu)[:K].tolist())  # empty cache: plain top-K of its own logits
     dec.close()
+
+
+@pytest.mark.parametrize("name,hidden,inter", [("c2_qwen_bf16", 2048, 96), ("c2_qwen_bf16", 1024, 64),
+                                               ("c2_qwen_bf16", 512, 64), ("c4_dsv2lite_int4", 2048, 128),
+                                               ("c4_dsv2lite_int4", 4096, 128), ("c5_mixtral_int8", 4096, 96),
+                                               ("c5_mixtral_int8", 1024, 64)])
+def test_boundary_inside_the_expert_launch(name, hidden, inter, monkeypatch):
+    """bf16 activations: with no host waiting for the decision, the boundary runs in workgroup 0 of the layer's
+    expert launch (reduce_glue_kernel + one expert launch per layer).  Every layer-token of a coupled stack is
+    checked against the oracle fed with the device's own inputs of that step (its h before the step, the y it
+    was handed, its x): h, x, logits, the routing decision incl. slots and misses (tie protocol), and y one step
+    later.  Small caches force misses, so the second expert launch of a layer is exercised too."""
+    base = CONFIGS[name]
+    cfg = base.with_(n_layers=3, hidden=hidden, n_experts=12, inter=inter,
+                     shared_inter=2 * inter if base.shared_inter else 0, capacity=5, top_k=min(base.top_k, 4),
+                     seed=4200 + hidden + inter)
+    L, K, N, d, T, lam = cfg.n_layers, cfg.top_k, cfg.n_experts, cfg.hidden, 16, 0.5
+    monkeypatch.setenv("MOE_FUSE_BOUNDARY", "1")  # also without a shared expert (read when the context is created)
+    store, dec = build(cfg, lam=lam)
+    ow = OracleWeights(cfg)
+    routers = [routing.CachePriorRouter(N, K, cfg.capacity, lam, 0, cfg.renormalize) for _ in range(L)]
+    a = workloads.ar1_stream(cfg, T)
+    a_dev = a.to(DEV)
+    h = torch.zeros(d, device=DEV)
+    x = torch.zeros(d, dtype=cfg.act_dtype, device=DEV)
+    y = torch.zeros(d, dtype=cfg.act_dtype, device=DEV)
+    torch.cuda.synchronize()
+    assert dec.plan().boundary_in_expert_launch == 1
+    ties = misses = 0
+    y_ref_prev = None  # oracle output of the previous layer-token, from the device's x of that step
+    for t in range(T):
+        for l in range(L):
+            print(f"case in-launch boundary {name} d={hidden} token {t} layer {l}", flush=True)
+            h_before = h.cpu().numpy().astype(np.float64)
+            perturb = 1.0 if l == 0 else stack.PERTURB
+            assert dec.stack_route_step(l, h, a_dev[t, l], perturb, x, carry=l > 0, y=y, wait=False) is None
+            dec.expert_forward(l, x, None)
+            raw = dec.last_route(l)
+            dec.compute_stream.synchronize()
+            out = route_fields(raw, K)
+            ctx = (t, l)
+            # y handed out by this boundary = output of the previous layer-token
+            if y_ref_prev is not None:
+                assert oexp.rel_err(y.float().cpu().numpy(), y_ref_prev) <= 1e-2, ctx
+            y_dev = y.float().cpu().numpy().astype(np.float64)
+            a_np = a[t, l].double().numpy()
+            h_ref = perturb * a_np if l == 0 else stack.next_hidden(h_before, y_dev, a[t, l].numpy())
+            assert oexp.rel_err(h.cpu().numpy(), h_ref) <= 1e-5, ctx
+            x_ref = stack.rmsnorm(h.cpu().numpy().astype(np.float64))
+            x_np = x.float().cpu().numpy()
+            assert oexp.rel_err(x_np, x_ref) <= 2.0 ** -7, ctx
+            z = routing.router_logits(ow.gate(l), x_np)
+            z_gpu = np.array(raw.logits[:N], np.float32)
+            assert np.abs(z_gpu - z).max() <= 1e-4 * max(np.abs(z).max(), 1e-3), ctx
+            sel, zp, delta = routers[l].select(z)
+            if out["sel"] != sel.tolist():
+                kth = np.sort(zp)[::-1][K - 1]
+                forced = {int(e) for e in np.nonzero(zp > kth + 1e-5)[0]}
+                assert np.all(zp[out["sel"]] >= kth - 1e-5) and forced <= set(out["sel"]), (ctx, out["sel"], sel.tolist())
+                ties += 1
+                sel = np.array(out["sel"])
+            ref = routers[l].commit(z, sel, zp, delta)
+            assert out["slot"] == ref.slot and out["miss"] == ref.miss and out["evicted"] == ref.evicted, ctx
+            misses += sum(ref.miss)
+            y_ref_prev = oexp.moe_output(x_np, [ow.expert(l, int(e)) for e in ref.sel], ref.weight, ow.shared(l))
+    assert misses > K * L  # more than the cold misses of the first token
+    for l in range(L):
+        s, o = dec.stats(l), routers[l].stats
+        assert (s.tokens, s.hits, s.misses, s.evictions) == (o.tokens, o.hits, o.misses, o.evictions)
+    print(f"in-launch boundary {name} d={hidden}: ties={ties} misses={misses}", flush=True)
+    dec.close()
