@@ -27,15 +27,15 @@ HBM_PEAK_GBS = 8000.0
 HEADLINE_LAMBDA = 0.5
 PERTURB = 0.5
 
-# HBM traffic of one whole-layer launch of the expert GEMV on the default workload, from two rocprofv3 --pmc runs
+# HBM traffic of one whole-layer launch of the expert kernel (layer boundary in its first workgroup) on the default workload, from two rocprofv3 --pmc runs
 # (FETCH_SIZE, WRITE_SIZE in KiB per dispatch), each scaled by what the same counter reads for an elementwise kernel
 # of known size in the same run (summary and commands: profiles/hbm_counters_expert_gemv_c2_qwen_bf16.txt).  Valid
 # only for the kernel sources it was taken with: reported as null once their hash differs.
 GEMV_TRAFFIC = {
     "workload": "c2_qwen_bf16",
-    "sources_sha256": "29be46d43382e309c19538a788e1443623221a98eb1ca73613a2e0685cbddb35",
-    "fetch_kib": 67717.1, "fetch_scale": 2.0,
-    "write_kib": 2048.0, "write_scale": 1.0,
+    "sources_sha256": "5abf37205582fb1f82ccbb519aa44ac4730f8387ecb8470519e12b121253b60c",
+    "fetch_kib": 68077.7, "fetch_scale": 2.0,
+    "write_kib": 2061.7, "write_scale": 1.0,
 }
 GEMV_SOURCES = ("expert_gemv.hip", "gemv_common.h", "route_device.h", "common.h")
 
