@@ -155,7 +155,11 @@ int moe_expert_forward(moe_cache_t *ctx, int32_t layer, const void *x_dev, void 
  *   then the routing step of `layer` on x, exactly as moe_route_step(ctx, layer, x_dev, NULL, out_host).
  * h_dev: device fp32 [d] in/out; a_dev: device fp32 [d] or NULL; x_dev: device act_fmt [d] (pass it to the
  * layer's moe_expert_forward); y_dev: device act_fmt [d] or NULL, receives the finished pending output.
- * hidden must be at most 8192.  Same blocking rule and errors as moe_route_step. */
+ * hidden must be at most 8192.  Same blocking rule and errors as moe_route_step.
+ * With out_host NULL the library may defer x and the routing into the layer's expert launch (its first workgroup
+ * does them while the others already stream the shared expert; see moe_cache_plan): x_dev and the routing record
+ * are then written by the kernels moe_expert_forward enqueues, not by this call's, so nothing but
+ * moe_expert_forward(ctx, layer, x_dev, ...) may use x_dev in between, and that call must be given the same x_dev. */
 int moe_stack_route_step(moe_cache_t *ctx, int32_t layer, float *h_dev, const float *a_dev, float perturb,
                          int32_t carry, void *x_dev, void *y_dev, moe_route_out_t *out_host);
 
