@@ -340,11 +340,16 @@ __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    if (lane < 3) {
-      const int chunk = lane < 2 ? W_WEIGHT / 4 + lane : W_SEQ / 4;
-      reinterpret_cast<u32x4 *>(out_dev)[chunk] = reinterpret_cast<const u32x4 *>(rec_s)[chunk];
+    if (lane < 6) {
+      // write-through (agent-scope atomic) stores, 8 bytes per lane, then a wait for their completion: cheaper
+      // than a release fence, which also has the L2 searched for lines to write back
+      const int chunk = lane < 4 ? W_WEIGHT / 4 + (lane >> 1) : W_SEQ / 4;
+      const int half = lane & 1;
+      const uint64_t v = reinterpret_cast<const uint64_t *>(rec_s)[2 * chunk + half];
+      __hip_atomic_store(reinterpret_cast<uint64_t *>(out_dev) + 2 * chunk + half, v, __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
     }
-    __threadfence();
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     for (int b = lane; b < flags.n; b += kWave)
       __hip_atomic_store(flags.words + kTagStride * b, p.seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
