@@ -3,13 +3,16 @@
 Workload (config.workload): the Qwen1.5-MoE-A2.7B-shaped stack, bf16, attention omitted - 24 layers,
 hidden 2048, 60 routed experts of intermediate 1408 (top-4) plus a shared SwiGLU of intermediate 5632,
 30 of 60 experts cached per layer, random N(0, 0.02) weights, AR(1) (rho = 0.9) hidden-state streams with
-a residual add between layers.  A step is one decode token through all layers: per layer one fused launch
-(previous expert output, stack glue, router) , the miss fills and the expert GEMV.  All weights and inputs are resident (device
-slots / pinned host tier) before the timed region.
+a residual add between layers.  A step is one decode token through all layers: per layer one launch that sums the
+previous layer's expert output and does the residual glue, and one expert launch whose first workgroup forms x and
+routes while the others stream the shared expert and then the selected experts; a miss adds a fill over the host
+link and a second expert launch.  All weights and inputs are resident (device slots / pinned host tier) before the
+timed region.
 
-Prints ONE JSON line.  `value` is tokens/s at the headline strength lambda = 0.5; `roofline` is the expert
-GEMV kernel (HIP events on the compute stream around every launch, in a second pass over the same tokens);
-`cpu_baseline` is the CPU oracle on the first tokens of the same workload.
+Prints ONE JSON line.  `value` is tokens/s at the headline strength lambda = 0.5; `roofline` is that expert kernel
+(HIP events on the compute stream around every launch, in a second pass over the same tokens);
+`boundary_as_separate_launch` times the same expert kernel as a launch of its own, with the routing in a launch
+before it; `cpu_baseline` is the CPU oracle on the first tokens of the same workload.
 """
 from __future__ import annotations
 
@@ -185,8 +188,8 @@ def main():
                     help="skip the plain 256 MiB device copy that calibrates HBM byte counters under rocprofv3 --pmc")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; the path has no multi-GPU part (see DESIGN.md). "
-              "Run with --gpus 1.", file=sys.stderr)
+        print("bench.py: the batch-1 decode path runs on ONE GPU and has no multi-GPU part; run with --gpus 1.",
+              file=sys.stderr)
         sys.exit(2)
 
     import torch
