@@ -8,7 +8,7 @@ import os
 LIB_PATH = os.environ.get("MOE_CACHE_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmoe_cache.so")
 if not os.path.exists(LIB_PATH):
     raise ImportError(
-        f"{LIB_PATH} is missing: build it with `python -m paper_2412_00099_amd.build` "
+        f"{LIB_PATH} is missing: build it with `python paper_2412_00099_amd/build.py` "
         "(hipcc, gfx950). There is no fallback path."
     )
 lib = C.CDLL(LIB_PATH)
