@@ -345,6 +345,10 @@ __global__ __launch_bounds__(256) void reduce_glue_kernel(const float *partial, 
   __shared__ float sq_s[16];
   const int tid = threadIdx.x, cl = tid & 15, rg = tid >> 4;
   const int col = blockIdx.x * 64 + cl * 4;
+  // the glue operands are fetched by every thread at the very start (absent ones read from h and ignored), so
+  // that they are there when the sum is: only the threads of the first row group use them
+  const float4 hv = *reinterpret_cast<const float4 *>(h + col);
+  const float4 av = *reinterpret_cast<const float4 *>((a != nullptr ? a : h) + col);
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   const int chunk = (n_partial + 15) / 16;
   const int b0 = rg * chunk, b1 = min(n_partial, b0 + chunk);
@@ -356,6 +360,8 @@ __global__ __launch_bounds__(256) void reduce_glue_kernel(const float *partial, 
     acc.z += t.z;
     acc.w += t.w;
   }
+  // (keeps the two early loads where they are: without a use here they are moved into the branch below)
+  asm volatile("" ::"v"(hv.x), "v"(hv.y), "v"(hv.z), "v"(hv.w), "v"(av.x), "v"(av.y), "v"(av.z), "v"(av.w));
   acc_s[rg][cl] = acc;
   __syncthreads();
   if (rg == 0) {
@@ -386,9 +392,8 @@ __global__ __launch_bounds__(256) void reduce_glue_kernel(const float *partial, 
       *reinterpret_cast<float4 *>(static_cast<float *>(y) + col) = s;
     }
     const bool with_y = carry && n_partial > 0;
-    const float4 hv = carry ? *reinterpret_cast<const float4 *>(h + col) : make_float4(0.f, 0.f, 0.f, 0.f);
-    const float4 av = a != nullptr ? *reinterpret_cast<const float4 *>(a + col) : make_float4(0.f, 0.f, 0.f, 0.f);
     float v[4] = {hv.x, hv.y, hv.z, hv.w};
+    if (!carry) v[0] = v[1] = v[2] = v[3] = 0.f;
     const float aa[4] = {av.x, av.y, av.z, av.w};
     float sq = 0.f;
 #pragma unroll
