@@ -208,6 +208,7 @@ def test_snapshot_restore_resumes_bit_exactly():
             for l in range(cfg.n_layers):
                 out = route_fields(dec.route_step(l, logits=zs[l][t]), K)
                 dec.expert_forward(l, xs[t], y)
+                dec.compute_stream.synchronize()  # y.clone() runs on torch's stream, the library on its own
                 rec.append((out["sel"], out["slot"], out["miss"], out["evicted"], float(out["delta"]), y.clone()))
         return rec
 
