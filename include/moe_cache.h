@@ -220,9 +220,12 @@ typedef struct moe_cache_plan {
 } moe_cache_plan_t;
 int moe_cache_plan(moe_cache_t *ctx, moe_cache_plan_t *out_host);
 
-/* Average duration in microseconds of the expert-GEMV launches that covered a whole layer (no expert missing)
- * since the last call with reset != 0, and their count; measured with start/stop events attached to the
- * launches on compute_stream while profiling is enabled. */
+/* Average duration in microseconds of the timed expert-GEMV launches that covered a whole layer (no expert missing)
+ * since the last call with reset != 0, and their count; measured with start/stop events attached to the launches
+ * on compute_stream.  enable = 0 switches the timing off, enable = n > 0 times every n-th first-pass launch from
+ * this call on (1 = all of them; events on every launch slow the host down to where the device idles between
+ * launches, a stride co-prime to the layer count samples every layer without that); at most 32768 launches are
+ * timed between two resets, later ones run untimed. */
 int moe_cache_profile(moe_cache_t *ctx, int32_t enable, int32_t reset, double *avg_us, int64_t *launches);
 
 const char *moe_last_error(void);

@@ -282,7 +282,7 @@ def moe_residual_rmsnorm(h_dev, y_dev, a_dev, perturb: float, carry: int, x_dev,
            "moe_residual_rmsnorm")
 
 
-def moe_cache_profile(ctx, enable: bool, reset: bool = True):
+def moe_cache_profile(ctx, enable: int, reset: bool = True):
     avg, n = C.c_double(), C.c_int64()
     _check(lib.moe_cache_profile(ctx, int(enable), int(reset), C.byref(avg), C.byref(n)), "moe_cache_profile")
     return avg.value, n.value

@@ -83,7 +83,8 @@ struct moe_cache {
   bool poll = false;
 
   // optional timing of the expert GEMV launches
-  bool profiling = false;
+  int profiling = 0;      // 0 = off, n = events on every n-th expert launch of a layer's first pass
+  uint64_t prof_tick = 0;
   std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_events;
   std::vector<uint8_t> prof_full;  // launch covered the whole layer (no expert was missing)
   size_t prof_used = 0;
@@ -479,15 +480,8 @@ int moe_expert_forward(moe_cache_t *c, int32_t layer, const void *x_dev, void *y
     p.fused = 1;
     p.b = c->boundary[layer];
   }
-  const bool prof = c->profiling && c->prof_used < (1u << 16);
+  const bool prof = c->profiling && c->prof_tick++ % (uint64_t)c->profiling == 0 && c->prof_used < c->prof_events.size();
   if (prof) {
-    if (c->prof_used == c->prof_events.size()) {
-      hipEvent_t a, b;
-      HIP_TRY(hipEventCreate(&a));
-      HIP_TRY(hipEventCreate(&b));
-      c->prof_events.emplace_back(a, b);
-      c->prof_full.push_back(0);
-    }
     HIP_TRY(launch_expert_gemv(p, g.weight_fmt, c->plan, c->compute, c->prof_events[c->prof_used].first,
                                c->prof_events[c->prof_used].second));
   } else {
@@ -666,6 +660,10 @@ int moe_cache_plan(moe_cache_t *c, moe_cache_plan_t *out) {
   return MOE_OK;
 }
 
+namespace {
+constexpr size_t kProfEvents = 1u << 15;  // launches timed between two resets
+}
+
 int moe_cache_profile(moe_cache_t *c, int32_t enable, int32_t reset, double *avg_us, int64_t *launches) {
   if (!c) return fail(MOE_EINVAL, "context is NULL");
   HIP_TRY(hipStreamSynchronize(c->compute));
@@ -681,7 +679,16 @@ int moe_cache_profile(moe_cache_t *c, int32_t enable, int32_t reset, double *avg
   if (avg_us) *avg_us = n_full ? total_ms * 1000.0 / (double)n_full : 0.0;
   if (launches) *launches = n_full;
   if (reset) c->prof_used = 0;
-  c->profiling = enable != 0;
+  c->profiling = enable > 0 ? enable : 0;
+  c->prof_tick = 0;
+  // the events are made here, not between the launches they time
+  while (c->profiling && c->prof_events.size() < kProfEvents) {
+    hipEvent_t a, b;
+    HIP_TRY(hipEventCreate(&a));
+    HIP_TRY(hipEventCreate(&b));
+    c->prof_events.emplace_back(a, b);
+    c->prof_full.push_back(0);
+  }
   return MOE_OK;
 }
 
