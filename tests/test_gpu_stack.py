@@ -106,22 +106,15 @@ def test_fused_boundary_single_step(name, hidden):
     dec.close()
 
 
-@pytest.mark.parametrize("name,hidden,inter", [("c2_qwen_bf16", 2048, 96), ("c2_qwen_bf16", 1024, 64),
-                                               ("c2_qwen_bf16", 512, 64), ("c4_dsv2lite_int4", 2048, 128),
-                                               ("c4_dsv2lite_int4", 4096, 128), ("c5_mixtral_int8", 4096, 96),
-                                               ("c5_mixtral_int8", 1024, 64)])
-def test_boundary_inside_the_expert_launch(name, hidden, inter, monkeypatch):
-    """bf16 activations: with no host waiting for the decision, the boundary runs in workgroup 0 of the layer's
-    expert launch (reduce_glue_kernel + one expert launch per layer).  Every layer-token of a coupled stack is
-    checked against the oracle fed with the device's own inputs of that step (its h before the step, the y it
-    was handed, its x): h, x, logits, the routing decision incl. slots and misses (tie protocol), and y one step
-    later.  Small caches force misses, so the second expert launch of a layer is exercised too."""
-    base = CONFIGS[name]
-    cfg = base.with_(n_layers=3, hidden=hidden, n_experts=12, inter=inter,
-                     shared_inter=2 * inter if base.shared_inter else 0, capacity=5, top_k=min(base.top_k, 4),
-                     seed=4200 + hidden + inter)
-    L, K, N, d, T, lam = cfg.n_layers, cfg.top_k, cfg.n_experts, cfg.hidden, 16, 0.5
-    monkeypatch.setenv("MOE_FUSE_BOUNDARY", "1")  # also without a shared expert (read when the context is created)
+def run_in_launch_boundary(cfg, T, lam, outputs_every=1, force=True, monkeypatch=None):
+    """A coupled stack driven as bench.py drives it - no host waiting for the decision, so that the boundary runs
+    in workgroup 0 of the layer's expert launch (reduce_glue_kernel + one expert launch per layer).  Every
+    layer-token is checked against the oracle fed with the device's own inputs of that step (its h before the
+    step, the y it was handed, its x): h, x, logits, the routing decision incl. slots and misses (tie protocol),
+    and, for every outputs_every-th step, y one step later.  Returns (ties, misses)."""
+    L, K, N, d = cfg.n_layers, cfg.top_k, cfg.n_experts, cfg.hidden
+    if force:
+        monkeypatch.setenv("MOE_FUSE_BOUNDARY", "1")  # also without a shared expert (read when the context is created)
     store, dec = build(cfg, lam=lam)
     ow = OracleWeights(cfg)
     routers = [routing.CachePriorRouter(N, K, cfg.capacity, lam, 0, cfg.renormalize) for _ in range(L)]
@@ -132,11 +125,11 @@ def test_boundary_inside_the_expert_launch(name, hidden, inter, monkeypatch):
     y = torch.zeros(d, dtype=cfg.act_dtype, device=DEV)
     torch.cuda.synchronize()
     assert dec.plan().boundary_in_expert_launch == 1
-    ties = misses = 0
+    ties = misses = step = 0
     y_ref_prev = None  # oracle output of the previous layer-token, from the device's x of that step
     for t in range(T):
         for l in range(L):
-            print(f"case in-launch boundary {name} d={hidden} token {t} layer {l}", flush=True)
+            print(f"case in-launch boundary {cfg.name} d={d} token {t} layer {l}", flush=True)
             h_before = h.cpu().numpy().astype(np.float64)
             perturb = 1.0 if l == 0 else stack.PERTURB
             assert dec.stack_route_step(l, h, a_dev[t, l], perturb, x, carry=l > 0, y=y, wait=False) is None
@@ -168,10 +161,28 @@ def test_boundary_inside_the_expert_launch(name, hidden, inter, monkeypatch):
             ref = routers[l].commit(z, sel, zp, delta)
             assert out["slot"] == ref.slot and out["miss"] == ref.miss and out["evicted"] == ref.evicted, ctx
             misses += sum(ref.miss)
-            y_ref_prev = oexp.moe_output(x_np, [ow.expert(l, int(e)) for e in ref.sel], ref.weight, ow.shared(l))
-    assert misses > K * L  # more than the cold misses of the first token
+            y_ref_prev = None
+            if step % outputs_every == 0:
+                y_ref_prev = oexp.moe_output(x_np, [ow.expert(l, int(e)) for e in ref.sel], ref.weight, ow.shared(l))
+            step += 1
     for l in range(L):
         s, o = dec.stats(l), routers[l].stats
         assert (s.tokens, s.hits, s.misses, s.evictions) == (o.tokens, o.hits, o.misses, o.evictions)
-    print(f"in-launch boundary {name} d={hidden}: ties={ties} misses={misses}", flush=True)
+    print(f"in-launch boundary {cfg.name} d={d}: ties={ties} misses={misses}", flush=True)
     dec.close()
+    return ties, misses
+
+
+@pytest.mark.parametrize("name,hidden,inter", [("c2_qwen_bf16", 2048, 96), ("c2_qwen_bf16", 1024, 64),
+                                               ("c2_qwen_bf16", 512, 64), ("c4_dsv2lite_int4", 2048, 128),
+                                               ("c4_dsv2lite_int4", 4096, 128), ("c5_mixtral_int8", 4096, 96),
+                                               ("c5_mixtral_int8", 1024, 64)])
+def test_boundary_inside_the_expert_launch(name, hidden, inter, monkeypatch):
+    """Reduced shapes of the three weight formats, every output checked.  Small caches force misses, so the second
+    expert launch of a layer is exercised too."""
+    base = CONFIGS[name]
+    cfg = base.with_(n_layers=3, hidden=hidden, n_experts=12, inter=inter,
+                     shared_inter=2 * inter if base.shared_inter else 0, capacity=5, top_k=min(base.top_k, 4),
+                     seed=4200 + hidden + inter)
+    ties, misses = run_in_launch_boundary(cfg, 16, 0.5, monkeypatch=monkeypatch)
+    assert misses > cfg.top_k * cfg.n_layers  # more than the cold misses of the first token
