@@ -159,7 +159,9 @@ int moe_expert_forward(moe_cache_t *ctx, int32_t layer, const void *x_dev, void 
  * With out_host NULL the library may defer x and the routing into the layer's expert launch (its first workgroup
  * does them while the others already stream the shared expert; see moe_cache_plan): x_dev and the routing record
  * are then written by the kernels moe_expert_forward enqueues, not by this call's, so nothing but
- * moe_expert_forward(ctx, layer, x_dev, ...) may use x_dev in between, and that call must be given the same x_dev. */
+ * moe_expert_forward(ctx, layer, x_dev, ...) may use x_dev in between, and that call must be given the same x_dev.
+ * The other workgroups' wait for the first one is bounded; should it ever run out, they finish without the routed
+ * experts, and every later call that names a layer returns MOE_EHIP until moe_cache_reset. */
 int moe_stack_route_step(moe_cache_t *ctx, int32_t layer, float *h_dev, const float *a_dev, float perturb,
                          int32_t carry, void *x_dev, void *y_dev, moe_route_out_t *out_host);
 
@@ -185,7 +187,8 @@ int moe_cache_restore(moe_cache_t *ctx, int32_t layer, const void *buf_host, siz
 /* Change lambda (and for the baselines M / p) between steps. */
 int moe_cache_set_lambda(moe_cache_t *ctx, float lambda);
 int moe_cache_set_baseline(moe_cache_t *ctx, int32_t route_mode, int32_t max_rank, float cumsum_p);
-/* Empty every layer's cache (then preload the initial residents again), zero Delta_avg and counters. */
+/* Empty every layer's cache (then preload the initial residents again), zero Delta_avg and counters; drops pending
+ * steps and outputs and clears the error state described at moe_stack_route_step.  Synchronises both streams. */
 int moe_cache_reset(moe_cache_t *ctx);
 
 /* Workload glue for multi-layer synthetic stacks (not part of the paper's method):

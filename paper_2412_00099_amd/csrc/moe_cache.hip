@@ -106,6 +106,7 @@ int do_reset(moe_cache_t *c) {
   if (c->n_initial > 0)
     HIP_TRY(hipMemcpy(c->d_initial, c->initial.data(), c->initial.size() * sizeof(int32_t), hipMemcpyHostToDevice));
   HIP_TRY(launch_state_init(c->d_state, c->cfg.n_layers, c->d_initial, c->n_initial, c->compute));
+  if (c->h_gave_up) __atomic_store_n(c->h_gave_up, 0u, __ATOMIC_RELAXED);
   c->pending_rows = 0;
   const int N = c->cfg.n_experts;
   for (int l = 0; l < c->cfg.n_layers; ++l) {
