@@ -59,6 +59,7 @@ struct BoundaryArgs {
   uint32_t *tags;            // device words [grid] 64 bytes apart: "routing record published", one copy per
                              // workgroup (compared with route.seq)
   uint32_t *gave_up;         // mapped host word set when a wavefront stopped waiting for a tag
+  int spin_limit;            // polls of a tag before a wavefront stops waiting (kTagSpins unless a test lowers it)
   // what the boundary of the layer that follows will read first (its gate matrix and cache state): workgroup 0
   // touches it once its own work is done, which measurably shortens that boundary (nullptr: don't)
   const void *next_gate_w;

@@ -62,9 +62,8 @@ __device__ __forceinline__ void wave_sum2(float &a, float &b) {
 // False if it did not appear within about a tenth of a second (the caller then skips its work and reports).
 // No agent-scope acquire follows: it would invalidate the XCD's L2 under thirty-two streaming compute units
 // (measured: the launch ran at half speed).  What the tag announces is read with ld128<true> / ld64<true> instead.
-constexpr int kTagSpins = 1 << 18;
-__device__ __forceinline__ bool wait_tag(const uint32_t *word, uint32_t tag) {
-  for (int i = 0; i < kTagSpins; ++i) {
+__device__ __forceinline__ bool wait_tag(const uint32_t *word, uint32_t tag, int spin_limit) {
+  for (int i = 0; i < spin_limit; ++i) {
     const uint32_t v = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if ((uint32_t)__builtin_amdgcn_readfirstlane((int)v) == tag) {
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // keeps the loads that follow behind the poll
@@ -177,7 +176,7 @@ struct RecordWalker {
     if (seg < 0) {  // first routed entry: unpack the routing record, locate the entry
       bool ok = true;
       if constexpr (FUSED) {
-        ok = wait_tag(p.b.tags + 16 * (int)blockIdx.x, p.b.route.seq);
+        ok = wait_tag(p.b.tags + 16 * (int)blockIdx.x, p.b.route.seq, p.b.spin_limit);
         load_record(p);
       }
       slots = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)rd.y) |

@@ -34,6 +34,16 @@ int fail(int code, const char *fmt, ...) {
     if (e_ != hipSuccess) return fail(MOE_EHIP, "%s: %s", #expr, hipGetErrorString(e_));     \
   } while (0)
 
+// Keeps the compute stream busy for about `ticks` periods of the 100 MHz wall clock (bounded by the iteration
+// count whatever the clock does).  Enqueued ahead of a launch that is timed with events: the start event of such
+// a launch is a marker of its own, enqueued a few microseconds of host time before the kernel, and on an idle
+// stream it would be stamped that much before the kernel starts.  Behind this kernel both are queued by the time
+// the marker is reached.
+__global__ void hold_stream_kernel(uint64_t ticks) {
+  const uint64_t t0 = wall_clock64();
+  for (int i = 0; i < 4096 && wall_clock64() - t0 < ticks; ++i) __builtin_amdgcn_s_sleep(8);
+}
+
 bool valid_wfmt(int f) { return f >= MOE_W_FP32 && f <= MOE_W_INT4_G128; }
 bool valid_afmt(int f) { return f == MOE_A_FP32 || f == MOE_A_BF16; }
 
@@ -68,6 +78,8 @@ struct moe_cache {
   uint32_t *h_gave_up_dev = nullptr;
   bool fuse_boundary = true;        // run deferred boundaries inside the expert launch (see moe_cache_init)
   bool prefetch_gate = true;        // MOE_PREFETCH_GATE=0: workgroup 0 does not touch the next layer's gate matrix
+  int tag_spins = 1 << 18;          // polls (about a tenth of a second) before a workgroup stops waiting for
+                                    // workgroup 0; MOE_TAG_SPINS lowers it so that tests reach the error path
   int32_t *d_initial = nullptr;
   float *d_partial = nullptr;
   int pending_rows = 0;            // partial rows of an expert output not reduced yet (y_dev was NULL)
@@ -259,6 +271,7 @@ int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, 
   c->fuse_boundary = 3 * (int64_t)cfg->shared_inter >= (int64_t)cfg->top_k * cfg->inter + cfg->shared_inter;
   if (const char *s = getenv("MOE_FUSE_BOUNDARY")) c->fuse_boundary = atoi(s) != 0;
   if (const char *s = getenv("MOE_PREFETCH_GATE")) c->prefetch_gate = atoi(s) != 0;
+  if (const char *s = getenv("MOE_TAG_SPINS")) if (atoi(s) > 0) c->tag_spins = atoi(s);
   HIP_INIT(hipMalloc(&c->d_initial, sizeof(int32_t) * (size_t)L * (b->n_initial > 0 ? b->n_initial : 1)));
   HIP_INIT(hipMalloc(&c->d_partial, sizeof(float) * 2 * (size_t)c->plan.grid * cfg->hidden));
   HIP_INIT(hipMalloc(&c->d_y, sizeof(float) * (size_t)cfg->hidden));
@@ -434,6 +447,7 @@ int moe_stack_route_step(moe_cache_t *c, int32_t layer, float *h_dev, const floa
     b.note = c->h_note_dev + layer;
     b.tags = c->d_tags;
     b.gave_up = c->h_gave_up_dev;
+    b.spin_limit = c->tag_spins;
     b.next_gate_w = c->prefetch_gate ? c->gate_w[(layer + 1) % c->cfg.n_layers] : nullptr;
     b.next_state = c->d_state + (layer + 1) % c->cfg.n_layers;
     b.gate_bytes = (int64_t)c->cfg.n_experts * c->cfg.hidden * (c->cfg.act_fmt == MOE_A_BF16 ? 2 : 4);
@@ -483,6 +497,8 @@ int moe_expert_forward(moe_cache_t *c, int32_t layer, const void *x_dev, void *y
   }
   const bool prof = c->profiling && c->prof_tick++ % (uint64_t)c->profiling == 0 && c->prof_used < c->prof_events.size();
   if (prof) {
+    hipLaunchKernelGGL(hold_stream_kernel, dim3(1), dim3(64), 0, c->compute, (uint64_t)1500);  // 15 us
+    HIP_TRY(hipGetLastError());
     HIP_TRY(launch_expert_gemv(p, g.weight_fmt, c->plan, c->compute, c->prof_events[c->prof_used].first,
                                c->prof_events[c->prof_used].second));
   } else {

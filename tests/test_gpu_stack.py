@@ -186,3 +186,31 @@ def test_boundary_inside_the_expert_launch(name, hidden, inter, monkeypatch):
                      seed=4200 + hidden + inter)
     ties, misses = run_in_launch_boundary(cfg, 16, 0.5, monkeypatch=monkeypatch)
     assert misses > cfg.top_k * cfg.n_layers  # more than the cold misses of the first token
+
+
+def test_bounded_wait_error_path_and_reset(monkeypatch):
+    """Failure handling of the boundary inside the expert launch, forced from the host: with a poll limit of one
+    the other workgroups stop waiting before workgroup 0 has routed (no shared expert: the wait comes first).
+    Every kernel still ends, the next call that names a layer reports MOE_EHIP, and a reset clears the state."""
+    import paper_2412_00099_amd as pkg
+
+    cfg = CONFIGS["c2_qwen_bf16"].with_(n_layers=1, hidden=512, n_experts=12, inter=64, shared_inter=0, capacity=5,
+                                        top_k=4, seed=77)
+    monkeypatch.setenv("MOE_FUSE_BOUNDARY", "1")
+    monkeypatch.setenv("MOE_TAG_SPINS", "1")
+    store, dec = build(cfg, lam=0.5)
+    assert dec.plan().boundary_in_expert_launch == 1
+    a = workloads.ar1_stream(cfg, 1).to(DEV)
+    h = torch.zeros(cfg.hidden, device=DEV)
+    x = torch.zeros(cfg.hidden, dtype=cfg.act_dtype, device=DEV)
+    torch.cuda.synchronize()
+    print("case bounded wait: one step with a poll limit of one", flush=True)
+    assert dec.stack_route_step(0, h, a[0, 0], 1.0, x, carry=False, y=None, wait=False) is None
+    dec.expert_forward(0, x, None)
+    dec.compute_stream.synchronize()
+    with pytest.raises(pkg.MoEError) as e:
+        dec.tables(0)
+    assert e.value.code == pkg.MOE_EHIP
+    dec.reset()
+    assert dec.tables(0).count == 0 and dec.stats(0).tokens == 0
+    dec.close()
