@@ -40,7 +40,10 @@ typedef struct moe_cache moe_cache_t; /* opaque, owned by the library */
 enum moe_status { MOE_OK = 0, MOE_EINVAL = -1, MOE_ENOMEM = -2, MOE_EHIP = -3, MOE_ESTATE = -4 };
 enum moe_weight_fmt { MOE_W_FP32 = 0, MOE_W_BF16 = 1, MOE_W_INT8_PC = 2, MOE_W_INT4_G128 = 3 };
 enum moe_act_fmt { MOE_A_FP32 = 0, MOE_A_BF16 = 1 };
-enum moe_delta_mode { MOE_DELTA_RUNNING_MEAN = 0, MOE_DELTA_FIXED = 1 };
+/* The logit range Delta that scales the prior (Eq. 9-10; App. D on the choice of the estimate): the running mean
+ * over the tokens seen since the last reset (the paper's method), a fixed value given by the caller (e.g. from a
+ * calibration set), or the current token's own range max z - min z. */
+enum moe_delta_mode { MOE_DELTA_RUNNING_MEAN = 0, MOE_DELTA_FIXED = 1, MOE_DELTA_TOKEN = 2 };
 /* How the ranking vector is altered before the top-K cut.  CACHE_PRIOR is the paper's method
  * (Sec. 3.3); MAX_RANK (Sec. 3.1, Eq. 6-7) and CUMSUM (Sec. 3.2, Eq. 8) are its two baselines. */
 enum moe_route_mode { MOE_ROUTE_CACHE_PRIOR = 0, MOE_ROUTE_MAX_RANK = 1, MOE_ROUTE_CUMSUM = 2 };
@@ -57,7 +60,7 @@ typedef struct moe_cache_config {
   int32_t weight_fmt;   /* moe_weight_fmt of expert blobs */
   int32_t act_fmt;      /* moe_act_fmt of x, y and the router matrix */
   int32_t renormalize;  /* 1: divide the K weights by their sum (Sec. 2.1) */
-  int32_t delta_mode;   /* moe_delta_mode: running mean of Eq. 10, or delta_fixed */
+  int32_t delta_mode;   /* moe_delta_mode */
   int32_t route_mode;   /* moe_route_mode */
   int32_t max_rank;     /* M of Eq. 6 (MOE_ROUTE_MAX_RANK) */
   float lambda;         /* >= 0, strength of the cache prior (Eq. 9) */

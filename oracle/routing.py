@@ -48,10 +48,14 @@ def ranking(v: np.ndarray) -> np.ndarray:
 
 
 class LogitRange:
-    """Delta_avg of Eq. 10 as a running mean over tokens (fp32, one rounding per step)."""
+    """Delta_avg of Eq. 10 as a running mean over tokens (fp32, one rounding per step).  Two variants of the
+    estimate (App. D discusses the choice): a fixed value, e.g. from a calibration set, and the current token's
+    own range max z - min z with no averaging at all."""
 
-    def __init__(self, fixed: float | None = None):
+    def __init__(self, fixed: float | None = None, per_token: bool = False):
+        assert fixed is None or not per_token
         self.fixed = None if fixed is None else f32(fixed)
+        self.per_token = per_token
         self.total = f32(0.0)
         self.count = 0
 
@@ -62,6 +66,8 @@ class LogitRange:
         self.count += 1
         if self.fixed is not None:
             return self.fixed
+        if self.per_token:
+            return rng
         return f32(self.total / f32(self.count))
 
 
@@ -197,12 +203,13 @@ class RouteResult:
 class CachePriorRouter:
     """One MoE layer's router state: Delta_avg accumulator + expert cache, stepped token by token."""
 
-    def __init__(self, n_experts, top_k, capacity, lam, top_j=0, renormalize=False, initial=(), delta_fixed=None):
+    def __init__(self, n_experts, top_k, capacity, lam, top_j=0, renormalize=False, initial=(), delta_fixed=None,
+                 delta_per_token=False):
         assert 0 <= top_j <= top_k <= capacity <= n_experts
         self.n, self.k, self.j = n_experts, top_k, top_j
         self.lam = lam
         self.renormalize = renormalize
-        self.range = LogitRange(delta_fixed)
+        self.range = LogitRange(delta_fixed, delta_per_token)
         self.cache = ExpertCache(n_experts, capacity, initial)
 
     def select(self, z):

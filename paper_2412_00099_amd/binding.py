@@ -18,7 +18,7 @@ MOE_MAX_TOPK = 8
 MOE_OK, MOE_EINVAL, MOE_ENOMEM, MOE_EHIP, MOE_ESTATE = 0, -1, -2, -3, -4
 MOE_W_FP32, MOE_W_BF16, MOE_W_INT8_PC, MOE_W_INT4_G128 = 0, 1, 2, 3
 MOE_A_FP32, MOE_A_BF16 = 0, 1
-MOE_DELTA_RUNNING_MEAN, MOE_DELTA_FIXED = 0, 1
+MOE_DELTA_RUNNING_MEAN, MOE_DELTA_FIXED, MOE_DELTA_TOKEN = 0, 1, 2
 MOE_ROUTE_CACHE_PRIOR, MOE_ROUTE_MAX_RANK, MOE_ROUTE_CUMSUM = 0, 1, 2
 MOE_POLICY_LRU, MOE_POLICY_FARTHEST = 0, 1
 

@@ -181,7 +181,7 @@ int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, 
       (cfg->shared_inter > 0 && !gemv_inter_supported(cfg->weight_fmt, cfg->shared_inter)))
     return fail(MOE_EINVAL, "intermediate size unsupported for this weight format (int8: multiple of 8, int4: multiple of 128)");
   if (!(cfg->lambda >= 0.f) || !std::isfinite(cfg->lambda)) return fail(MOE_EINVAL, "lambda must be finite and >= 0");
-  if (cfg->delta_mode != MOE_DELTA_RUNNING_MEAN && cfg->delta_mode != MOE_DELTA_FIXED) return fail(MOE_EINVAL, "bad delta_mode");
+  if (cfg->delta_mode < MOE_DELTA_RUNNING_MEAN || cfg->delta_mode > MOE_DELTA_TOKEN) return fail(MOE_EINVAL, "bad delta_mode");
   if (cfg->delta_mode == MOE_DELTA_FIXED && !std::isfinite(cfg->delta_fixed)) return fail(MOE_EINVAL, "delta_fixed must be finite");
   if (cfg->route_mode < MOE_ROUTE_CACHE_PRIOR || cfg->route_mode > MOE_ROUTE_CUMSUM) return fail(MOE_EINVAL, "bad route_mode");
   if (cfg->route_mode == MOE_ROUTE_MAX_RANK && (cfg->max_rank < 0 || cfg->max_rank > cfg->n_experts))

@@ -200,7 +200,9 @@ __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_
   const float range = zmax - zmin;
   const float dsum = dsum_prev + range;
   const int cnt = t + 1;
-  const float delta = (p.delta_mode == MOE_DELTA_FIXED) ? p.delta_fixed : dsum / (float)cnt;
+  const float delta = p.delta_mode == MOE_DELTA_FIXED ? p.delta_fixed
+                      : p.delta_mode == MOE_DELTA_TOKEN ? range
+                                                        : dsum / (float)cnt;
 
   const bool resident = my_slot >= 0;
 

@@ -82,7 +82,8 @@ class MoEDecoder:
     """One library context over an ExpertStore."""
 
     def __init__(self, store: ExpertStore, *, top_k, top_j=0, lam=0.0, renormalize=False, initial=None,
-                 delta_fixed=None, route_mode=B.MOE_ROUTE_CACHE_PRIOR, max_rank=0, cumsum_p=0.0):
+                 delta_fixed=None, delta_per_token=False, route_mode=B.MOE_ROUTE_CACHE_PRIOR, max_rank=0,
+                 cumsum_p=0.0):
         self.store = store
         dev = store.device
         self.compute_stream = torch.cuda.Stream(device=dev)
@@ -93,7 +94,9 @@ class MoEDecoder:
         cfg.top_k, cfg.top_j, cfg.capacity = top_k, top_j, store.cap
         cfg.weight_fmt, cfg.act_fmt = store.wfmt, store.afmt
         cfg.renormalize = int(renormalize)
-        cfg.delta_mode = B.MOE_DELTA_FIXED if delta_fixed is not None else B.MOE_DELTA_RUNNING_MEAN
+        assert delta_fixed is None or not delta_per_token
+        cfg.delta_mode = (B.MOE_DELTA_FIXED if delta_fixed is not None else
+                          B.MOE_DELTA_TOKEN if delta_per_token else B.MOE_DELTA_RUNNING_MEAN)
         cfg.delta_fixed = float(delta_fixed or 0.0)
         cfg.route_mode, cfg.max_rank, cfg.cumsum_p = route_mode, max_rank, cumsum_p
         cfg.lambda_ = float(lam)

@@ -22,7 +22,8 @@ def np_expert(weights: dict) -> dict:
     return {k: to_np(v) for k, v in weights.items()}
 
 
-def build(cfg, *, lam=0.0, top_j=None, initial=None, delta_fixed=None, route_mode=0, max_rank=0, cumsum_p=0.0):
+def build(cfg, *, lam=0.0, top_j=None, initial=None, delta_fixed=None, delta_per_token=False, route_mode=0,
+          max_rank=0, cumsum_p=0.0):
     import paper_2412_00099_amd as pkg
 
     store = pkg.ExpertStore(
@@ -33,8 +34,8 @@ def build(cfg, *, lam=0.0, top_j=None, initial=None, delta_fixed=None, route_mod
     store.fill_from(cfg, workloads.expert_weights, workloads.shared_weights, workloads.gate_weight)
     dec = pkg.MoEDecoder(
         store, top_k=cfg.top_k, top_j=cfg.top_j if top_j is None else top_j, lam=lam,
-        renormalize=cfg.renormalize, initial=initial, delta_fixed=delta_fixed, route_mode=route_mode,
-        max_rank=max_rank, cumsum_p=cumsum_p,
+        renormalize=cfg.renormalize, initial=initial, delta_fixed=delta_fixed, delta_per_token=delta_per_token,
+        route_mode=route_mode, max_rank=max_rank, cumsum_p=cumsum_p,
     )
     return store, dec
 

@@ -20,11 +20,13 @@ pytestmark = pytest.mark.gpu
 TINY = CONFIGS["c1_single_fp32"].with_(inter=64)  # small blobs: these tests are about routing
 
 
-def run_logits_case(cfg, lam, top_j, T, initial=None, scale=1.0, delta_fixed=None, logits=None):
-    store, dec = build(cfg, lam=lam, top_j=top_j, initial=initial, delta_fixed=delta_fixed)
+def run_logits_case(cfg, lam, top_j, T, initial=None, scale=1.0, delta_fixed=None, logits=None, delta_per_token=False):
+    store, dec = build(cfg, lam=lam, top_j=top_j, initial=initial, delta_fixed=delta_fixed,
+                       delta_per_token=delta_per_token)
     N, K, C = cfg.n_experts, cfg.top_k, cfg.capacity
     routers = [routing.CachePriorRouter(N, K, C, lam, top_j, cfg.renormalize,
-                                        initial[l] if initial else (), delta_fixed) for l in range(cfg.n_layers)]
+                                        initial[l] if initial else (), delta_fixed, delta_per_token)
+               for l in range(cfg.n_layers)]
     x = torch.zeros(cfg.hidden, dtype=cfg.act_dtype, device=DEV)
     y = torch.zeros(cfg.hidden, dtype=cfg.act_dtype, device=DEV)
     zs = [workloads.logits_stream(cfg, T, layer=l, scale=scale) if logits is None else logits
@@ -76,6 +78,8 @@ def test_initial_residents_renormalise_fixed_delta():
     run_logits_case(cfg, 0.5, 1, 128, initial=init)
     print("case fixed delta", flush=True)
     run_logits_case(cfg, 0.5, 0, 64, delta_fixed=1.75)
+    print("case delta = the token's own range", flush=True)
+    run_logits_case(cfg, 0.5, 1, 96, delta_per_token=True, scale=1.5)
 
 
 def test_fixed_points_on_device():

@@ -190,6 +190,32 @@ def test_delta_fp32_steps_exact():
     assert out[1] == f32(f32(a + a) / f32(2.0))
 
 
+def test_per_token_range_variant():
+    """Delta = the current token's own range (App. D on the choice of the estimate).  What the arithmetic fixes:
+    lambda > 1 lifts every resident expert above every logit of the token, so with at least K residents nothing
+    ever misses again; at lambda = 0 the estimate does not matter; and the first token agrees with the running
+    mean, whose first value is that token's range."""
+    N, K, C = 24, 3, 8
+    z = ar1_logits(300, N, seed=23, scale=2.0)
+    r = CachePriorRouter(N, K, C, 1.25, delta_per_token=True)
+    for t in range(len(z)):
+        out = r.step(z[t])
+        assert out.delta == f32(np.ptp(z[t]))
+        assert t == 0 or not any(out.miss), t
+    assert r.stats.misses == K
+    a = CachePriorRouter(N, K, C, 0.0, delta_per_token=True)
+    b = CachePriorRouter(N, K, C, 0.0)
+    for t in range(100):
+        ra, rb = a.step(z[t]), b.step(z[t])
+        assert ra.sel.tolist() == rb.sel.tolist() and ra.miss == rb.miss
+    c = CachePriorRouter(N, K, C, 0.7, delta_per_token=True)
+    d = CachePriorRouter(N, K, C, 0.7)
+    assert c.step(z[0]).delta == d.step(z[0]).delta
+    # between the two extremes the two estimates do select differently on this stream
+    differs = sum(c.step(z[t]).sel.tolist() != d.step(z[t]).sel.tolist() for t in range(1, 300))
+    assert differs > 0
+
+
 # ---------------------------------------------------------------- LRU vs brute force, random tiny traces
 
 
