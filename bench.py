@@ -37,8 +37,8 @@ PERTURB = 0.5
 # only for the kernel sources it was taken with: reported as null once their hash differs.
 GEMV_TRAFFIC = {
     "workload": "c2_qwen_bf16",
-    "sources_sha256": "20becc7bd0b381007649f3df7724809ddd093b07b642395a0a6cb47c040d8226",
-    "fetch_kib": 68080.0, "fetch_scale": 2.0,
+    "sources_sha256": "dd6cfa3629af376021eb9332fe9b1348cec0ebb0efff0a1c94f0bda2b71d4180",
+    "fetch_kib": 68079.7, "fetch_scale": 2.0,
     "write_kib": 2061.7, "write_scale": 1.0,
 }
 GEMV_SOURCES = ("expert_gemv.hip", "gemv_common.h", "route_device.h", "common.h")

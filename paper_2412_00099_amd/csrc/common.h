@@ -113,6 +113,8 @@ struct GemvPlan {
 };
 GemvPlan gemv_plan(int n_cus, int total_records, int weight_fmt, int act_fmt);
 bool gemv_fused_supported(int weight_fmt, int act_fmt, int hidden, const GemvPlan &plan);  // a launch variant with the boundary in workgroup 0
+// f.ss != nullptr: the glue has been done by launch_reduce_glue (needs fused_route_pre_supported(hidden))
+bool fused_route_pre_supported(int hidden);
 hipError_t launch_fused_route(const RouteParams &p, const FusedParams &f, const void *gate_w, LayerState *state,
                               moe_route_out_t *out_dev, HostNote *note_mapped, hipStream_t s);
 hipError_t launch_expert_gemv(const GemvParams &p, int weight_fmt, const GemvPlan &plan, hipStream_t s,

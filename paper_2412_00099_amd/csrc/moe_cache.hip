@@ -455,13 +455,22 @@ int moe_stack_route_step(moe_cache_t *c, int32_t layer, float *h_dev, const floa
     c->routed[layer] = 3;
     return MOE_OK;
   }
-  if (c->pending_rows > 0)
-    HIP_TRY(launch_partial_reduce(c->d_partial, c->pending_rows, y, c->cfg.hidden, c->cfg.act_fmt, c->compute));
+  if (fused_route_pre_supported(c->cfg.hidden)) {
+    // the sum of the pending output and the residual glue spread over d / 64 workgroups; the single-workgroup
+    // boundary launch then starts from h and the sums of squares
+    HIP_TRY(launch_reduce_glue(c->d_partial, c->pending_rows, y, c->cfg.hidden, c->cfg.act_fmt, h_dev, a_dev, perturb,
+                               carry, c->d_ss, c->compute));
+    f.ss = c->d_ss;
+    f.n_ss = c->cfg.hidden / 64;
+  } else {
+    if (c->pending_rows > 0)
+      HIP_TRY(launch_partial_reduce(c->d_partial, c->pending_rows, y, c->cfg.hidden, c->cfg.act_fmt, c->compute));
+    f.y = y;
+    f.a = a_dev;
+    f.perturb = perturb;
+    f.carry = carry;
+  }
   c->pending_rows = 0;
-  f.y = y;
-  f.a = a_dev;
-  f.perturb = perturb;
-  f.carry = carry;
   HIP_TRY(launch_fused_route(p, f, c->gate_w[layer], c->d_state + layer, c->d_route + layer, c->h_note_dev + layer,
                              c->compute));
   return finish_route_call(c, layer, p.seq, out_host);

@@ -44,13 +44,15 @@ __global__ __launch_bounds__(1024) void route_kernel(RouteParams p, const void *
 }
 
 
-// The layer boundary as a launch of its own (one workgroup of 16 wavefronts): see fused_boundary.
-template <int CH, int PER>
+// The layer boundary as a launch of its own (one workgroup of 16 wavefronts): see fused_boundary.  PRE: the residual
+// glue and the sums of squares were left by reduce_glue_kernel; the boundary starts from h.
+template <int CH, int PER, bool PRE>
 __global__ __launch_bounds__(1024) void fused_route_kernel(RouteParams p, FusedParams f, const void *gate_w,
                                                            LayerState *st, moe_route_out_t *out_dev,
                                                            HostNote *note) {
   __shared__ __attribute__((aligned(16))) uint32_t lds[kBoundaryLdsWords];
-  fused_boundary<16, CH, PER>(p, f, gate_w, st, out_dev, note, BoundaryFlags{nullptr, 0}, carve_boundary_lds(lds));
+  fused_boundary<16, CH, PER, PRE>(p, f, gate_w, st, out_dev, note, BoundaryFlags{nullptr, 0},
+                                   carve_boundary_lds(lds));
 }
 
 __global__ void state_init_kernel(LayerState *state, int n_layers, const int32_t *initial, int n_initial) {
@@ -90,6 +92,10 @@ hipError_t launch_route(const RouteParams &p, const void *gate_w, const void *x,
   return hipGetLastError();
 }
 
+// hidden sizes for which the boundary can start from what reduce_glue_kernel leaves: 16 wavefronts x PER columns
+// per thread with PER in {1, 2, 4}, one sum of squares per 64 columns
+bool fused_route_pre_supported(int hidden) { return hidden == 1024 || hidden == 2048 || hidden == 4096; }
+
 hipError_t launch_fused_route(const RouteParams &p, const FusedParams &f, const void *gate_w, LayerState *state,
                               moe_route_out_t *out_dev, HostNote *note_mapped, hipStream_t s) {
   if (p.hidden > kFusedMaxHidden || p.hidden % 8 != 0) return hipErrorInvalidValue;
@@ -100,19 +106,27 @@ hipError_t launch_fused_route(const RouteParams &p, const FusedParams &f, const 
   if (ch != 1 && ch != 2 && ch != 4) ch = 0;  // more than 4 chunks per row: gate rows are not held in registers
   const int per = (p.hidden % 1024 == 0 && (p.hidden / 1024 == 1 || p.hidden / 1024 == 2 || p.hidden / 1024 == 4))
                       ? p.hidden / 1024 : 0;
-#define MOE_FUSED(CH_, PER_)                                                                                    \
-  hipLaunchKernelGGL((fused_route_kernel<CH_, PER_>), g, b, 0, s, p, f, gate_w, state, out_dev, note_mapped)
+  const bool pre = f.ss != nullptr;
+  if (pre && !fused_route_pre_supported(p.hidden)) return hipErrorInvalidValue;
+#define MOE_FUSED(CH_, PER_, PRE_)                                                                              \
+  hipLaunchKernelGGL((fused_route_kernel<CH_, PER_, PRE_>), g, b, 0, s, p, f, gate_w, state, out_dev, note_mapped)
+#define MOE_FUSED2(CH_, PER_)                                                                                   \
+  do {                                                                                                          \
+    if (pre) MOE_FUSED(CH_, PER_, true);                                                                        \
+    else MOE_FUSED(CH_, PER_, false);                                                                           \
+  } while (0)
   switch (ch * 10 + per) {  // (bf16: d = 512 ch; fp32: d = 256 ch)
-    case 42: MOE_FUSED(4, 2); break;  // bf16 d = 2048
-    case 41: MOE_FUSED(4, 1); break;  // fp32 d = 1024
-    case 21: MOE_FUSED(2, 1); break;  // bf16 d = 1024
-    case 20: MOE_FUSED(2, 0); break;  // fp32 d = 512
-    case 10: MOE_FUSED(1, 0); break;  // bf16 d = 512, fp32 d = 256
+    case 42: MOE_FUSED2(4, 2); break;         // bf16 d = 2048
+    case 41: MOE_FUSED2(4, 1); break;         // fp32 d = 1024
+    case 21: MOE_FUSED2(2, 1); break;         // bf16 d = 1024
+    case 20: MOE_FUSED(2, 0, false); break;   // fp32 d = 512
+    case 10: MOE_FUSED(1, 0, false); break;   // bf16 d = 512, fp32 d = 256
     default:
-      if (per == 2) MOE_FUSED(0, 2);       // fp32 d = 2048
-      else if (per == 4) MOE_FUSED(0, 4);  // d = 4096
-      else MOE_FUSED(0, 0);
+      if (per == 2) MOE_FUSED2(0, 2);         // fp32 d = 2048
+      else if (per == 4) MOE_FUSED2(0, 4);    // d = 4096
+      else MOE_FUSED(0, 0, false);
   }
+#undef MOE_FUSED2
 #undef MOE_FUSED
   return hipGetLastError();
 }
