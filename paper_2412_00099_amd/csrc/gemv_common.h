@@ -58,10 +58,11 @@ __device__ __forceinline__ void wave_sum2(float &a, float &b) {
 // skewed by XCD parity) leave the kernel time unchanged - the XCDs that finish early free bandwidth for the
 // late ones, so the spread is not lost time.  Fixed shares keep the summation order of y, hence y itself,
 // identical from run to run.
-// Bounded wait for a tag another workgroup of the same launch publishes after an agent-scope release fence.
+// Bounded wait for a tag another workgroup of the same launch stores (relaxed, agent scope).
 // False if it did not appear within about a tenth of a second (the caller then skips its work and reports).
 // No agent-scope acquire follows: it would invalidate the XCD's L2 under thirty-two streaming compute units
-// (measured: the launch ran at half speed).  What the tag announces is read with ld128<true> / ld64<true> instead.
+// (measured: the launch ran at half speed).  What the tag announces is read with agent-scope atomic loads and
+// carries its own tags (RecordWalker::load_handover), so the tag is a hint, not a release.
 __device__ __forceinline__ bool wait_tag(const uint32_t *word, uint32_t tag, int spin_limit) {
   for (int i = 0; i < spin_limit; ++i) {
     const uint32_t v = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -102,7 +103,7 @@ __device__ __forceinline__ u32x2 ld64(const void *p) {
 }
 
 // FUSED: workgroup 0 of the launch runs the layer boundary; the records are shared among workgroups 1..G-1 and
-// the routing record is loaded only when the first routed entry comes up, after its tag has appeared.
+// the decision is fetched only when the first routed entry comes up, once workgroup 0 has handed it over.
 template <int NW, bool FUSED = false>
 struct RecordWalker {
   int s0, q0, ns, nl;  // this workgroup's shared rows start at s0 (ns of them), routed records at q0; nl entries
@@ -125,6 +126,44 @@ struct RecordWalker {
     rw0 = ld128<FUSED>(rr + offsetof(moe_route_out_t, sel_weight) / 16);
     rw1 = ld128<FUSED>(rr + offsetof(moe_route_out_t, sel_weight) / 16 + 1);
     rd = ld128<FUSED>(rr + offsetof(moe_route_out_t, seq) / 16);
+  }
+
+  // FUSED: the decision as workgroup 0 of this launch hands it over - eight 8-byte words, each carrying the low
+  // half of the step's tag beside 48 bits of payload (layout: rt::BoundaryFlags).  The words are taken only when all
+  // eight carry the tag, whatever order their stores arrived in; re-read until they do, at most spin_limit times.
+  __device__ __forceinline__ bool load_handover(const uint64_t *words, uint32_t seq, int spin_limit) {
+    const uint32_t want = seq & 0xffffu;
+    for (int i = 0; i < spin_limit; ++i) {
+      uint64_t q[8];
+      uint32_t tags_ok = 1;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        q[j] = __hip_atomic_load(words + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        tags_ok &= (uint32_t)(((uint32_t)q[j] & 0xffffu) == want);
+      }
+      if (__builtin_amdgcn_readfirstlane((int)tags_ok)) {
+        // the same in every lane: kept in scalar registers from here on
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          q[j] = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(q[j] >> 32)) << 16) |
+                 (uint64_t)((uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)q[j]) >> 16);
+        rd.x = seq;
+        rd.y = (uint32_t)q[0];
+        rd.z = (uint32_t)(q[0] >> 32) | ((uint32_t)(q[1] & 0xffffu) << 16);
+        rd.w = (uint32_t)(q[1] >> 16) & 0xffu;
+        rw0.x = (uint32_t)q[2];
+        rw0.y = (uint32_t)(q[2] >> 32) | ((uint32_t)q[3] << 16);
+        rw0.z = (uint32_t)(q[3] >> 16);
+        rw0.w = (uint32_t)q[4];
+        rw1.x = (uint32_t)(q[4] >> 32) | ((uint32_t)q[5] << 16);
+        rw1.y = (uint32_t)(q[5] >> 16);
+        rw1.z = (uint32_t)q[6];
+        rw1.w = (uint32_t)(q[6] >> 32) | ((uint32_t)q[7] << 16);
+        return true;
+      }
+      __builtin_amdgcn_s_sleep(2);
+    }
+    return false;
   }
 
   __device__ __forceinline__ void init(const GemvParams &p, int wave) {
@@ -176,8 +215,8 @@ struct RecordWalker {
     if (seg < 0) {  // first routed entry: unpack the routing record, locate the entry
       bool ok = true;
       if constexpr (FUSED) {
-        ok = wait_tag(p.b.tags + 16 * (int)blockIdx.x, p.b.route.seq, p.b.spin_limit);
-        load_record(p);
+        ok = wait_tag(p.b.tags + 16 * (int)blockIdx.x, p.b.route.seq, p.b.spin_limit) &&
+             load_handover(p.b.handover, p.b.route.seq, p.b.spin_limit);
       }
       slots = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)rd.y) |
               ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)rd.z) << 32);
