@@ -56,11 +56,9 @@ struct BoundaryArgs {
   LayerState *state;
   moe_route_out_t *out_dev;  // the layer's device record (= GemvParams::route)
   struct HostNote *note;     // the layer's words in mapped host memory
-  uint32_t *tags;            // device words [grid] 64 bytes apart: "decision handed over", one copy per
-                             // workgroup (compared with route.seq)
-  uint64_t *handover;        // the layer's eight self-tagged words with slots, miss flags and weights
-  uint32_t *gave_up;         // mapped host word set when a wavefront stopped waiting for a tag
-  int spin_limit;            // polls of a tag before a wavefront stops waiting (kTagSpins unless a test lowers it)
+  uint64_t *handover;        // the layer's self-tagged words with slots, miss flags and weights (8 copies of 8)
+  uint32_t *gave_up;         // mapped host word set when a wavefront stopped waiting for the hand-over
+  int spin_limit;            // polls of the hand-over before a wavefront stops waiting (a test lowers it)
   // what the boundary of the layer that follows will read first (its gate matrix and cache state): workgroup 0
   // touches it once its own work is done, which measurably shortens that boundary (nullptr: don't)
   const void *next_gate_w;

@@ -58,23 +58,6 @@ __device__ __forceinline__ void wave_sum2(float &a, float &b) {
 // skewed by XCD parity) leave the kernel time unchanged - the XCDs that finish early free bandwidth for the
 // late ones, so the spread is not lost time.  Fixed shares keep the summation order of y, hence y itself,
 // identical from run to run.
-// Bounded wait for a tag another workgroup of the same launch stores (relaxed, agent scope).
-// False if it did not appear within about a tenth of a second (the caller then skips its work and reports).
-// No agent-scope acquire follows: it would invalidate the XCD's L2 under thirty-two streaming compute units
-// (measured: the launch ran at half speed).  What the tag announces is read with agent-scope atomic loads and
-// carries its own tags (RecordWalker::load_handover), so the tag is a hint, not a release.
-__device__ __forceinline__ bool wait_tag(const uint32_t *word, uint32_t tag, int spin_limit) {
-  for (int i = 0; i < spin_limit; ++i) {
-    const uint32_t v = __hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if ((uint32_t)__builtin_amdgcn_readfirstlane((int)v) == tag) {
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");  // keeps the loads that follow behind the poll
-      return true;
-    }
-    __builtin_amdgcn_s_sleep(2);
-  }
-  return false;
-}
-
 // 16 / 8 bytes; COH: with agent-scope atomic loads, which see what another workgroup of the same launch wrote
 // before its release fence whatever this XCD's L2 holds for the address
 template <bool COH>
@@ -131,6 +114,8 @@ struct RecordWalker {
   // FUSED: the decision as workgroup 0 of this launch hands it over - eight 8-byte words, each carrying the low
   // half of the step's tag beside 48 bits of payload (layout: rt::BoundaryFlags).  The words are taken only when all
   // eight carry the tag, whatever order their stores arrived in; re-read until they do, at most spin_limit times.
+  // No agent-scope acquire is involved (it would invalidate the XCD's L2 under thirty-two streaming compute
+  // units - measured: the launch ran at half speed): the words are read with agent-scope atomic loads.
   __device__ __forceinline__ bool load_handover(const uint64_t *words, uint32_t seq, int spin_limit) {
     const uint32_t want = seq & 0xffffu;
     for (int i = 0; i < spin_limit; ++i) {
@@ -215,8 +200,8 @@ struct RecordWalker {
     if (seg < 0) {  // first routed entry: unpack the routing record, locate the entry
       bool ok = true;
       if constexpr (FUSED) {
-        ok = wait_tag(p.b.tags + 16 * (int)blockIdx.x, p.b.route.seq, p.b.spin_limit) &&
-             load_handover(p.b.handover, p.b.route.seq, p.b.spin_limit);
+        // (one wavefront per workgroup fetching for all eight through LDS was measured: no faster)
+        ok = load_handover(p.b.handover + 8 * ((int)blockIdx.x % 8), p.b.route.seq, p.b.spin_limit);
       }
       slots = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)rd.y) |
               ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)rd.z) << 32);

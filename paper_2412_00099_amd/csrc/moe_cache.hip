@@ -72,10 +72,9 @@ struct moe_cache {
   std::vector<Decision> decided;
   // layer boundaries deferred into the expert launch (see BoundaryArgs)
   std::vector<BoundaryArgs> boundary;
-  uint32_t *d_tags = nullptr;       // [grid] publication tags, 64 bytes apart
-  uint64_t *d_handover = nullptr;   // [n_layers][8] self-tagged words: a boundary's decision for its own launch
+  uint64_t *d_handover = nullptr;   // [n_layers][64] self-tagged words: a boundary's decision for its own launch
   float *d_ss = nullptr;            // [128] sums of squares of the residual stream per 64 columns
-  uint32_t *h_gave_up = nullptr;    // pinned, mapped: set by a wavefront that stopped waiting for a tag
+  uint32_t *h_gave_up = nullptr;    // pinned, mapped: set by a wavefront that stopped waiting for the hand-over
   uint32_t *h_gave_up_dev = nullptr;
   bool fuse_boundary = true;        // run deferred boundaries inside the expert launch (see moe_cache_init)
   bool prefetch_gate = true;        // MOE_PREFETCH_GATE=0: workgroup 0 does not touch the next layer's gate matrix
@@ -258,10 +257,8 @@ int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, 
                          hipHostMallocMapped | hipHostMallocCoherent));
   memset(c->h_note, 0, sizeof(HostNote) * L);
   HIP_INIT(hipHostGetDevicePointer(reinterpret_cast<void **>(&c->h_note_dev), c->h_note, 0));
-  HIP_INIT(hipMalloc(&c->d_tags, sizeof(uint32_t) * 16 * (size_t)c->plan.grid));
-  HIP_INIT(hipMemset(c->d_tags, 0, sizeof(uint32_t) * 16 * (size_t)c->plan.grid));
-  HIP_INIT(hipMalloc(&c->d_handover, sizeof(uint64_t) * 8 * (size_t)L));
-  HIP_INIT(hipMemset(c->d_handover, 0, sizeof(uint64_t) * 8 * (size_t)L));
+  HIP_INIT(hipMalloc(&c->d_handover, sizeof(uint64_t) * 64 * (size_t)L));
+  HIP_INIT(hipMemset(c->d_handover, 0, sizeof(uint64_t) * 64 * (size_t)L));
   HIP_INIT(hipMalloc(&c->d_ss, sizeof(float) * 128));
   HIP_INIT(hipMemset(c->d_ss, 0, sizeof(float) * 128));
   HIP_INIT(hipHostMalloc(reinterpret_cast<void **>(&c->h_gave_up), sizeof(uint32_t),
@@ -294,7 +291,6 @@ void moe_cache_destroy(moe_cache_t *c) {
   if (c->d_state) (void)hipFree(c->d_state);
   if (c->d_route) (void)hipFree(c->d_route);
   if (c->h_note) (void)hipHostFree(c->h_note);
-  if (c->d_tags) (void)hipFree(c->d_tags);
   if (c->d_handover) (void)hipFree(c->d_handover);
   if (c->d_ss) (void)hipFree(c->d_ss);
   if (c->h_gave_up) (void)hipHostFree(c->h_gave_up);
@@ -449,8 +445,7 @@ int moe_stack_route_step(moe_cache_t *c, int32_t layer, float *h_dev, const floa
     b.state = c->d_state + layer;
     b.out_dev = c->d_route + layer;
     b.note = c->h_note_dev + layer;
-    b.tags = c->d_tags;
-    b.handover = c->d_handover + 8 * (size_t)layer;
+    b.handover = c->d_handover + 64 * (size_t)layer;
     b.gave_up = c->h_gave_up_dev;
     b.spin_limit = c->tag_spins;
     b.next_gate_w = c->prefetch_gate ? c->gate_w[(layer + 1) % c->cfg.n_layers] : nullptr;

@@ -163,28 +163,25 @@ __device__ __forceinline__ CacheRegs load_cache_regs(const LayerState *st, int l
 }
 
 // Where a layer-boundary step hands its decision to the other workgroups of the same launch (expert kernels that
-// run the boundary in their first workgroup).
-//   handover[0..7]: what they need - the K slots, the miss flags and the K weights - as eight 8-byte words, each
-//     complete in itself: bits 0..15 = the low half of the step's tag, bits 16..63 = 48 bits of payload
-//       word 0: slots of positions 0..5 (8 bits each)      word 1: slots of positions 6, 7 | miss flags << 16
-//       words 2..7: the eight fp32 weights as one 256-bit string, 48 bits per word
-//     A reader accepts the eight words only when all carry the tag it waits for, so no order between the stores
-//     (or between them and the words below) is assumed: 8-byte atomic stores and loads, no fence.
-//   words[16*b] = tag, b < n: a hint for workgroup b that the hand-over is on its way.  Every waiting workgroup
-//     polls a word of its own, 64 bytes apart (thousands of wavefronts polling one address serialise in the
-//     memory system).
-// words = nullptr when nobody waits (separate router launch).
+// run the boundary in their first workgroup): what they need - the K slots, the miss flags and the K weights - as
+// eight 8-byte words, each complete in itself: bits 0..15 = the low half of the step's tag, bits 16..63 = 48 bits
+// of payload
+//     word 0: slots of positions 0..5 (8 bits each)      word 1: slots of positions 6, 7 | miss flags << 16
+//     words 2..7: the eight fp32 weights as one 256-bit string, 48 bits per word
+// A reader accepts the eight words only when all carry the tag it waits for, so no order between the stores is
+// assumed: 8-byte atomic stores and loads, no fence.  The block is written kHandoverCopies times, 64 bytes apart,
+// by one store instruction; workgroup b reads copy b % kHandoverCopies (hundreds of wavefronts polling one line
+// serialise in the memory system).  handover = nullptr when nobody waits (separate router launch).
 struct BoundaryFlags {
-  uint32_t *words;
-  int n;
   uint64_t *handover;
 };
-constexpr int kTagStride = 16;  // dwords
+constexpr int kHandoverCopies = 8;
+static_assert(kHandoverCopies * 8 == kWave, "one lane per word of every copy");
 
 // Everything after the logits (Eq. 3 softmax, Eq. 10, Eq. 9, Eq. 2, Eq. 4, Sec. 4.2), run by one wavefront.
 __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_s, const CacheRegs &cr, LayerState *st,
                                            moe_route_out_t *out_dev, HostNote *note, uint32_t *rec_s, int lane,
-                                           BoundaryFlags flags = BoundaryFlags{nullptr, 0, nullptr}) {
+                                           BoundaryFlags flags = BoundaryFlags{nullptr}) {
 #pragma clang fp contract(off)
   const int N = p.n_experts, K = p.top_k, C = p.capacity;
   int my_slot = cr.my_slot, slot_exp = cr.slot_exp;
@@ -335,31 +332,27 @@ __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_
     __hip_atomic_store(&note->w[lane], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
   }
 
-  // ---- expert kernels waiting in the same launch need weights, slots and miss flags: the hand-over words go out
-  // first, then the tags (see BoundaryFlags; nothing depends on the order in which they arrive)
-  if (flags.words != nullptr) {
+  // ---- expert kernels waiting in the same launch need weights, slots and miss flags (see BoundaryFlags)
+  if (flags.handover != nullptr) {
     if (lane <= MOE_MAX_TOPK) rec_s[W_WEIGHT + lane] = 0u;  // W_WEIGHT + 8 (= W_MISS) is rewritten further down
     __builtin_amdgcn_wave_barrier();
     if (sel) rec_s[W_WEIGHT + rank_p] = __float_as_uint(w);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    if (lane < 8) {
-      uint64_t payload;
-      if (lane == 0) {
-        payload = ((uint64_t)lo | ((uint64_t)hi << 32)) & 0xffffffffffffull;
-      } else if (lane == 1) {
-        payload = (uint64_t)(hi >> 16) | ((uint64_t)(mm & 0xffu) << 16);
-      } else {
-        const int bit = 48 * (lane - 2), i = bit >> 5, sh = bit & 31;  // position in the 256-bit weight string
-        const uint64_t two = (uint64_t)rec_s[W_WEIGHT + i] | ((uint64_t)rec_s[W_WEIGHT + i + 1] << 32);
-        payload = (two >> sh) & 0xffffffffffffull;
-      }
-      __hip_atomic_store(flags.handover + lane, (payload << 16) | (uint64_t)(p.seq & 0xffffu), __ATOMIC_RELAXED,
-                         __HIP_MEMORY_SCOPE_AGENT);
+    const int word = lane & 7;  // lane = copy * 8 + word
+    uint64_t payload;
+    if (word == 0) {
+      payload = ((uint64_t)lo | ((uint64_t)hi << 32)) & 0xffffffffffffull;
+    } else if (word == 1) {
+      payload = (uint64_t)(hi >> 16) | ((uint64_t)(mm & 0xffu) << 16);
+    } else {
+      const int bit = 48 * (word - 2), i = bit >> 5, sh = bit & 31;  // position in the 256-bit weight string
+      const uint64_t two = (uint64_t)rec_s[W_WEIGHT + i] | ((uint64_t)rec_s[W_WEIGHT + i + 1] << 32);
+      payload = (two >> sh) & 0xffffffffffffull;
     }
-    for (int b = lane; b < flags.n; b += kWave)
-      __hip_atomic_store(flags.words + kTagStride * b, p.seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(flags.handover + lane, (payload << 16) | (uint64_t)(p.seq & 0xffffu), __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
   }
 
   // margin between the K-th and (K+1)-th altered logit: one more arg-max round
@@ -712,7 +705,7 @@ template <int NW, int CH, int PER>
 __device__ __forceinline__ void boundary_workgroup(const GemvParams &p, float *red) {
   const int tid = threadIdx.x, d = p.hidden;
   fused_boundary<NW, CH, PER, true>(p.b.route, p.b.glue, p.b.gate_w, p.b.state, p.b.out_dev, p.b.note,
-                                    BoundaryFlags{p.b.tags, (int)gridDim.x, p.b.handover},
+                                    BoundaryFlags{p.b.handover},
                                     carve_boundary_lds(reinterpret_cast<uint32_t *>(red)));
   float *row = p.partial + (int64_t)p.row_offset * d;  // this workgroup's partial row: nothing to add
   for (int j = tid; j < d; j += NW * kWave) row[j] = 0.f;
