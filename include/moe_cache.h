@@ -231,7 +231,7 @@ int moe_cache_plan(moe_cache_t *ctx, moe_cache_plan_t *out_host);
  * on compute_stream.  enable = 0 switches the timing off, enable = n > 0 times every n-th first-pass launch from
  * this call on (1 = all of them; events on every launch slow the host down to where the device idles between
  * launches, a stride co-prime to the layer count samples every layer without that); at most 32768 launches are
- * timed between two resets, later ones run untimed.  Each timed launch is preceded by a 15 us hold of the stream,
+ * timed between two resets, later ones run untimed.  Each timed launch is preceded by a 50 us hold of the stream,
  * so that the kernel is already queued behind its start marker when the device reaches the marker. */
 int moe_cache_profile(moe_cache_t *ctx, int32_t enable, int32_t reset, double *avg_us, int64_t *launches);
 

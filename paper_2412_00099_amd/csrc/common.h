@@ -48,7 +48,7 @@ struct FusedParams {
 
 // The layer boundary (x from the new residual stream + routing step, see rt::fused_boundary) when it is run by
 // workgroup 0 of the expert launch itself: the other workgroups compute x for themselves, stream the shared
-// expert's records meanwhile, and wait for a tag before the first routed record.
+// expert's records meanwhile, and wait for its decision before the first routed record.
 struct BoundaryArgs {
   RouteParams route;
   FusedParams glue;

@@ -30,13 +30,12 @@ struct Chunk;
 template <>
 struct Chunk<MOE_W_FP32, false> {
   static constexpr int VEC = 4, XW = 4;
-  template <bool COH>
   static __device__ __forceinline__ void load_x(const void *x, int act_fmt, int col, float *xr) {
     if (act_fmt == MOE_A_BF16) {
-      const u32x2 v = ld64<COH>(static_cast<const uint16_t *>(x) + col);
+      const u32x2 v = ld64(static_cast<const uint16_t *>(x) + col);
       xr[0] = bf16_lo(v.x); xr[1] = bf16_hi(v.x); xr[2] = bf16_lo(v.y); xr[3] = bf16_hi(v.y);
     } else {
-      const u32x4 v = ld128<COH>(static_cast<const float *>(x) + col);
+      const u32x4 v = ld128(static_cast<const float *>(x) + col);
       xr[0] = __uint_as_float(v.x); xr[1] = __uint_as_float(v.y); xr[2] = __uint_as_float(v.z);
       xr[3] = __uint_as_float(v.w);
     }
@@ -69,15 +68,14 @@ struct Chunk<MOE_W_FP32, false> {
 template <>
 struct Chunk<MOE_W_BF16, false> {
   static constexpr int VEC = 8, XW = 8;
-  template <bool COH>
   static __device__ __forceinline__ void load_x(const void *x, int act_fmt, int col, float *xr) {
     if (act_fmt == MOE_A_BF16) {
-      const u32x4 v = ld128<COH>(static_cast<const uint16_t *>(x) + col);
+      const u32x4 v = ld128(static_cast<const uint16_t *>(x) + col);
       xr[0] = bf16_lo(v.x); xr[1] = bf16_hi(v.x); xr[2] = bf16_lo(v.y); xr[3] = bf16_hi(v.y);
       xr[4] = bf16_lo(v.z); xr[5] = bf16_hi(v.z); xr[6] = bf16_lo(v.w); xr[7] = bf16_hi(v.w);
     } else {
       const float *p = static_cast<const float *>(x) + col;
-      const u32x4 a = ld128<COH>(p), b = ld128<COH>(p + 4);
+      const u32x4 a = ld128(p), b = ld128(p + 4);
       xr[0] = __uint_as_float(a.x); xr[1] = __uint_as_float(a.y); xr[2] = __uint_as_float(a.z);
       xr[3] = __uint_as_float(a.w); xr[4] = __uint_as_float(b.x); xr[5] = __uint_as_float(b.y);
       xr[6] = __uint_as_float(b.z); xr[7] = __uint_as_float(b.w);
@@ -123,9 +121,8 @@ struct Chunk<MOE_W_BF16, false> {
 template <>
 struct Chunk<MOE_W_BF16, true> {
   static constexpr int VEC = 8, XW = 4;
-  template <bool COH>
   static __device__ __forceinline__ void load_x(const void *x, int, int col, float *xr) {
-    const u32x4 v = ld128<COH>(static_cast<const uint16_t *>(x) + col);
+    const u32x4 v = ld128(static_cast<const uint16_t *>(x) + col);
     xr[0] = __uint_as_float(v.x); xr[1] = __uint_as_float(v.y); xr[2] = __uint_as_float(v.z); xr[3] = __uint_as_float(v.w);
   }
   static __device__ __forceinline__ void load_h(const float *h, int col, float *out) {
@@ -161,9 +158,9 @@ struct RecRegs {
 // FUSED: workgroup 0 runs the layer boundary (x, gate GEMV, routing: rt::fused_boundary) instead of streaming
 // records.  The residual glue has been done by reduce_glue_kernel; every workgroup forms x for itself from the
 // new residual stream and its sums of squares (same operations in the same order everywhere, so all copies are
-// bit-identical), starts on the shared expert's records at once, and waits for the tag of the routing record only
-// before its first routed record (the shared records take longer than the routing), so the boundary costs the
-// launch next to nothing.  The wait is on workgroup 0 only, which is dispatched first, and is bounded.
+// bit-identical), starts on the shared expert's records at once, and waits for workgroup 0's decision only before
+// its first routed record (RecordWalker::load_handover), so the boundary costs the launch little.  The wait is
+// on workgroup 0 only, which is dispatched first, and is bounded.
 template <int FMT, int LPR, int NW, int DEPTH, bool DOT2, bool FUSED>
 __global__ __launch_bounds__(NW *kWave) void expert_gemv_kernel(GemvParams p) {
   using F = Chunk<FMT, DOT2>;
@@ -244,7 +241,7 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_kernel(GemvParams p) {
     for (int c = 0; c < LPR; ++c) F::make_x(&hraw[c * VEC], scale, p.act_fmt, &xr[c * XW]);
   } else {
 #pragma unroll
-    for (int c = 0; c < LPR; ++c) F::template load_x<false>(p.x, p.act_fmt, (c * kWave + lane) * VEC, &xr[c * XW]);
+    for (int c = 0; c < LPR; ++c) F::load_x(p.x, p.act_fmt, (c * kWave + lane) * VEC, &xr[c * XW]);
   }
 
   float y[CPL];

@@ -58,32 +58,8 @@ __device__ __forceinline__ void wave_sum2(float &a, float &b) {
 // skewed by XCD parity) leave the kernel time unchanged - the XCDs that finish early free bandwidth for the
 // late ones, so the spread is not lost time.  Fixed shares keep the summation order of y, hence y itself,
 // identical from run to run.
-// 16 / 8 bytes; COH: with agent-scope atomic loads, which see what another workgroup of the same launch wrote
-// before its release fence whatever this XCD's L2 holds for the address
-template <bool COH>
-__device__ __forceinline__ u32x4 ld128(const void *p) {
-  if constexpr (COH) {
-    const uint64_t *q = static_cast<const uint64_t *>(p);
-    const uint64_t a = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const uint64_t b = __hip_atomic_load(q + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    u32x4 v;
-    v.x = (uint32_t)a; v.y = (uint32_t)(a >> 32); v.z = (uint32_t)b; v.w = (uint32_t)(b >> 32);
-    return v;
-  } else {
-    return *static_cast<const u32x4 *>(p);
-  }
-}
-template <bool COH>
-__device__ __forceinline__ u32x2 ld64(const void *p) {
-  if constexpr (COH) {
-    const uint64_t a = __hip_atomic_load(static_cast<const uint64_t *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    u32x2 v;
-    v.x = (uint32_t)a; v.y = (uint32_t)(a >> 32);
-    return v;
-  } else {
-    return *static_cast<const u32x2 *>(p);
-  }
-}
+__device__ __forceinline__ u32x4 ld128(const void *p) { return *static_cast<const u32x4 *>(p); }
+__device__ __forceinline__ u32x2 ld64(const void *p) { return *static_cast<const u32x2 *>(p); }
 
 // FUSED: workgroup 0 of the launch runs the layer boundary; the records are shared among workgroups 1..G-1 and
 // the decision is fetched only when the first routed entry comes up, once workgroup 0 has handed it over.
@@ -106,9 +82,9 @@ struct RecordWalker {
 
   __device__ __forceinline__ void load_record(const GemvParams &p) {
     const u32x4 *rr = reinterpret_cast<const u32x4 *>(p.route);
-    rw0 = ld128<FUSED>(rr + offsetof(moe_route_out_t, sel_weight) / 16);
-    rw1 = ld128<FUSED>(rr + offsetof(moe_route_out_t, sel_weight) / 16 + 1);
-    rd = ld128<FUSED>(rr + offsetof(moe_route_out_t, seq) / 16);
+    rw0 = ld128(rr + offsetof(moe_route_out_t, sel_weight) / 16);
+    rw1 = ld128(rr + offsetof(moe_route_out_t, sel_weight) / 16 + 1);
+    rd = ld128(rr + offsetof(moe_route_out_t, seq) / 16);
   }
 
   // FUSED: the decision as workgroup 0 of this launch hands it over - eight 8-byte words, each carrying the low

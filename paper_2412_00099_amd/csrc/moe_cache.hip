@@ -506,7 +506,7 @@ int moe_expert_forward(moe_cache_t *c, int32_t layer, const void *x_dev, void *y
   }
   const bool prof = c->profiling && c->prof_tick++ % (uint64_t)c->profiling == 0 && c->prof_used < c->prof_events.size();
   if (prof) {
-    hipLaunchKernelGGL(hold_stream_kernel, dim3(1), dim3(64), 0, c->compute, (uint64_t)1500);  // 15 us
+    hipLaunchKernelGGL(hold_stream_kernel, dim3(1), dim3(64), 0, c->compute, (uint64_t)5000);  // 50 us
     HIP_TRY(hipGetLastError());
     HIP_TRY(launch_expert_gemv(p, g.weight_fmt, c->plan, c->compute, c->prof_events[c->prof_used].first,
                                c->prof_events[c->prof_used].second));
