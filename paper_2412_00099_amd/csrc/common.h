@@ -57,6 +57,8 @@ struct BoundaryArgs {
   moe_route_out_t *out_dev;  // the layer's device record (= GemvParams::route)
   struct HostNote *note;     // the layer's words in mapped host memory
   uint64_t *handover;        // the layer's self-tagged words with slots, miss flags and weights (8 copies of 8)
+  uint32_t hand_tag;         // 16-bit tag of this hand-over: the count of the layer's hand-overs so far, so that
+                             // what the words still hold (the previous one) can never pass for it
   uint32_t *gave_up;         // mapped host word set when a wavefront stopped waiting for the hand-over
   int spin_limit;            // polls of the hand-over before a wavefront stops waiting (a test lowers it)
   // what the boundary of the layer that follows will read first (its gate matrix and cache state): workgroup 0

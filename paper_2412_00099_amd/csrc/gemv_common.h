@@ -87,13 +87,13 @@ struct RecordWalker {
     rd = ld128(rr + offsetof(moe_route_out_t, seq) / 16);
   }
 
-  // FUSED: the decision as workgroup 0 of this launch hands it over - eight 8-byte words, each carrying the low
-  // half of the step's tag beside 48 bits of payload (layout: rt::BoundaryFlags).  The words are taken only when all
+  // FUSED: the decision as workgroup 0 of this launch hands it over - eight 8-byte words, each carrying the
+  // hand-over's 16-bit tag beside 48 bits of payload (layout: rt::BoundaryFlags).  The words are taken only when all
   // eight carry the tag, whatever order their stores arrived in; re-read until they do, at most spin_limit times.
   // No agent-scope acquire is involved (it would invalidate the XCD's L2 under thirty-two streaming compute
   // units - measured: the launch ran at half speed): the words are read with agent-scope atomic loads.
-  __device__ __forceinline__ bool load_handover(const uint64_t *words, uint32_t seq, int spin_limit) {
-    const uint32_t want = seq & 0xffffu;
+  __device__ __forceinline__ bool load_handover(const uint64_t *words, uint32_t tag, int spin_limit) {
+    const uint32_t want = tag & 0xffffu;
     for (int i = 0; i < spin_limit; ++i) {
       uint64_t q[8];
       uint32_t tags_ok = 1;
@@ -108,7 +108,7 @@ struct RecordWalker {
         for (int j = 0; j < 8; ++j)
           q[j] = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(q[j] >> 32)) << 16) |
                  (uint64_t)((uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)q[j]) >> 16);
-        rd.x = seq;
+        rd.x = tag;
         rd.y = (uint32_t)q[0];
         rd.z = (uint32_t)(q[0] >> 32) | ((uint32_t)(q[1] & 0xffffu) << 16);
         rd.w = (uint32_t)(q[1] >> 16) & 0xffu;
@@ -177,7 +177,7 @@ struct RecordWalker {
       bool ok = true;
       if constexpr (FUSED) {
         // (one wavefront per workgroup fetching for all eight through LDS was measured: no faster)
-        ok = load_handover(p.b.handover + 8 * ((int)blockIdx.x % 8), p.b.route.seq, p.b.spin_limit);
+        ok = load_handover(p.b.handover + 8 * ((int)blockIdx.x % 8), p.b.hand_tag, p.b.spin_limit);
       }
       slots = (uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)rd.y) |
               ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)rd.z) << 32);

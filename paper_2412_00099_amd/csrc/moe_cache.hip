@@ -90,6 +90,7 @@ struct moe_cache {
   std::vector<uint8_t> routed;        // per layer: 0 idle, 1 routed (decision on the host), 2 routed (not collected
                                       // yet), 3 boundary deferred into the expert launch
   std::vector<uint32_t> route_seq;    // per layer: completion tag of the pending route step
+  std::vector<uint32_t> hand_count;   // per layer: hand-overs inside an expert launch so far
   std::vector<int64_t> bytes_filled;
   uint32_t seq = 0;
   bool poll = false;
@@ -222,6 +223,7 @@ int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, 
   c->copy = static_cast<hipStream_t>(cfg->copy_stream);
   c->routed.assign(L, 0);
   c->route_seq.assign(L, 0);
+  c->hand_count.assign(L, 0);
   c->decided.assign(L, {});
   c->boundary.assign(L, BoundaryArgs{});
   c->bytes_filled.assign(L, 0);
@@ -446,6 +448,7 @@ int moe_stack_route_step(moe_cache_t *c, int32_t layer, float *h_dev, const floa
     b.out_dev = c->d_route + layer;
     b.note = c->h_note_dev + layer;
     b.handover = c->d_handover + 64 * (size_t)layer;
+    b.hand_tag = ++c->hand_count[layer] & 0xffffu;  // the words hold count - 1 (0 at first): never equal
     b.gave_up = c->h_gave_up_dev;
     b.spin_limit = c->tag_spins;
     b.next_gate_w = c->prefetch_gate ? c->gate_w[(layer + 1) % c->cfg.n_layers] : nullptr;

@@ -164,8 +164,8 @@ __device__ __forceinline__ CacheRegs load_cache_regs(const LayerState *st, int l
 
 // Where a layer-boundary step hands its decision to the other workgroups of the same launch (expert kernels that
 // run the boundary in their first workgroup): what they need - the K slots, the miss flags and the K weights - as
-// eight 8-byte words, each complete in itself: bits 0..15 = the low half of the step's tag, bits 16..63 = 48 bits
-// of payload
+// eight 8-byte words, each complete in itself: bits 0..15 = the tag of this hand-over (a per-layer count, so the
+// words' previous content never carries it), bits 16..63 = 48 bits of payload
 //     word 0: slots of positions 0..5 (8 bits each)      word 1: slots of positions 6, 7 | miss flags << 16
 //     words 2..7: the eight fp32 weights as one 256-bit string, 48 bits per word
 // A reader accepts the eight words only when all carry the tag it waits for, so no order between the stores is
@@ -174,6 +174,7 @@ __device__ __forceinline__ CacheRegs load_cache_regs(const LayerState *st, int l
 // serialise in the memory system).  handover = nullptr when nobody waits (separate router launch).
 struct BoundaryFlags {
   uint64_t *handover;
+  uint32_t tag;  // 16 bits
 };
 constexpr int kHandoverCopies = 8;
 static_assert(kHandoverCopies * 8 == kWave, "one lane per word of every copy");
@@ -181,7 +182,7 @@ static_assert(kHandoverCopies * 8 == kWave, "one lane per word of every copy");
 // Everything after the logits (Eq. 3 softmax, Eq. 10, Eq. 9, Eq. 2, Eq. 4, Sec. 4.2), run by one wavefront.
 __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_s, const CacheRegs &cr, LayerState *st,
                                            moe_route_out_t *out_dev, HostNote *note, uint32_t *rec_s, int lane,
-                                           BoundaryFlags flags = BoundaryFlags{nullptr}) {
+                                           BoundaryFlags flags = BoundaryFlags{nullptr, 0}) {
 #pragma clang fp contract(off)
   const int N = p.n_experts, K = p.top_k, C = p.capacity;
   int my_slot = cr.my_slot, slot_exp = cr.slot_exp;
@@ -351,7 +352,7 @@ __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_
       const uint64_t two = (uint64_t)rec_s[W_WEIGHT + i] | ((uint64_t)rec_s[W_WEIGHT + i + 1] << 32);
       payload = (two >> sh) & 0xffffffffffffull;
     }
-    __hip_atomic_store(flags.handover + lane, (payload << 16) | (uint64_t)(p.seq & 0xffffu), __ATOMIC_RELAXED,
+    __hip_atomic_store(flags.handover + lane, (payload << 16) | (uint64_t)(flags.tag & 0xffffu), __ATOMIC_RELAXED,
                        __HIP_MEMORY_SCOPE_AGENT);
   }
 
@@ -705,7 +706,7 @@ template <int NW, int CH, int PER>
 __device__ __forceinline__ void boundary_workgroup(const GemvParams &p, float *red) {
   const int tid = threadIdx.x, d = p.hidden;
   fused_boundary<NW, CH, PER, true>(p.b.route, p.b.glue, p.b.gate_w, p.b.state, p.b.out_dev, p.b.note,
-                                    BoundaryFlags{p.b.handover},
+                                    BoundaryFlags{p.b.handover, p.b.hand_tag},
                                     carve_boundary_lds(reinterpret_cast<uint32_t *>(red)));
   float *row = p.partial + (int64_t)p.row_offset * d;  // this workgroup's partial row: nothing to add
   for (int j = tid; j < d; j += NW * kWave) row[j] = 0.f;

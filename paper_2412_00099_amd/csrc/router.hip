@@ -51,7 +51,7 @@ __global__ __launch_bounds__(1024) void fused_route_kernel(RouteParams p, FusedP
                                                            LayerState *st, moe_route_out_t *out_dev,
                                                            HostNote *note) {
   __shared__ __attribute__((aligned(16))) uint32_t lds[kBoundaryLdsWords];
-  fused_boundary<16, CH, PER, PRE>(p, f, gate_w, st, out_dev, note, BoundaryFlags{nullptr},
+  fused_boundary<16, CH, PER, PRE>(p, f, gate_w, st, out_dev, note, BoundaryFlags{nullptr, 0},
                                    carve_boundary_lds(lds));
 }
 
