@@ -195,6 +195,9 @@ def main():
 
     import torch
 
+    import __graft_entry__
+
+    __graft_entry__.ensure_built()
     import paper_2412_00099_amd as pkg
     from synth import workloads
     from synth.workloads import CONFIGS
