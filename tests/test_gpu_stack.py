@@ -214,3 +214,39 @@ def test_bounded_wait_error_path_and_reset(monkeypatch):
     dec.reset()
     assert dec.tables(0).count == 0 and dec.stats(0).tokens == 0
     dec.close()
+
+
+def test_launch_timing_counts_and_strides():
+    """moe_cache_profile: events on every n-th first-pass expert launch; only launches that covered a whole layer
+    (no expert missing) are averaged."""
+    cfg = CONFIGS["c2_qwen_bf16"].with_(n_layers=2, hidden=512, n_experts=8, inter=64, shared_inter=128, capacity=8,
+                                        top_k=2, seed=5)
+    store, dec = build(cfg, lam=0.5)
+    T = 12
+    a = workloads.ar1_stream(cfg, T).to(DEV)
+    h = torch.zeros(cfg.hidden, device=DEV)
+    x = torch.zeros(cfg.hidden, dtype=cfg.act_dtype, device=DEV)
+    torch.cuda.synchronize()
+
+    def run():
+        for t in range(T):
+            for l in range(cfg.n_layers):
+                dec.stack_route_step(l, h, a[t, l], 1.0 if l == 0 else stack.PERTURB, x, carry=l > 0, wait=False)
+                dec.expert_forward(l, x, None)
+        dec.compute_stream.synchronize()
+
+    print("case launch timing: warm the cache (capacity = all experts)", flush=True)
+    run()
+    for stride, expect in ((1, T * cfg.n_layers), (5, -(-T * cfg.n_layers // 5))):
+        print(f"case launch timing: stride {stride}", flush=True)
+        misses_before = dec.stats().misses
+        dec.profile(stride, reset=True)
+        run()
+        avg_us, n = dec.profile(0, reset=True)
+        late_misses = dec.stats().misses - misses_before  # a launch with a (late cold) miss is timed but not counted
+        assert expect - late_misses <= n <= expect and (n == expect or late_misses > 0)
+        assert 0.5 < avg_us < 1000.0
+    dec.profile(0, reset=True)
+    run()
+    assert dec.profile(0, reset=True) == (0.0, 0)
+    dec.close()
