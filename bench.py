@@ -9,10 +9,15 @@ routes while the others stream the shared expert and then the selected experts; 
 link and a second expert launch.  All weights and inputs are resident (device slots / pinned host tier) before the
 timed region.
 
-Prints ONE JSON line.  `value` is tokens/s at the headline strength lambda = 0.5; `roofline` is that expert kernel
-(HIP events on the compute stream around every launch, in a second pass over the same tokens);
+Prints ONE JSON line.  `value` is tokens/s at the headline strength lambda = 0.5 over exactly --steps tokens after
+--warmup tokens from an empty cache.  With few tokens the cache is still filling (`headline_regime`: "cold_fill");
+`steady_state` always holds the same measurement at the workload's own length (64 + 960 tokens), and everything
+below refers to that run: `roofline` is its expert kernel (HIP start/stop events attached to every 5th first-pass
+launch on the compute stream, in a second pass over the same tokens, each behind a short hold of the stream);
 `boundary_as_separate_launch` times the same expert kernel as a launch of its own, with the routing in a launch
-before it; `cpu_baseline` is the CPU oracle on the first tokens of the same workload.
+before it; `lambda_sweep` / `top_j_2` vary the strength and the guaranteed top-J; `other_workloads` runs the other
+three stacks (expert kernel time, fraction of the HBM roofline, tok/s); `stream_ceiling_GBps` is what a plain
+elementwise kernel reaches on this device; `cpu_baseline` is the CPU oracle on the first tokens of the workload.
 """
 from __future__ import annotations
 
@@ -98,6 +103,9 @@ def decode_tokens(dec, a, h, x, y, t0, t1):
             dec.expert_forward(l, x, None)
 
 
+OWN_WARMUP = 64  # the workload's own length is split into 64 warm-up tokens and the rest
+
+
 def timed_run(dec, a, h, x, y, warmup, steps):
     import torch
 
@@ -118,7 +126,82 @@ def timed_run(dec, a, h, x, y, warmup, steps):
         cold_misses=s1.cold_misses, misses=s1.misses - s0.misses,
         host_link_bytes=s1.bytes_filled - s0.bytes_filled,
         mean_lifetime=(s1.lifetime_sum - s0.lifetime_sum) / max(s1.evictions - s0.evictions, 1),
+        evictions=s1.evictions, cold_misses_timed=s1.cold_misses - s0.cold_misses,
     )
+
+
+def stream_ceiling(dev, reps=6):
+    """GB/s of a plain elementwise kernel (int64 add over 32 Mi elements: reads 256 MiB, writes 256 MiB), the best
+    of a few launches timed with events: what HBM delivers to simple streaming code on this device.  The same
+    launches serve as the copy of known size that scales the byte counters of a rocprofv3 --pmc run."""
+    import torch
+
+    src = torch.arange(32 << 20, dtype=torch.int64, device=dev)
+    dst = torch.empty_like(src)
+    best = 0.0
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        torch.add(src, 1, out=dst)
+        e1.record()
+        torch.cuda.synchronize()
+        best = max(best, 2 * src.numel() * 8 / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    del src, dst
+    return best
+
+
+def kernel_time(dec, a, h, x, y, warmup, steps):
+    """Average duration of the whole-layer expert launches in a second pass over the same tokens."""
+    dec.profile(PROFILE_STRIDE, reset=True)
+    prof = timed_run(dec, a, h, x, y, warmup, steps)
+    us, n = dec.profile(0, reset=True)
+    return us, n, prof
+
+
+def other_workload(name, dev, n_tokens):
+    """One of the other stacks at full depth: tok/s and miss rate at the headline strength over n_tokens (64 of
+    them warm-up), then a miss-free pass (overwhelming prior) in which the expert kernel is timed."""
+    import torch
+
+    import paper_2412_00099_amd as pkg
+    from synth import workloads
+    from synth.workloads import CONFIGS
+
+    cfg = CONFIGS[name]
+    t0 = time.perf_counter()
+    store = pkg.ExpertStore(n_layers=cfg.n_layers, hidden=cfg.hidden, n_experts=cfg.n_experts, inter=cfg.inter,
+                            shared_inter=cfg.shared_inter, capacity=cfg.capacity, weight_fmt=cfg.weight_fmt,
+                            act_fmt=cfg.act_fmt, device=dev)
+    store.fill_from(cfg, workloads.expert_weights, workloads.shared_weights, workloads.gate_weight)
+    a = workloads.ar1_stream(cfg, n_tokens, device=dev)
+    dec = pkg.MoEDecoder(store, top_k=cfg.top_k, top_j=cfg.top_j, lam=HEADLINE_LAMBDA, renormalize=cfg.renormalize)
+    h = torch.zeros(cfg.hidden, dtype=torch.float32, device=dev)
+    x = torch.zeros(cfg.hidden, dtype=cfg.act_dtype, device=dev)
+    torch.cuda.synchronize()
+    log(f"{name}: setup {time.perf_counter() - t0:.1f} s")
+    steps = n_tokens - OWN_WARMUP
+    r = timed_run(dec, a, h, x, None, OWN_WARMUP, steps)
+    dec.set_lambda(1e6)
+    free = timed_run(dec, a, h, x, None, OWN_WARMUP, steps)
+    us, n, _ = kernel_time(dec, a, h, x, None, OWN_WARMUP, steps)
+    algo = cfg.top_k * store.blob_bytes + store.shared_bytes
+    gbs = algo / (us * 1e-6) / 1e9 if us > 0 else 0.0
+    out = dict(
+        workload=f"{cfg.name}: L={cfg.n_layers} d={cfg.hidden} N={cfg.n_experts} I={cfg.inter} shared_I={cfg.shared_inter} "
+                 f"top{cfg.top_k} cache={cfg.capacity}/{cfg.n_experts} {cfg.weight_fmt} tokens={n_tokens}",
+        tok_s=round(r["tok_s"], 2), miss_rate=round(r["miss_rate"], 5),
+        miss_free_tok_s=round(free["tok_s"], 2),
+        miss_free_per_layer_us=round(1e3 * free["ms_per_step"] / cfg.n_layers, 3),
+        expert_kernel_us=round(us, 3), launches=n, algorithmic_bytes_per_launch=algo,
+        GBps=round(gbs, 1), frac=round(gbs / HBM_PEAK_GBS, 4),
+        boundary_in_expert_launch=bool(dec.plan().boundary_in_expert_launch),
+    )
+    log(f"{name}: {out['tok_s']} tok/s (miss rate {out['miss_rate']}), miss-free {out['miss_free_tok_s']} tok/s, "
+        f"expert kernel {us:.2f} us = {gbs:.0f} GB/s")
+    dec.close()
+    del dec, store, a
+    torch.cuda.empty_cache()
+    return out
 
 
 def cpu_oracle_baseline(cfg, store_weights, a_cpu, n_tokens):
@@ -179,14 +262,16 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=960)
-    ap.add_argument("--warmup", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=OWN_WARMUP)
     ap.add_argument("--workload", default="c2_qwen_bf16")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debugging)")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-others", action="store_true", help="skip the other three workloads")
     ap.add_argument("--cpu-tokens", type=int, default=8)
     ap.add_argument("--no-calib-copy", action="store_true",
-                    help="skip the plain 256 MiB device copy that calibrates HBM byte counters under rocprofv3 --pmc")
+                    help="skip the plain elementwise kernel that gives the streaming ceiling and calibrates HBM byte "
+                         "counters under rocprofv3 --pmc")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: the batch-1 decode path runs on ONE GPU and has no multi-GPU part; run with --gpus 1.",
@@ -205,7 +290,8 @@ def main():
     cfg = CONFIGS[args.workload]
     if args.layers:
         cfg = cfg.with_(n_layers=args.layers)
-    T = args.warmup + args.steps
+    own_steps = cfg.n_tokens - OWN_WARMUP
+    T = max(args.warmup + args.steps, cfg.n_tokens)
     dev = "cuda:0"
     torch.cuda.set_device(0)
 
@@ -225,26 +311,27 @@ def main():
     y = torch.zeros(cfg.hidden, dtype=cfg.act_dtype, device=dev)
     torch.cuda.synchronize()
 
+    ceiling = None
     if not args.no_calib_copy:
-        # one plain copy of known size: its FETCH_SIZE / WRITE_SIZE readings scale the counters of the other kernels
-        # (an elementwise add kernel over 32 Mi int64: reads 256 MiB, writes 256 MiB; a same-dtype copy_ would be a DMA)
-        src = torch.arange(32 << 20, dtype=torch.int64, device=dev)
-        dst = torch.empty_like(src)
-        torch.add(src, 1, out=dst)
-        torch.cuda.synchronize()
-        del src, dst
+        ceiling = stream_ceiling(dev)
+        log(f"plain elementwise kernel: {ceiling:.0f} GB/s")
 
-    # ---- headline: lambda = 0.5 ---------------------------------------------------------------
+    # ---- headline: lambda = 0.5, exactly --steps tokens after --warmup tokens ---------------------
     head = timed_run(dec, a, h, x, y, args.warmup, args.steps)
-    log(f"lambda={HEADLINE_LAMBDA}: {head['tok_s']:.1f} tok/s, miss rate {head['miss_rate']:.4f}")
+    regime = "steady" if head["evictions"] > 0 else "cold_fill"
+    log(f"lambda={HEADLINE_LAMBDA}: {head['tok_s']:.1f} tok/s, miss rate {head['miss_rate']:.4f} ({regime})")
+    # ---- the same at the workload's own length ------------------------------------------------------
+    if (args.warmup, args.steps) == (OWN_WARMUP, own_steps):
+        steady = head
+    else:
+        steady = timed_run(dec, a, h, x, y, OWN_WARMUP, own_steps)
+        log(f"steady state ({OWN_WARMUP} + {own_steps} tokens): {steady['tok_s']:.1f} tok/s, "
+            f"miss rate {steady['miss_rate']:.4f}")
 
     # ---- expert-GEMV kernel time: events around every PROFILE_STRIDE-th launch, second pass over the same tokens
     # (events on every launch make the host the bottleneck: the device then idles between launches and the
     # kernel is no longer timed in the state the decode runs it in)
-    dec.profile(PROFILE_STRIDE, reset=True)
-    prof = timed_run(dec, a, h, x, y, args.warmup, args.steps)
-    gemv_us, gemv_launches = dec.profile(0, reset=True)
-    el = 2 if cfg.weight_fmt == "bf16" else 4
+    gemv_us, gemv_launches, prof = kernel_time(dec, a, h, x, y, OWN_WARMUP, own_steps)
     algo_bytes = cfg.top_k * store.blob_bytes + store.shared_bytes
     achieved = algo_bytes / (gemv_us * 1e-6) / 1e9 if gemv_us > 0 else 0.0
     log(f"expert GEMV: {gemv_us:.2f} us avg over {gemv_launches} launches -> {achieved:.0f} GB/s")
@@ -253,15 +340,16 @@ def main():
     if not args.no_sweep:
         for lam in (0.0, 0.25, 1.0):
             dec.set_lambda(lam)
-            r = timed_run(dec, a, h, x, y, args.warmup, args.steps)
+            r = timed_run(dec, a, h, x, y, OWN_WARMUP, own_steps)
             sweep[str(lam)] = dict(tok_s=round(r["tok_s"], 2), miss_rate=round(r["miss_rate"], 5),
                                    host_link_GB=round(r["host_link_bytes"] / 1e9, 3),
                                    mean_lifetime_tokens=round(r["mean_lifetime"], 2))
             log(f"lambda={lam}: {r['tok_s']:.1f} tok/s, miss rate {r['miss_rate']:.4f}")
         # miss-free run: with an overwhelming prior the cache freezes after warm-up (Sec. 3.3)
         dec.set_lambda(1e6)
-        r = timed_run(dec, a, h, x, y, args.warmup, args.steps)
-        sweep["miss_free"] = dict(tok_s=round(r["tok_s"], 2), miss_rate=round(r["miss_rate"], 5))
+        r = timed_run(dec, a, h, x, y, OWN_WARMUP, own_steps)
+        sweep["miss_free"] = dict(tok_s=round(r["tok_s"], 2), miss_rate=round(r["miss_rate"], 5),
+                                  per_layer_us=round(1e3 * r["ms_per_step"] / cfg.n_layers, 3))
         log(f"miss-free: {r['tok_s']:.1f} tok/s")
         dec.set_lambda(HEADLINE_LAMBDA)
 
@@ -272,10 +360,8 @@ def main():
         os.environ["MOE_FUSE_BOUNDARY"] = "0"
         dec2 = pkg.MoEDecoder(store, top_k=cfg.top_k, top_j=cfg.top_j, lam=HEADLINE_LAMBDA, renormalize=cfg.renormalize)
         del os.environ["MOE_FUSE_BOUNDARY"]
-        r2 = timed_run(dec2, a, h, x, y, args.warmup, args.steps)
-        dec2.profile(PROFILE_STRIDE, reset=True)
-        timed_run(dec2, a, h, x, y, args.warmup, args.steps)
-        us2, n2 = dec2.profile(0, reset=True)
+        r2 = timed_run(dec2, a, h, x, y, OWN_WARMUP, own_steps)
+        us2, n2, _ = kernel_time(dec2, a, h, x, y, OWN_WARMUP, own_steps)
         dec2.close()
         alone = dict(tok_s=round(r2["tok_s"], 2), expert_kernel_us=round(us2, 3), launches=n2,
                      GBps=round(algo_bytes / (us2 * 1e-6) / 1e9, 1) if us2 > 0 else 0.0,
@@ -286,7 +372,7 @@ def main():
     top_j_run = None
     if not args.no_sweep and cfg.top_k > 2:
         dec3 = pkg.MoEDecoder(store, top_k=cfg.top_k, top_j=2, lam=HEADLINE_LAMBDA, renormalize=cfg.renormalize)
-        r3 = timed_run(dec3, a, h, x, y, args.warmup, args.steps)
+        r3 = timed_run(dec3, a, h, x, y, OWN_WARMUP, own_steps)
         dec3.close()
         top_j_run = dict(top_j=2, tok_s=round(r3["tok_s"], 2), miss_rate=round(r3["miss_rate"], 5),
                          mean_lifetime_tokens=round(r3["mean_lifetime"], 2))
@@ -330,6 +416,19 @@ def main():
         except ImportError:
             pass
 
+    dec.close()
+    workload_desc = (f"{cfg.name}: L={cfg.n_layers} d={cfg.hidden} N={cfg.n_experts} I={cfg.inter} "
+                     f"shared_I={cfg.shared_inter} top{cfg.top_k} cache={cfg.capacity}/{cfg.n_experts} rho={cfg.rho}")
+    others = None
+    if not args.no_others and args.workload == "c2_qwen_bf16" and not args.layers:
+        del dec, store, a
+        torch.cuda.empty_cache()
+        others = {}
+        # full depth each; the token counts keep the whole bench within minutes (a miss of the Mixtral-shaped stack
+        # moves 176 MB over the host link)
+        for name, n_tok in (("c3_olmoe_bf16", 1024), ("c4_dsv2lite_int4", 1024), ("c5_mixtral_int8", 192)):
+            others[name] = other_workload(name, dev, n_tok)
+
     out = {
         "metric": "batch1_decode_tok_per_s",
         "value": round(head["tok_s"], 2),
@@ -344,17 +443,28 @@ def main():
         "dtype": "bf16" if cfg.weight_fmt == "bf16" else cfg.weight_fmt,
         "data": "synthetic",
         "config": {
-            "workload": f"{cfg.name}: L={cfg.n_layers} d={cfg.hidden} N={cfg.n_experts} I={cfg.inter} "
-                        f"shared_I={cfg.shared_inter} top{cfg.top_k} cache={cfg.capacity}/{cfg.n_experts} "
-                        f"T={T} rho={cfg.rho}",
+            "workload": f"{workload_desc} T={args.warmup + args.steps}",
             "lambda": HEADLINE_LAMBDA, "top_j": cfg.top_j, "seed": cfg.seed,
         },
+        "headline_regime": regime,
+        "headline_note": ("the cache was still filling during the timed tokens (no eviction yet): see steady_state"
+                          if regime == "cold_fill" else "cache full: steady-state decode"),
         "per_layer_us": round(1e3 * head["ms_per_step"] / cfg.n_layers, 3),
         "miss_rate": round(head["miss_rate"], 5),
         "miss_rate_incl_warmup": round(head["miss_rate_incl_warmup"], 5),
         "host_link_GB_filled": round(head["host_link_bytes"] / 1e9, 3),
         "host_link_GBps": round(link_gbs, 2),
         "mean_cache_lifetime_tokens": round(head["mean_lifetime"], 2),
+        "steady_state": {
+            "workload": f"{workload_desc} T={OWN_WARMUP + own_steps}", "warmup": OWN_WARMUP, "steps": own_steps,
+            "tok_s": round(steady["tok_s"], 2), "ms_per_step": round(steady["ms_per_step"], 4),
+            "per_layer_us": round(1e3 * steady["ms_per_step"] / cfg.n_layers, 3),
+            "miss_rate": round(steady["miss_rate"], 5), "misses": steady["misses"],
+            "cold_misses_in_timed_tokens": steady["cold_misses_timed"],
+            "miss_rate_incl_warmup": round(steady["miss_rate_incl_warmup"], 5), "cold_misses_total": steady["cold_misses"],
+            "mean_cache_lifetime_tokens": round(steady["mean_lifetime"], 2),
+            "expert_kernel_us": round(gemv_us, 3),
+        },
         "roofline": {
             "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": measured_traffic(cfg.name),
@@ -362,14 +472,16 @@ def main():
                       else "expert_gemv_kernel (layer boundary as a launch of its own)",
             "algorithmic_bytes_per_launch": algo_bytes,
             "avg_launch_us": round(gemv_us, 3), "launches": gemv_launches, "timed_every": PROFILE_STRIDE,
+            "measured_on": f"steady-state run, {OWN_WARMUP} + {own_steps} tokens",
             "tok_s_while_profiled": round(prof["tok_s"], 2),
         },
+        "stream_ceiling_GBps": round(ceiling, 1) if ceiling else None,
         "boundary_as_separate_launch": alone,
         "cpu_baseline": cpu,
         "lambda_sweep": sweep,
         "top_j_2": top_j_run,
+        "other_workloads": others,
     }
-    dec.close()
     print(json.dumps(out))
 
 

@@ -21,6 +21,13 @@
  *  - Streams are hipStream_t passed as void*; both are borrowed.  Calls on one context must come
  *    from one thread at a time.
  *  - Expert ids are 0..n_experts-1, slots 0..capacity-1.  n_experts <= 64, top_k <= 8.
+ *  - Environment variables read by moe_cache_init (all optional):
+ *      MOE_HOST_SYNC=event     the host waits for a routing decision on a stream event instead of polling the
+ *                              words the router stores into mapped host memory
+ *      MOE_FUSE_BOUNDARY=0|1   overrides the rule that decides whether a non-blocking moe_stack_route_step runs
+ *                              inside the layer's expert launch (see moe_cache_plan)
+ *      MOE_TAG_SPINS=n         polls before a workgroup stops waiting for the first workgroup of its own launch
+ *                              (a test lowers it to reach the error path described at moe_stack_route_step)
  */
 #ifndef MOE_CACHE_H
 #define MOE_CACHE_H
@@ -73,7 +80,7 @@ typedef struct moe_cache_config {
 
 typedef struct moe_cache_buffers {
   const void *const *host_expert_blob; /* [n_layers*n_experts] pinned host, packed blobs (moe_pack_expert) */
-  void *const *slot_pool;              /* [n_layers] device, capacity*moe_slot_bytes each, 256-byte aligned */
+  void *const *slot_pool;              /* [n_layers] device, capacity*moe_slot_bytes(cfg) each, 256-byte aligned */
   const void *const *gate_w;           /* [n_layers] device, router matrix [N,d] row-major, act_fmt */
   const void *const *shared_blob;      /* [n_layers] device packed blob of the shared expert, or NULL */
   const int32_t *initial_resident;     /* host [n_layers*n_initial] experts preloaded into slots 0.., or NULL */
@@ -92,9 +99,8 @@ typedef struct moe_route_out {
   float delta;                      /* Delta_avg used (Eq. 10) */
   float margin;                     /* gap between the K-th and (K+1)-th altered logit */
   float logits[MOE_MAX_EXPERTS];    /* z, as used */
-  uint32_t seq;                     /* internal completion tag */
-  uint32_t packed_slots[2];         /* internal: sel_slot, 8 bits each (read by the expert kernels) */
-  uint32_t miss_mask;               /* internal: bit k = miss[k] */
+  uint32_t opaque[4];               /* the library's own compact copy of the decision (read by its expert kernels);
+                                     * not part of the interface: do not interpret, do not rely on */
 } moe_route_out_t;
 
 typedef struct moe_cache_stats {
@@ -115,6 +121,10 @@ typedef struct moe_cache_tables {
 /* Bytes of one packed expert with intermediate size `inter` (0 on invalid arguments).  A slot and a
  * host blob are moe_blob_bytes(fmt, hidden, cfg.inter); the shared blob uses cfg.shared_inter. */
 size_t moe_blob_bytes(int32_t weight_fmt, int32_t hidden, int32_t inter);
+/* Bytes of one expert slot of the fast tier for this configuration (Sec. 2.2: the cache holds whole experts), so
+ * that the caller can size slot_pool (capacity * moe_slot_bytes per layer) and the host blobs.  Only weight_fmt,
+ * hidden and inter are read.  0 on NULL or an unsupported shape. */
+size_t moe_slot_bytes(const moe_cache_config_t *cfg);
 
 /* Pack one expert from canonical row-major weights into the blob layout the kernels stream
  * (record i = gate row i | up row i | column i of down).  All pointers are device memory:
@@ -173,7 +183,8 @@ int moe_stack_route_step(moe_cache_t *ctx, int32_t layer, float *h_dev, const fl
 int moe_cache_last_route(moe_cache_t *ctx, int32_t layer, moe_route_out_t *out_host);
 
 /* Counters of one layer, or summed over layers with layer = -1 (Eq. 4 numerators/denominators).
- * Synchronises compute_stream. */
+ * Synchronises compute_stream.  MOE_EHIP after an abandoned hand-over (see moe_stack_route_step), like every
+ * other call on a context in that state. */
 int moe_cache_stats(moe_cache_t *ctx, int32_t layer, moe_cache_stats_t *out_host);
 /* Slot table, stamps and Delta accumulator of one layer.  Synchronises compute_stream. */
 int moe_cache_tables(moe_cache_t *ctx, int32_t layer, moe_cache_tables_t *out_host);
@@ -187,11 +198,16 @@ int moe_cache_tables(moe_cache_t *ctx, int32_t layer, moe_cache_tables_t *out_ho
  * the layer or an expert output is pending. */
 int moe_cache_snapshot(moe_cache_t *ctx, int32_t layer, void *buf_host, size_t *bytes);
 int moe_cache_restore(moe_cache_t *ctx, int32_t layer, const void *buf_host, size_t bytes);
-/* Change lambda (and for the baselines M / p) between steps. */
+/* Change the strength lambda of the cache prior (Eq. 9: z' = z + lambda * Delta_avg * m~_t; Sec. 3.3 sweeps it as
+ * the knob between the original routing, lambda = 0, and fully cache-driven routing) from the next routing step on.
+ * Finite and >= 0, else MOE_EINVAL.  Does not touch the cache or Delta_avg. */
 int moe_cache_set_lambda(moe_cache_t *ctx, float lambda);
+/* Switch between the paper's method and its two list-based baselines (Sec. 3.1-3.2) and set M of Eq. 6 / p of Eq. 8. */
 int moe_cache_set_baseline(moe_cache_t *ctx, int32_t route_mode, int32_t max_rank, float cumsum_p);
-/* Empty every layer's cache (then preload the initial residents again), zero Delta_avg and counters; drops pending
- * steps and outputs and clears the error state described at moe_stack_route_step.  Synchronises both streams. */
+/* Start a new evaluation: empty every layer's cache (then preload the initial residents again, App. G), restart
+ * the running mean Delta_avg of Eq. 10 (sum and token count to zero) and the hit/miss counters of Eq. 4; drops
+ * pending steps and outputs and clears the error state described at moe_stack_route_step.  Synchronises both
+ * streams. */
 int moe_cache_reset(moe_cache_t *ctx);
 
 /* Workload glue for multi-layer synthetic stacks (not part of the paper's method):

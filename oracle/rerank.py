@@ -5,7 +5,11 @@ rest in their order.  Max-Rank (Eq. 6-7) promotes the cached experts found among
 the first M ranks, then the router's own top-J in front of those.
 Cumsum-Threshold (Eq. 8) picks M per token as the shortest prefix of the ranking
 whose softmax weights sum to at least p, then applies Max-Rank.  Pruning
-(Sec. 4.2) keeps only the ranks below h.
+(Sec. 4.2) discards the experts ranked h or worse.
+
+Parity unpinned: prune().  The paper prints no worked value for it, and its
+rank base is a reading (see prune): the tests pin only what follows from the
+definition itself (prefix of the ranking, h = K + 1 is the original routing).
 """
 from __future__ import annotations
 
@@ -45,5 +49,17 @@ def cumsum_threshold(ranking, weights, cache, p: float, top_j: int):
 
 
 def prune(ranking, top_k: int, h: int):
-    """Sec. 4.2 pruning baseline: of the top-K keep ranks below h (the miss rate stays normalised by K)."""
-    return list(ranking)[: min(top_k, h)]
+    """Sec. 4.2 pruning baseline: of the top-K, the experts ranked >= h are discarded, ranks counted from 1.
+
+    The paper restricts h to 1 < h <= K.  With ranks counted from 1 that range is exactly the useful one: h = 1
+    would discard every expert (hence 1 < h) and h = K still discards the last one, so h - 1 experts are kept.
+    (Counted from 0 the bound 1 < h would needlessly exclude "keep one expert", and h = K would prune nothing.)
+    h = K + 1 keeps all K: the original routing.  The miss rate stays normalised by K: see pruned_miss_rate.
+    """
+    assert h >= 2, "h = 1 would discard every expert"
+    return list(ranking)[: min(top_k, h - 1)]
+
+
+def pruned_miss_rate(misses: int, tokens: int, top_k: int) -> float:
+    """Sec. 4.2: the pruning baseline's miss rate is normalised by the original K, not by the experts kept."""
+    return misses / max(tokens * top_k, 1)

@@ -4,8 +4,7 @@ from __future__ import annotations
 import ctypes as C
 import os
 
-# MOE_CACHE_LIB selects another build of the same library (kernel tuning experiments)
-LIB_PATH = os.environ.get("MOE_CACHE_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmoe_cache.so")
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libmoe_cache.so")
 if not os.path.exists(LIB_PATH):
     raise ImportError(
         f"{LIB_PATH} is missing: build it with `python paper_2412_00099_amd/build.py` "
@@ -74,9 +73,7 @@ class moe_route_out_t(C.Structure):
         ("delta", C.c_float),
         ("margin", C.c_float),
         ("logits", C.c_float * MOE_MAX_EXPERTS),
-        ("seq", C.c_uint32),
-        ("packed_slots", C.c_uint32 * 2),
-        ("miss_mask", C.c_uint32),
+        ("opaque", C.c_uint32 * 4),
     ]
 
 
@@ -105,6 +102,8 @@ class moe_cache_tables_t(C.Structure):
 _vp = C.c_void_p
 lib.moe_blob_bytes.restype = C.c_size_t
 lib.moe_blob_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
+lib.moe_slot_bytes.restype = C.c_size_t
+lib.moe_slot_bytes.argtypes = [C.POINTER(moe_cache_config_t)]
 lib.moe_pack_expert.restype = C.c_int
 lib.moe_pack_expert.argtypes = [C.c_int32, C.c_int32, C.c_int32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.moe_cache_init.restype = C.c_int
@@ -146,7 +145,7 @@ lib.moe_last_error.restype = C.c_char_p
 lib.moe_last_error.argtypes = []
 
 EXPORTS = [
-    "moe_blob_bytes", "moe_pack_expert", "moe_cache_init", "moe_cache_destroy", "moe_route_step", "moe_stack_route_step",
+    "moe_blob_bytes", "moe_slot_bytes", "moe_pack_expert", "moe_cache_init", "moe_cache_destroy", "moe_route_step", "moe_stack_route_step",
     "moe_expert_forward", "moe_cache_last_route", "moe_cache_stats", "moe_cache_tables", "moe_cache_snapshot",
     "moe_cache_restore", "moe_trace_misses", "moe_cache_plan", "moe_cache_set_lambda",
     "moe_cache_set_baseline", "moe_cache_reset", "moe_residual_rmsnorm", "moe_cache_profile", "moe_last_error",
@@ -170,6 +169,10 @@ def moe_last_error() -> str:
 
 def moe_blob_bytes(weight_fmt: int, hidden: int, inter: int) -> int:
     return int(lib.moe_blob_bytes(weight_fmt, hidden, inter))
+
+
+def moe_slot_bytes(cfg: moe_cache_config_t) -> int:
+    return int(lib.moe_slot_bytes(C.byref(cfg)))
 
 
 def moe_pack_expert(weight_fmt, hidden, inter, gate, up, down, gate_s, up_s, down_s, blob_dev, stream) -> None:

@@ -106,10 +106,10 @@ hipError_t launch_route(const RouteParams &p, const void *gate_w, const void *x,
                         LayerState *state, moe_route_out_t *out_dev, HostNote *note_mapped,
                         hipStream_t s);
 // launch shape of the expert GEMV
+constexpr int kGemvWaves = 8;  // wavefronts per workgroup
+constexpr int kGemvDepth = 2;  // records in flight per wavefront (fp32 / bf16 kernels)
 struct GemvPlan {
-  int grid;   // workgroups (= fp32 partial rows written)
-  int waves;  // wavefronts per workgroup: 4 or 8
-  int depth;  // records in flight per wavefront: 2 or 3
+  int grid;   // workgroups (= fp32 partial rows written): one per compute unit
   bool dot2;  // packed bf16 dot products (bf16 weights and activations)
 };
 GemvPlan gemv_plan(int n_cus, int total_records, int weight_fmt, int act_fmt);

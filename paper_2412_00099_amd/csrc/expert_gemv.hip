@@ -12,8 +12,6 @@
 // Each wavefront keeps DEPTH records' loads in flight in a register ring.  The wavefronts' private outputs
 // are tree-reduced through LDS, each workgroup writes one fp32 partial row, and a second small kernel adds
 // the partial rows in a fixed order (deterministic result).
-#include <cstdlib>
-
 #include "common.h"
 #include "gemv_common.h"
 #include "route_device.h"
@@ -419,23 +417,16 @@ void launch_one(const GemvParams &p, int grid, hipStream_t s, hipEvent_t e0, hip
 
 template <int FMT, int LPR, bool DOT2>
 hipError_t launch_plan(const GemvParams &p, const GemvPlan &plan, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
-  const int key = plan.waves * 10 + plan.depth;
-  if (p.fused) {  // only the default launch shape has the variant with the boundary in workgroup 0
+  if (p.fused) {  // the variant with the boundary in workgroup 0 exists for packed bf16 arithmetic, d <= 2048
     if constexpr (LPR <= 4 && DOT2) {
-      if (key != 82 || plan.grid < 2) return hipErrorInvalidValue;
-      launch_one<FMT, LPR, 8, 2, DOT2, true>(p, plan.grid, s, e0, e1);
+      if (plan.grid < 2) return hipErrorInvalidValue;
+      launch_one<FMT, LPR, kGemvWaves, kGemvDepth, DOT2, true>(p, plan.grid, s, e0, e1);
       return hipGetLastError();
     } else {
       return hipErrorInvalidValue;
     }
   }
-  switch (key) {
-    case 42: launch_one<FMT, LPR, 4, 2, DOT2>(p, plan.grid, s, e0, e1); break;
-    case 43: launch_one<FMT, LPR, 4, 3, DOT2>(p, plan.grid, s, e0, e1); break;
-    case 82: launch_one<FMT, LPR, 8, 2, DOT2>(p, plan.grid, s, e0, e1); break;
-    case 161: launch_one<FMT, LPR, 16, 1, DOT2>(p, plan.grid, s, e0, e1); break;
-    default: return hipErrorInvalidValue;
-  }
+  launch_one<FMT, LPR, kGemvWaves, kGemvDepth, DOT2>(p, plan.grid, s, e0, e1);
   return hipGetLastError();
 }
 
@@ -478,29 +469,20 @@ bool gemv_inter_supported(int weight_fmt, int inter) {
 }
 
 // Launch shape: one workgroup of 8 wavefronts per compute unit, two records in flight per wavefront
-// (measured best on MI355X among 4/8/16 wavefronts and depths 1-3; the environment variables below
-// exist for such sweeps).
+// (measured best on MI355X among 4/8/16 wavefronts, depths 1-3 and 1-4 workgroups per compute unit).
 GemvPlan gemv_plan(int n_cus, int total_records, int weight_fmt, int act_fmt) {
   GemvPlan pl{};
   pl.grid = n_cus < total_records ? n_cus : total_records;
   if (pl.grid < 1) pl.grid = 1;
-  pl.waves = 8;
-  pl.depth = 2;
   pl.dot2 = weight_fmt == MOE_W_BF16 && act_fmt == MOE_A_BF16;
-  if (const char *s = getenv("MOE_GEMV_GRID")) if (atoi(s) > 0) pl.grid = atoi(s) < total_records ? atoi(s) : total_records;
-  if (const char *s = getenv("MOE_GEMV_WAVES")) if (atoi(s) == 4 || atoi(s) == 8 || atoi(s) == 16) pl.waves = atoi(s);
-  if (const char *s = getenv("MOE_GEMV_DEPTH")) if (atoi(s) == 2 || atoi(s) == 3) pl.depth = atoi(s);
-  if (const char *s = getenv("MOE_GEMV_DOT2")) pl.dot2 = pl.dot2 && atoi(s) != 0;
-  if (pl.waves == 8) pl.depth = 2;
-  if (pl.waves == 16) pl.depth = 1;
   return pl;
 }
 
 bool gemv_fused_supported(int weight_fmt, int act_fmt, int hidden, const GemvPlan &plan) {
   if (act_fmt != MOE_A_BF16 || plan.grid < 2 || hidden % 512 != 0) return false;
   switch (weight_fmt) {
-    case MOE_W_BF16:  // packed bf16 arithmetic, default launch shape, up to 4 loads per row per lane
-      return plan.dot2 && hidden / (kWave * 8) <= 4 && plan.waves == 8 && plan.depth == 2;
+    case MOE_W_BF16:  // packed bf16 arithmetic, up to 4 loads per row per lane
+      return plan.dot2 && hidden / (kWave * 8) <= 4;
     case MOE_W_INT8_PC:
     case MOE_W_INT4_G128: return hidden <= 4096;  // 8 wavefronts, at most 8 columns per thread of workgroup 0
     default: return false;

@@ -18,8 +18,6 @@
 //  consumed by mixed-precision FMAs; accumulators are unscaled within a group of 128 records and flushed with
 //  the group's per-column scales (and the constant (1024 + 8) * sum(h) removed) when the group or expert
 //  changes and at the end.
-#include <cstdlib>
-
 #include "common.h"
 #include "gemv_common.h"
 #include "route_device.h"

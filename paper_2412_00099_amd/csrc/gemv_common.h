@@ -84,7 +84,7 @@ struct RecordWalker {
     const u32x4 *rr = reinterpret_cast<const u32x4 *>(p.route);
     rw0 = ld128(rr + offsetof(moe_route_out_t, sel_weight) / 16);
     rw1 = ld128(rr + offsetof(moe_route_out_t, sel_weight) / 16 + 1);
-    rd = ld128(rr + offsetof(moe_route_out_t, seq) / 16);
+    rd = ld128(rr + offsetof(moe_route_out_t, opaque) / 16);
   }
 
   // FUSED: the decision as workgroup 0 of this launch hands it over - eight 8-byte words, each carrying the

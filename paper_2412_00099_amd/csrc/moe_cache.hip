@@ -77,7 +77,6 @@ struct moe_cache {
   uint32_t *h_gave_up = nullptr;    // pinned, mapped: set by a wavefront that stopped waiting for the hand-over
   uint32_t *h_gave_up_dev = nullptr;
   bool fuse_boundary = true;        // run deferred boundaries inside the expert launch (see moe_cache_init)
-  bool prefetch_gate = true;        // MOE_PREFETCH_GATE=0: workgroup 0 does not touch the next layer's gate matrix
   int tag_spins = 1 << 18;          // polls (about a tenth of a second) before a workgroup stops waiting for
                                     // workgroup 0; MOE_TAG_SPINS lowers it so that tests reach the error path
   int32_t *d_initial = nullptr;
@@ -145,6 +144,11 @@ size_t moe_blob_bytes(int32_t weight_fmt, int32_t hidden, int32_t inter) {
   if (!valid_wfmt(weight_fmt) || hidden <= 0 || inter <= 0) return 0;
   if (!gemv_shape_supported(weight_fmt, hidden) || !gemv_inter_supported(weight_fmt, inter)) return 0;
   return (size_t)blob_layout(weight_fmt, hidden, inter).total;
+}
+
+size_t moe_slot_bytes(const moe_cache_config_t *cfg) {
+  if (!cfg) return 0;
+  return moe_blob_bytes(cfg->weight_fmt, cfg->hidden, cfg->inter);
 }
 
 int moe_pack_expert(int32_t weight_fmt, int32_t hidden, int32_t inter, const void *gate, const void *up,
@@ -247,8 +251,8 @@ int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, 
   int cus = 0;
   HIP_INIT(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
   c->plan = gemv_plan(cus, cfg->top_k * cfg->inter + cfg->shared_inter, cfg->weight_fmt, cfg->act_fmt);
-  // the host learns a routing decision by polling the tag the kernel releases into mapped host memory;
-  // MOE_HOST_SYNC=event waits on a stream event instead
+  // the host learns a routing decision by polling the three self-tagged words the router stores into mapped host
+  // memory (each complete in itself, no ordering between them); MOE_HOST_SYNC=event waits on a stream event instead
   c->poll = true;
   if (const char *s = getenv("MOE_HOST_SYNC")) c->poll = strcmp(s, "event") != 0;
 
@@ -272,7 +276,6 @@ int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, 
   // MOE_FUSE_BOUNDARY=0 / 1 in the environment overrides the rule.
   c->fuse_boundary = 3 * (int64_t)cfg->shared_inter >= (int64_t)cfg->top_k * cfg->inter + cfg->shared_inter;
   if (const char *s = getenv("MOE_FUSE_BOUNDARY")) c->fuse_boundary = atoi(s) != 0;
-  if (const char *s = getenv("MOE_PREFETCH_GATE")) c->prefetch_gate = atoi(s) != 0;
   if (const char *s = getenv("MOE_TAG_SPINS")) if (atoi(s) > 0) c->tag_spins = atoi(s);
   HIP_INIT(hipMalloc(&c->d_initial, sizeof(int32_t) * (size_t)L * (b->n_initial > 0 ? b->n_initial : 1)));
   HIP_INIT(hipMalloc(&c->d_partial, sizeof(float) * 2 * (size_t)c->plan.grid * cfg->hidden));
@@ -451,7 +454,7 @@ int moe_stack_route_step(moe_cache_t *c, int32_t layer, float *h_dev, const floa
     b.hand_tag = ++c->hand_count[layer] & 0xffffu;  // the words hold count - 1 (0 at first): never equal
     b.gave_up = c->h_gave_up_dev;
     b.spin_limit = c->tag_spins;
-    b.next_gate_w = c->prefetch_gate ? c->gate_w[(layer + 1) % c->cfg.n_layers] : nullptr;
+    b.next_gate_w = c->gate_w[(layer + 1) % c->cfg.n_layers];
     b.next_state = c->d_state + (layer + 1) % c->cfg.n_layers;
     b.gate_bytes = (int64_t)c->cfg.n_experts * c->cfg.hidden * (c->cfg.act_fmt == MOE_A_BF16 ? 2 : 4);
     c->route_seq[layer] = p.seq;
@@ -548,8 +551,7 @@ int moe_cache_last_route(moe_cache_t *c, int32_t layer, moe_route_out_t *out) {
 
 int moe_cache_stats(moe_cache_t *c, int32_t layer, moe_cache_stats_t *out) {
   if (!c || !out) return fail(MOE_EINVAL, "NULL argument");
-  if (layer != -1)
-    if (int rc = check_layer(c, layer)) return rc;
+  if (int rc = check_layer(c, layer == -1 ? 0 : layer)) return rc;  // also refuses a context whose hand-over was abandoned
   HIP_TRY(hipStreamSynchronize(c->compute));
   std::vector<LayerState> st(c->cfg.n_layers);
   HIP_TRY(hipMemcpy(st.data(), c->d_state, sizeof(LayerState) * st.size(), hipMemcpyDeviceToHost));
@@ -681,8 +683,8 @@ int moe_residual_rmsnorm(float *h_dev, const void *y_dev, const float *a_dev, fl
 int moe_cache_plan(moe_cache_t *c, moe_cache_plan_t *out) {
   if (!c || !out) return fail(MOE_EINVAL, "NULL argument");
   out->grid = c->plan.grid;
-  out->wavefronts = c->plan.waves;
-  out->depth = c->plan.depth;
+  out->wavefronts = kGemvWaves;
+  out->depth = kGemvDepth;
   out->packed_bf16_dot = c->plan.dot2;
   out->boundary_in_expert_launch = c->fuse_boundary && c->cfg.hidden % 64 == 0 && c->cfg.hidden <= kFusedMaxHidden &&
                                    gemv_fused_supported(c->cfg.weight_fmt, c->cfg.act_fmt, c->cfg.hidden, c->plan);

@@ -23,7 +23,7 @@ static_assert(sizeof(moe_route_out_t) % 16 == 0, "route record is copied in 16-b
 // word offsets inside moe_route_out_t
 constexpr int W_EXPERT = 0, W_SLOT = 8, W_WEIGHT = 16, W_MISS = 24, W_EVICT = 32, W_NMISS = 40, W_TOKEN = 41,
               W_DELTA = 42, W_MARGIN = 43, W_LOGITS = 44, W_SEQ = 44 + MOE_MAX_EXPERTS;
-static_assert(W_SEQ * 4 == offsetof(moe_route_out_t, seq), "record layout");
+static_assert(W_SEQ * 4 == offsetof(moe_route_out_t, opaque), "record layout");
 static_assert(W_LOGITS * 4 == offsetof(moe_route_out_t, logits), "record layout");
 
 __device__ __forceinline__ uint64_t ballot(bool p) { return __builtin_amdgcn_ballot_w64(p); }

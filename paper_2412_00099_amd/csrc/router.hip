@@ -10,8 +10,9 @@
 // wavefront 0 then does the routing with lane e <-> expert e and lane s <-> slot s (N <= 64, C <= 64),
 // entirely in registers.  Rankings are counted with one 64-bit compare per pair: the key is the logit
 // mapped to an order-preserving unsigned integer, with 63 - lane below it so that equal logits rank the
-// lower index first.  The decision record is assembled in LDS and written with 16-byte stores to device
-// memory and to host-mapped memory, followed by a release of the completion tag.
+// lower index first.  What the host needs (experts, slots, miss flags) goes to host-mapped memory as three
+// self-tagged 8-byte words, each complete in itself, as soon as the victims are known; the full decision record is
+// assembled in LDS and written with 16-byte stores to device memory.
 #include "route_device.h"
 
 namespace moe {

@@ -52,6 +52,24 @@ def test_blob_bytes(B):
     assert B.moe_blob_bytes(7, 2048, 64) == 0
 
 
+def test_slot_bytes_follows_the_config(B):
+    cfg = B.moe_cache_config_t()
+    cfg.weight_fmt, cfg.hidden, cfg.inter, cfg.shared_inter = B.MOE_W_BF16, 2048, 1408, 5632
+    assert B.moe_slot_bytes(cfg) == B.moe_blob_bytes(B.MOE_W_BF16, 2048, 1408) == 17301504
+    cfg.weight_fmt = B.MOE_W_INT4_G128
+    assert B.moe_slot_bytes(cfg) == B.moe_blob_bytes(B.MOE_W_INT4_G128, 2048, 1408)
+    cfg.hidden = 100
+    assert B.moe_slot_bytes(cfg) == 0
+    assert B.lib.moe_slot_bytes(None) == 0
+
+
+def test_route_record_layout(B):
+    # the public part ends with the logits; the trailing 16 bytes belong to the library
+    f = dict((n, getattr(B.moe_route_out_t, n)) for n, _ in B.moe_route_out_t._fields_)
+    assert f["logits"].offset == 4 * 44 and f["opaque"].offset == 4 * (44 + 64) and f["opaque"].size == 16
+    assert [n for n, _ in B.moe_route_out_t._fields_][-1] == "opaque"
+
+
 def _cfg(B, **kw):
     c = B.moe_cache_config_t()
     c.n_layers, c.hidden, c.n_experts, c.inter, c.shared_inter = 1, 256, 16, 512, 0

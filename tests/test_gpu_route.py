@@ -362,3 +362,42 @@ def test_c1_free_run_routing_and_outputs(lam):
 def test_c1_free_run_deferred_decision(lam):
     print(f"case c1 deferred lam={lam}", flush=True)
     free_run(CONFIGS["c1_single_fp32"], lam, 128, deferred=True)
+
+
+@pytest.mark.parametrize("h", [2, 3, 4, 5])
+def test_pruning_baseline_on_device(h):
+    """Pruning baseline (Sec. 4.2): of the router's top-K the experts ranked >= h (ranks from 1) are discarded; on
+    the device that is the original routing (lambda = 0) with h - 1 experts per token.  Selections, slots, misses and
+    evictions against oracle.rerank.prune fed through the oracle cache; the miss rate is normalised by the
+    original K on both sides."""
+    from oracle import rerank
+
+    K = 4
+    cfg = TINY.with_(n_experts=60, top_k=min(K, h - 1), capacity=30, n_layers=1, seed=313)
+    print(f"case pruning h={h} (keeps {cfg.top_k} of {K})", flush=True)
+    store, dec = build(cfg, lam=0.0)
+    N, C, T = cfg.n_experts, cfg.capacity, 300
+    cache = routing.ExpertCache(N, C)
+    x = torch.zeros(cfg.hidden, dtype=cfg.act_dtype, device=DEV)
+    y = torch.zeros(cfg.hidden, dtype=cfg.act_dtype, device=DEV)
+    zs = workloads.logits_stream(cfg, T, layer=0, scale=1.5)
+    zs_dev = zs.to(DEV)
+    torch.cuda.synchronize()
+    for t in range(T):
+        out = route_fields(dec.route_step(0, logits=zs_dev[t]), cfg.top_k)
+        dec.expert_forward(0, x, y)
+        z = zs[t].numpy()
+        kept = rerank.prune(routing.ranking(z).tolist(), K, h)
+        miss, slot, evicted = cache.access(kept, z)
+        assert out["sel"] == kept and out["slot"] == slot and out["miss"] == miss and out["evicted"] == evicted, t
+        np.testing.assert_allclose(out["weight"], routing.softmax(z)[kept], rtol=2e-6)
+    st = dec.stats(0)
+    assert (st.misses, st.evictions, st.lifetime_sum) == (cache.stats.misses, cache.stats.evictions,
+                                                          cache.stats.lifetime_sum)
+    assert rerank.pruned_miss_rate(st.misses, T, K) == rerank.pruned_miss_rate(cache.stats.misses, T, K) <= (h - 1) / K
+    if h == K + 1:  # nothing pruned: the original routing with plain LRU
+        ref = routing.CachePriorRouter(N, K, C, 0.0)
+        for z in zs.numpy():
+            ref.step(z)
+        assert ref.stats.misses == st.misses
+    dec.close()

@@ -2,6 +2,7 @@
 import math
 
 import numpy as np
+import pytest
 import torch
 
 from oracle import experts, rerank, stack
@@ -115,7 +116,40 @@ def test_cumsum_rank():
     assert rerank.cumsum_rank([0.25] * 4, 0.7) > rerank.cumsum_rank([0.9, 0.05, 0.03, 0.02], 0.7)
     r = rerank.cumsum_threshold([0, 1, 2, 3], dict(enumerate(w)), {2, 3}, 0.85, 1)
     assert r == [0, 2, 1, 3]
-    assert rerank.prune([4, 2, 7, 1], 3, 2) == [4, 2]
+
+
+def test_prune_structure():
+    """Pruning baseline (Sec. 4.2): no value is printed in the paper (parity unpinned); what the definition itself
+    fixes is pinned here - a prefix of the ranking, ranks counted from 1 so that h = 2 keeps one expert and h = K
+    still drops the last, h = K + 1 is the original routing, and the miss rate is normalised by K."""
+    r = [4, 2, 7, 1, 0]
+    K = 3
+    assert rerank.prune(r, K, 2) == [4]
+    assert rerank.prune(r, K, 3) == [4, 2]
+    assert rerank.prune(r, K, K + 1) == r[:K] == rerank.prune(r, K, 9)
+    for h in range(2, K + 2):
+        kept = rerank.prune(r, K, h)
+        assert kept == r[: len(kept)] and len(kept) == min(K, h - 1)
+    with pytest.raises(AssertionError):
+        rerank.prune(r, K, 1)
+    assert rerank.pruned_miss_rate(6, 4, 3) == 0.5  # 6 misses over 4 tokens of K = 3, whatever was kept
+
+
+def test_pruned_miss_rate_bounds():
+    """A pruned token touches at most h - 1 experts, so its miss rate normalised by K is at most (h - 1) / K; with
+    h = K + 1 the pruned run is the original routing, miss for miss."""
+    from oracle import eviction
+
+    rng = np.random.default_rng(11)
+    N, K, C, T = 12, 4, 6, 300
+    z = np.cumsum(rng.normal(size=(T, N)), axis=0) * 0.3 + rng.normal(size=(T, N))
+    ranks = [np.argsort(-row, kind="stable").tolist() for row in z]
+    full, _ = eviction.lru_list_misses([r[:K] for r in ranks], C)
+    for h in range(2, K + 2):
+        m, _ = eviction.lru_list_misses([rerank.prune(r, K, h) for r in ranks], C)
+        assert rerank.pruned_miss_rate(m, T, K) <= (h - 1) / K
+        if h == K + 1:
+            assert m == full
 
 
 def test_stack_glue():
