@@ -158,6 +158,18 @@ def kernel_time(dec, a, h, x, y, warmup, steps):
     return us, n, prof
 
 
+def release_memory():
+    """Give device and pinned host memory of a finished workload back (both are cached by PyTorch's allocators)."""
+    import gc
+
+    import torch
+
+    gc.collect()
+    torch.cuda.empty_cache()
+    if hasattr(torch._C, "_host_emptyCache"):
+        torch._C._host_emptyCache()
+
+
 def other_workload(name, dev, n_tokens):
     """One of the other stacks at full depth: tok/s and miss rate at the headline strength over n_tokens (64 of
     them warm-up), then a miss-free pass (overwhelming prior) in which the expert kernel is timed."""
@@ -200,7 +212,7 @@ def other_workload(name, dev, n_tokens):
         f"expert kernel {us:.2f} us = {gbs:.0f} GB/s")
     dec.close()
     del dec, store, a
-    torch.cuda.empty_cache()
+    release_memory()
     return out
 
 
@@ -422,7 +434,7 @@ def main():
     others = None
     if not args.no_others and args.workload == "c2_qwen_bf16" and not args.layers:
         del dec, store, a
-        torch.cuda.empty_cache()
+        release_memory()
         others = {}
         # full depth each; the token counts keep the whole bench within minutes (a miss of the Mixtral-shaped stack
         # moves 176 MB over the host link)

@@ -161,6 +161,24 @@ int moe_route_step(moe_cache_t *ctx, int32_t layer, const void *x_dev, const flo
  * moe_stack_route_step (of any layer), which must follow before another moe_expert_forward. */
 int moe_expert_forward(moe_cache_t *ctx, int32_t layer, const void *x_dev, void *y_dev);
 
+/* moe_expert_forward for callers that cannot allocate device memory or hold a context: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid allocation.  Computes y = sum_k w_k E_k(x) + shared(x) for experts that are
+ * all in their slots, with the kernels moe_expert_forward uses.  The call allocates nothing (no hipMalloc / hipFree, no
+ * memset): the routing record its kernels read and their fp32 partial rows live in a fixed 4 MiB + 512 B device array
+ * inside the library, one per GPU, held until the process ends.  Hence the limits: hidden <= 4096, at most 256
+ * workgroups; larger shapes are refused with MOE_EINVAL.  Every call on a GPU shares that GPU's array: calls that
+ * overlap in time on one GPU (different streams, different threads) race; calls on one stream are ordered.
+ *   slot_pool_dev   device, n_slots slots of moe_blob_bytes(weight_fmt, hidden, inter) each, 256-byte aligned
+ *   shared_blob_dev device packed shared expert (shared_inter > 0) or NULL
+ *   sel_slot_host, sel_weight_host   HOST arrays [top_k]: the slot of each selected expert and its weight (read
+ *                   before the call returns; slots are checked against n_slots)
+ *   x_dev, y_dev    device [hidden] in act_fmt; y is complete when `stream` reaches the end of the three kernels
+ *                   this call enqueues.  The device of `stream` must be current. */
+int moe_expert_forward_static(int32_t weight_fmt, int32_t act_fmt, int32_t hidden, int32_t inter, int32_t shared_inter,
+                              int32_t top_k, const void *slot_pool_dev, int32_t n_slots, const void *shared_blob_dev,
+                              const int32_t *sel_slot_host, const float *sel_weight_host, const void *x_dev,
+                              void *y_dev, void *stream);
+
 /* Layer boundary of a multi-layer stack (workload glue fused with the router kernel: Eq. 3, 9, 10, 4, Sec. 4.2):
  *   y  = the expert output left pending by moe_expert_forward(..., y_dev = NULL), if any
  *   h  = carry ? h + y + perturb * a : perturb * a  (a may be NULL; carry = 0 starts a new token)

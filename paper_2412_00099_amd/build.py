@@ -32,6 +32,7 @@ SOURCES = {
     "pack.hip": [],
     "moe_cache.hip": [],
     "trace_sim.hip": [],
+    "expert_static.hip": [],
 }
 
 

@@ -132,6 +132,14 @@ hipError_t launch_residual_rmsnorm(float *h, const void *y, const float *a, floa
                                    int hidden, int act_fmt, hipStream_t s);
 hipError_t launch_state_init(LayerState *state, int n_layers, const int32_t *initial_dev, int n_initial,
                              hipStream_t s);
+// the allocation-free entry point (expert_static.hip): device address of its fixed scratch array and the compute-unit
+// count of device `dev` (which must be current), looked up once per device
+hipError_t static_scratch_setup(int dev, void **ptr, int *cus);
+hipError_t launch_expert_forward_static(int weight_fmt, int act_fmt, int hidden, int inter, int shared_inter, int top_k,
+                                        const void *slot_pool, int64_t slot_bytes, const void *shared_blob,
+                                        const int32_t *sel_slot, const float *sel_weight, const void *x, void *y,
+                                        hipStream_t s);
+int static_max_hidden();
 bool gemv_shape_supported(int weight_fmt, int hidden);
 bool gemv_inter_supported(int weight_fmt, int inter);
 hipError_t launch_expert_gemv_quant(const GemvParams &p, int weight_fmt, const GemvPlan &plan, hipStream_t s,

@@ -250,6 +250,7 @@ int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, 
   HIP_INIT(hipGetDevice(&dev));
   int cus = 0;
   HIP_INIT(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  HIP_INIT(static_scratch_setup(dev, nullptr, nullptr));  // moe_expert_forward_static's scratch array on this device
   c->plan = gemv_plan(cus, cfg->top_k * cfg->inter + cfg->shared_inter, cfg->weight_fmt, cfg->act_fmt);
   // the host learns a routing decision by polling the three self-tagged words the router stores into mapped host
   // memory (each complete in itself, no ordering between them); MOE_HOST_SYNC=event waits on a stream event instead
@@ -539,6 +540,32 @@ int moe_expert_forward(moe_cache_t *c, int32_t layer, const void *x_dev, void *y
   else
     c->pending_rows = rows;  // finished by the next moe_stack_route_step
   c->routed[layer] = 0;
+  return MOE_OK;
+}
+
+int moe_expert_forward_static(int32_t weight_fmt, int32_t act_fmt, int32_t hidden, int32_t inter, int32_t shared_inter,
+                              int32_t top_k, const void *slot_pool_dev, int32_t n_slots, const void *shared_blob_dev,
+                              const int32_t *sel_slot_host, const float *sel_weight_host, const void *x_dev,
+                              void *y_dev, void *stream) {
+  if (!valid_wfmt(weight_fmt) || !valid_afmt(act_fmt)) return fail(MOE_EINVAL, "unknown weight or activation format");
+  if (hidden <= 0 || hidden > static_max_hidden())
+    return fail(MOE_EINVAL, "hidden=%d beyond the fixed scratch buffer of this entry point (at most %d)", hidden, static_max_hidden());
+  if (!gemv_shape_supported(weight_fmt, hidden)) return fail(MOE_EINVAL, "hidden=%d unsupported for weight format %d", hidden, weight_fmt);
+  if (inter <= 0 || shared_inter < 0 || !gemv_inter_supported(weight_fmt, inter) ||
+      (shared_inter > 0 && !gemv_inter_supported(weight_fmt, shared_inter)))
+    return fail(MOE_EINVAL, "intermediate size unsupported for this weight format");
+  if (top_k <= 0 || top_k > MOE_MAX_TOPK) return fail(MOE_EINVAL, "top_k must be in 1..%d", MOE_MAX_TOPK);
+  if (n_slots <= 0 || n_slots > 256) return fail(MOE_EINVAL, "n_slots must be in 1..256");
+  if (!slot_pool_dev || !sel_slot_host || !sel_weight_host || !x_dev || !y_dev) return fail(MOE_EINVAL, "NULL argument");
+  if (shared_inter > 0 && !shared_blob_dev) return fail(MOE_EINVAL, "shared_inter > 0 needs shared_blob_dev");
+  for (int k = 0; k < top_k; ++k) {
+    if (sel_slot_host[k] < 0 || sel_slot_host[k] >= n_slots) return fail(MOE_EINVAL, "sel_slot[%d]=%d outside 0..%d", k, sel_slot_host[k], n_slots - 1);
+    if (!std::isfinite(sel_weight_host[k])) return fail(MOE_EINVAL, "sel_weight[%d] is not finite", k);
+  }
+  const int64_t slot_bytes = blob_layout(weight_fmt, hidden, inter).total;
+  HIP_TRY(launch_expert_forward_static(weight_fmt, act_fmt, hidden, inter, shared_inter, top_k, slot_pool_dev, slot_bytes,
+                                       shared_blob_dev, sel_slot_host, sel_weight_host, x_dev, y_dev,
+                                       static_cast<hipStream_t>(stream)));
   return MOE_OK;
 }
 
