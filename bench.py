@@ -277,6 +277,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=OWN_WARMUP)
     ap.add_argument("--workload", default="c2_qwen_bf16")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debugging)")
+    ap.add_argument("--tokens", type=int, default=0,
+                    help="override the workload's own length (64 warm-up tokens + the rest); short runs under a profiler")
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the other three workloads")
@@ -302,6 +304,10 @@ def main():
     cfg = CONFIGS[args.workload]
     if args.layers:
         cfg = cfg.with_(n_layers=args.layers)
+    if args.tokens:
+        if args.tokens <= OWN_WARMUP:
+            ap.error(f"--tokens must exceed the {OWN_WARMUP} warm-up tokens")
+        cfg = cfg.with_(n_tokens=args.tokens)
     own_steps = cfg.n_tokens - OWN_WARMUP
     T = max(args.warmup + args.steps, cfg.n_tokens)
     dev = "cuda:0"
@@ -432,7 +438,7 @@ def main():
     workload_desc = (f"{cfg.name}: L={cfg.n_layers} d={cfg.hidden} N={cfg.n_experts} I={cfg.inter} "
                      f"shared_I={cfg.shared_inter} top{cfg.top_k} cache={cfg.capacity}/{cfg.n_experts} rho={cfg.rho}")
     others = None
-    if not args.no_others and args.workload == "c2_qwen_bf16" and not args.layers:
+    if not args.no_others and args.workload == "c2_qwen_bf16" and not args.layers and not args.tokens:
         del dec, store, a
         release_memory()
         others = {}

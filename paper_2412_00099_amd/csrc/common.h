@@ -90,6 +90,9 @@ struct BlobLayout {
   int64_t total;        // whole blob, multiple of 256
 };
 BlobLayout blob_layout(int fmt, int hidden, int inter);
+// int4: bytes of one record - three rows of nibbles and the record's (gate, up) fp16 scale pairs, one pair per group of
+// 128 columns, padded so that every record starts on a 128-byte line (a wavefront's 1 KB load then covers 8 lines, not 9)
+__host__ __device__ constexpr int64_t int4_record_bytes(int64_t d) { return 3 * (d / 2) + ((d / 128) * 4 + 127) / 128 * 128; }
 
 // What the host needs of a routing decision, written by the router into mapped host memory as three 8-byte words,
 // each complete in itself (no ordering between them is assumed):

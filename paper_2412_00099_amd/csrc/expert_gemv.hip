@@ -474,6 +474,7 @@ GemvPlan gemv_plan(int n_cus, int total_records, int weight_fmt, int act_fmt) {
   GemvPlan pl{};
   pl.grid = n_cus < total_records ? n_cus : total_records;
   if (pl.grid < 1) pl.grid = 1;
+  if (pl.grid > 1024) pl.grid = 1024;  // (the record split multiplies workgroup index and record count in 32 bits)
   pl.dot2 = weight_fmt == MOE_W_BF16 && act_fmt == MOE_A_BF16;
   return pl;
 }

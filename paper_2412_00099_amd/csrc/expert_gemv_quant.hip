@@ -297,6 +297,21 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int8_kernel(GemvParams 
 // =================================================================================================
 // int4, group 128
 // =================================================================================================
+// A dword holds the nibbles n0..n7 of eight consecutive columns.  Four masked copies of it are four fp16 pairs:
+//     (w      & 0x000f000f) | 0x64006400  =  (1024 +      n0, 1024 +      n4)
+//     (w      & 0x00f000f0) | 0x64006400  =  (1024 + 16 * n1, 1024 + 16 * n5)
+//     (w >> 8 & 0x000f000f) | 0x64006400  =  (1024 +      n2, 1024 +      n6)
+//     (w >> 8 & 0x00f000f0) | 0x64006400  =  (1024 + 16 * n3, 1024 + 16 * n7)
+// one shift and four and-or operations per eight weights.  The factor 16 of the odd columns is undone in the other
+// operand: the activations of odd columns are stored divided by 16 (gate / up rows), the down scales of odd columns
+// are divided by 16 when the accumulators are flushed.  The constants (1024 and the zero point 8) are removed through
+// sums of the activations (per lane and chunk, once) and of h (per group).
+constexpr uint32_t kNibMaskLo = 0x000f000fu, kNibMaskHi = 0x00f000f0u, kF16Bias = 0x64006400u;
+
+// (w & mask) | bias as one operation: mask and bias are handed over as register values so that the three-operand
+// form is chosen (it takes no literal constants)
+__device__ __forceinline__ uint32_t and_or(uint32_t w, uint32_t mask, uint32_t bias) { return (w & mask) | bias; }
+
 template <int LPR>
 struct RecI4 {
   u32x4 g[LPR], u[LPR], dn[LPR];
@@ -320,8 +335,8 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int4_kernel(GemvParams 
     }
   }
   const int64_t row16 = d / VEC;                             // 16-byte chunks per row of nibbles
-  const int64_t rec_bytes = 3 * row16 * 16 + (d / 128) * 4;  // three rows + (gate, up) scale pairs
-  RecordWalker<NW, FUSED> walk;
+  const int64_t rec_bytes = int4_record_bytes(d);            // three rows + (gate, up) scale pairs, padded
+  RecordWalker<NW, FUSED, 1> walk;  // a contiguous block of records per wavefront: few changes of scale group
   walk.init(p, wave);
 
   auto issue = [&](RecI4<LPR> &R) {
@@ -357,45 +372,31 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int4_kernel(GemvParams 
     for (int c = 0; c < LPR; ++c) fetch_x<VEC>(p.x, p.act_fmt, (c * kWave + lane) * VEC, xraw[c]);
   }
 
+  // Pass 0 loads every list entry of the wavefront, also the rare ones whose expert is only being filled (their
+  // arithmetic is skipped), so that the steady-state loop issues its loads unconditionally and each use waits for
+  // the oldest record only.  Pass 1 (the experts just filled) skips the other records without loading them.
+  const bool all = p.pass == 0;
+  int todo = all ? walk.remaining() : 0;
   RecI4<LPR> ring[DEPTH];
-  bool live[DEPTH];
-#pragma unroll
-  for (int j = 0; j < DEPTH; ++j) {
-    live[j] = walk.next(p);
-    if (live[j]) issue(ring[j]);
-  }
-
-  // activations as packed bf16 pairs (column t, column t+4) per dword of 8 nibbles, and per-chunk sums
-  uint32_t xp[CPL / 2];
-  float xoff[LPR];
-  float x_scale = 0.f;
-  if constexpr (FUSED) x_scale = 1.0f / sqrtf(blocks.total() / (float)d + 1e-6f);
-#pragma unroll
-  for (int c = 0; c < LPR; ++c) {
-    float xf[VEC];
-    if constexpr (FUSED) x_from_h<VEC>(hraw[c], x_scale, p.act_fmt, xf);
-    else unpack_x<VEC>(xraw[c], p.act_fmt, xf);
-    float s = 0.f;
-#pragma unroll
-    for (int w = 0; w < 4; ++w)
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const float a = xf[w * 8 + t], b = xf[w * 8 + t + 4];
-        const uint32_t pa = f32_to_bf16_rne(a), pb = f32_to_bf16_rne(b);
-        xp[c * 16 + w * 4 + t] = pa | (pb << 16);
-        s += __uint_as_float(pa << 16) + __uint_as_float(pb << 16);
+  bool live[DEPTH], want[DEPTH];
+  auto advance = [&](int j) {
+    if (all) {
+      live[j] = todo > 0;
+      if (live[j]) {
+        --todo;
+        want[j] = walk.step(p);
       }
-    xoff[c] = -(128.f + 8.f) * s;
-  }
-
-  float y[CPL], acc[CPL];
+    } else {
+      live[j] = walk.next(p);
+      want[j] = true;
+    }
+    if (live[j]) issue(ring[j]);
+  };
 #pragma unroll
-  for (int j = 0; j < CPL; ++j) y[j] = acc[j] = 0.f;
-  float hsum = 0.f;
+  for (int j = 0; j < DEPTH; ++j) advance(j);
+  // the down scales of the first record's group travel with the first records
   const uint8_t *cur_base = nullptr;
   int cur_rows = 0, cur_grp = -1;
-
-  // PRE: a group's per-column scales of W_down are fetched when the wavefront enters the group
   u32x4 dsc[PRE ? 4 * LPR : 1];
   auto load_scales = [&](const uint8_t *base, int rows, int grp) {
     const uint16_t *sd = reinterpret_cast<const uint16_t *>(base + (int64_t)rows * rec_bytes) + (int64_t)grp * d;
@@ -406,11 +407,56 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int4_kernel(GemvParams 
       for (int q4 = 0; q4 < 4; ++q4) dsc[4 * c + q4] = sp[q4];
     }
   };
+  if (live[0]) {
+    cur_base = ring[0].base;
+    cur_rows = ring[0].rows;
+    cur_grp = ring[0].grp;
+    load_scales(cur_base, cur_rows, cur_grp);
+  }
 
-  // y += scale[group][col] * (acc - 1032*hsum)
+  // mask and bias of the nibble unpacking as register values (see and_or)
+  uint32_t mask_lo = kNibMaskLo, mask_hi = kNibMaskHi, bias = kF16Bias;
+  asm volatile("" : "+s"(mask_lo), "+s"(mask_hi));
+  asm volatile("" : "+v"(bias));
+
+  // Activations as packed fp16 pairs in the order the unpacking produces the weights: per dword of eight columns
+  // (x0, x4), (x1, x5) / 16, (x2, x6), (x3, x7) / 16.  xoff[c] removes, per chunk, what the biased weights add:
+  // 1024 * (sum of the even-column entries) + 64 * (sum of the odd-column entries, which are x / 16 times 1024)
+  // and the zero point 8 * (sum of all x).
+  uint32_t xp[CPL / 2];
+  float xoff[LPR];
+  float x_scale = 0.f;
+  if constexpr (FUSED) x_scale = 1.0f / sqrtf(blocks.total() / (float)d + 1e-6f);
+#pragma unroll
+  for (int c = 0; c < LPR; ++c) {
+    float xf[VEC];
+    if constexpr (FUSED) x_from_h<VEC>(hraw[c], x_scale, p.act_fmt, xf);
+    else unpack_x<VEC>(xraw[c], p.act_fmt, xf);
+    float s_even = 0.f, s_odd = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const float k = (t & 1) ? 0.0625f : 1.f;
+        const uint32_t pr = pack_f16(xf[w * 8 + t] * k, xf[w * 8 + t + 4] * k);
+        xp[c * 16 + w * 4 + t] = pr;
+        if (t & 1) s_odd += f16_lo(pr) + f16_hi(pr); else s_even += f16_lo(pr) + f16_hi(pr);
+      }
+    // odd entries hold x / 16: 1024 * (x / 16) = 64 x of bias, and 8 x = 128 * (x / 16) of zero point
+    xoff[c] = -((1024.f + 8.f) * s_even + (1024.f + 128.f) * s_odd);
+  }
+
+  float y[CPL], acc[CPL];
+#pragma unroll
+  for (int j = 0; j < CPL; ++j) y[j] = acc[j] = 0.f;
+  float hsum = 0.f;
+  bool dirty = false;  // acc holds something (scales of a group nothing was taken from are never applied)
+
+  // even columns: y += s * (acc - (1024 + 8) * hsum);  odd columns (weights taken 16-fold):
+  // y += (s / 16) * (acc - (1024 + 128) * hsum)
   auto flush = [&](const uint8_t *base, int rows, int grp) {
     const uint16_t *sd = reinterpret_cast<const uint16_t *>(base + (int64_t)rows * rec_bytes) + (int64_t)grp * d;
-    const float off = (1024.f + 8.f) * hsum;
+    const float off_even = (1024.f + 8.f) * hsum, off_odd = (1024.f + 128.f) * hsum;
 #pragma unroll
     for (int c = 0; c < LPR; ++c) {
       const u32x4 *sp = reinterpret_cast<const u32x4 *>(sd + (c * kWave + lane) * VEC);
@@ -421,18 +467,19 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int4_kernel(GemvParams 
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
           const int j = c * VEC + q4 * 8 + t * 2;
-          y[j] = __builtin_fmaf(f16_lo(sw[t]), acc[j] - off, y[j]);
-          y[j + 1] = __builtin_fmaf(f16_hi(sw[t]), acc[j + 1] - off, y[j + 1]);
+          y[j] = __builtin_fmaf(f16_lo(sw[t]), acc[j] - off_even, y[j]);
+          y[j + 1] = __builtin_fmaf(f16_hi(sw[t]) * 0.0625f, acc[j + 1] - off_odd, y[j + 1]);
           acc[j] = acc[j + 1] = 0.f;
         }
       }
     }
     hsum = 0.f;
+    dirty = false;
   };
 
   auto consume = [&](const RecI4<LPR> &R) {
     if (R.base != cur_base || R.grp != cur_grp) {
-      if (cur_base) flush(cur_base, cur_rows, cur_grp);
+      if (dirty) flush(cur_base, cur_rows, cur_grp);
       cur_base = R.base;
       cur_rows = R.rows;
       cur_grp = R.grp;
@@ -447,15 +494,15 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int4_kernel(GemvParams 
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
         const uint32_t *xw = &xp[c * 16 + w * 4];
-        // nibble pairs (t, t+4) -> packed bf16 (128 + n)
-        g0 = dot2_bf16((gw[w] & 0x000f000fu) | 0x43004300u, xw[0], g0);
-        g1 = dot2_bf16(((gw[w] >> 4) & 0x000f000fu) | 0x43004300u, xw[1], g1);
-        g0 = dot2_bf16(((gw[w] >> 8) & 0x000f000fu) | 0x43004300u, xw[2], g0);
-        g1 = dot2_bf16(((gw[w] >> 12) & 0x000f000fu) | 0x43004300u, xw[3], g1);
-        u0 = dot2_bf16((uw[w] & 0x000f000fu) | 0x43004300u, xw[0], u0);
-        u1 = dot2_bf16(((uw[w] >> 4) & 0x000f000fu) | 0x43004300u, xw[1], u1);
-        u0 = dot2_bf16(((uw[w] >> 8) & 0x000f000fu) | 0x43004300u, xw[2], u0);
-        u1 = dot2_bf16(((uw[w] >> 12) & 0x000f000fu) | 0x43004300u, xw[3], u1);
+        const uint32_t g8 = gw[w] >> 8, u8 = uw[w] >> 8;
+        g0 = dot2_f16(and_or(gw[w], mask_lo, bias), xw[0], g0);
+        g1 = dot2_f16(and_or(gw[w], mask_hi, bias), xw[1], g1);
+        g0 = dot2_f16(and_or(g8, mask_lo, bias), xw[2], g0);
+        g1 = dot2_f16(and_or(g8, mask_hi, bias), xw[3], g1);
+        u0 = dot2_f16(and_or(uw[w], mask_lo, bias), xw[0], u0);
+        u1 = dot2_f16(and_or(uw[w], mask_hi, bias), xw[1], u1);
+        u0 = dot2_f16(and_or(u8, mask_lo, bias), xw[2], u0);
+        u1 = dot2_f16(and_or(u8, mask_hi, bias), xw[3], u1);
       }
       g = __builtin_fmaf((g0 + g1) + xoff[c], f16_lo(R.sc[c]), g);
       u = __builtin_fmaf((u0 + u1) + xoff[c], f16_hi(R.sc[c]), u);
@@ -463,33 +510,49 @@ __global__ __launch_bounds__(NW *kWave) void expert_gemv_int4_kernel(GemvParams 
     wave_sum2(g, u);
     const float h = g / (1.f + __expf(-g)) * u * R.wt;
     hsum += h;
+    dirty = true;
 #pragma unroll
     for (int c = 0; c < LPR; ++c) {
       const uint32_t dw[4] = {R.dn[c].x, R.dn[c].y, R.dn[c].z, R.dn[c].w};
 #pragma unroll
-      for (int w = 0; w < 4; ++w)
+      for (int w = 0; w < 4; ++w) {
+        const uint32_t d8 = dw[w] >> 8;
+        const uint32_t pr[4] = {and_or(dw[w], mask_lo, bias), and_or(dw[w], mask_hi, bias), and_or(d8, mask_lo, bias),
+                                and_or(d8, mask_hi, bias)};
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-          // nibbles t and t+4 of the dword -> fp16 pair (1024 + n), consumed by mixed-precision FMAs
-          const uint32_t pr = ((dw[w] >> (4 * t)) & 0x000f000fu) | 0x64006400u;
+          // pair t = columns t and t + 4 of the dword (odd t: 16-fold), consumed by mixed-precision FMAs
           const int j = c * VEC + w * 8 + t;
-          acc[j] = __builtin_fmaf(f16_lo(pr), h, acc[j]);
-          acc[j + 4] = __builtin_fmaf(f16_hi(pr), h, acc[j + 4]);
+          acc[j] = __builtin_fmaf(f16_lo(pr[t]), h, acc[j]);
+          acc[j + 4] = __builtin_fmaf(f16_hi(pr[t]), h, acc[j + 4]);
         }
+      }
     }
   };
 
+  // steady state of pass 0: all ring entries live and at least DEPTH more entries to fetch
+  if (all && live[DEPTH - 1]) {
+    while (todo >= DEPTH) {
+#pragma unroll
+      for (int j = 0; j < DEPTH; ++j) {
+        if (want[j]) consume(ring[j]);
+        want[j] = walk.step(p);
+        issue(ring[j]);
+      }
+      todo -= DEPTH;
+    }
+  }
+  // start-up of short lists, tail, and pass 1.  ring[0] is always the oldest record in flight
   while (live[0]) {
 #pragma unroll
     for (int j = 0; j < DEPTH; ++j) {
       if (live[j]) {
-        consume(ring[j]);
-        live[j] = walk.next(p);
-        if (live[j]) issue(ring[j]);
+        if (want[j]) consume(ring[j]);
+        advance(j);
       }
     }
   }
-  if (cur_base) flush(cur_base, cur_rows, cur_grp);
+  if (dirty) flush(cur_base, cur_rows, cur_grp);
   reduce_and_store<NW, VEC, LPR>(y, red, p.partial + (int64_t)(p.row_offset + blockIdx.x) * d, tid, lane, wave);
 }
 
@@ -513,7 +576,7 @@ hipError_t launch_expert_gemv_quant(const GemvParams &p, int weight_fmt, const G
     }
   } else if (weight_fmt == MOE_W_INT4_G128) {
     switch (p.hidden / (kWave * 32)) {
-      case 1: MOE_Q(expert_gemv_int4_kernel, 1, 8, 4, true); break;
+      case 1: MOE_Q(expert_gemv_int4_kernel, 1, 8, 6, true); break;
       case 2: MOE_Q(expert_gemv_int4_kernel, 2, 8, 2, false); break;
       default: return hipErrorInvalidValue;
     }

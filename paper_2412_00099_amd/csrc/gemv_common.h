@@ -63,28 +63,45 @@ __device__ __forceinline__ u32x2 ld64(const void *p) { return *static_cast<const
 
 // FUSED: workgroup 0 of the launch runs the layer boundary; the records are shared among workgroups 1..G-1 and
 // the decision is fetched only when the first routed entry comes up, once workgroup 0 has handed it over.
-template <int NW, bool FUSED = false>
+// STEP: distance between a wavefront's consecutive list entries.  NW (the default) interleaves the wavefronts over
+// the workgroup's list; 1 gives every wavefront one contiguous block of it, so that its records stay inside one
+// expert and, for int4, inside one scale group of 128 records as far as possible.
+//
+// The walk is organised in runs - consecutive entries of the wavefront inside one blob (the shared expert, or one
+// selected expert) - so that the per-record work is an increment and a decrement; slot, weight and the split of the
+// routed index into (expert, row) are worked out once per run.  All of it is wavefront-uniform (scalar registers).
+template <int NW, bool FUSED = false, int STEP = NW>
 struct RecordWalker {
-  int s0, q0, ns, nl;  // this workgroup's shared rows start at s0 (ns of them), routed records at q0; nl entries
-  int idx;             // next list entry of this wavefront
-  int seg, row;        // position in the routed part (seg < 0: not entered yet)
-  // the routing record: loaded at kernel start, unpacked when the first routed record comes up
+  static_assert(STEP == NW || STEP == 1, "interleaved or blocked");
+  int sh_at, n_sh;   // the wavefront's shared records: first row, how many (not yet started)
+  int r, n_rt;       // its routed entries: next index into the K*I routed records, how many are left to start
+  int left;          // records left in the current run
+  int next_at;       // row of the current run's next record
+  bool run_wanted;   // the pass covers the current run's expert
+  bool decided;      // the routing decision has been unpacked
+  // the routing record: loaded at kernel start, unpacked when the first routed run comes up
   u32x4 rw0, rw1, rd;  // sel_weight[0..3], sel_weight[4..7], {tag, slots lo, slots hi, miss mask}
   uint64_t slots;
   uint32_t miss_mask;
-  // the record found by next()
+  // the record found by step() / next()
   const uint8_t *base;  // blob of the record's expert
   int rows, at;
   float wt;
 
-  // start of workgroup b's share of n records
-  static __device__ __forceinline__ int bound(int b, int n, int G) { return (int)((int64_t)b * n / G); }
+  // start of part b of n records split into G parts (b * n < 2^32: the host limits n to 2^22 and G to 2^10)
+  static __device__ __forceinline__ int bound(int b, int n, int G) {
+    return (int)((uint32_t)b * (uint32_t)n / (uint32_t)G);
+  }
 
+  // The record is the same for every lane and was written by an earlier launch: it is read through the scalar data
+  // path (constant address space), whose completion is counted apart from the vector loads - waiting for it does not
+  // wait for the weight loads already queued, and the values arrive in scalar registers.
   __device__ __forceinline__ void load_record(const GemvParams &p) {
-    const u32x4 *rr = reinterpret_cast<const u32x4 *>(p.route);
-    rw0 = ld128(rr + offsetof(moe_route_out_t, sel_weight) / 16);
-    rw1 = ld128(rr + offsetof(moe_route_out_t, sel_weight) / 16 + 1);
-    rd = ld128(rr + offsetof(moe_route_out_t, opaque) / 16);
+    typedef const __attribute__((address_space(4))) u32x4 *cvec;
+    cvec rr = (cvec)(reinterpret_cast<uintptr_t>(p.route));
+    rw0 = rr[offsetof(moe_route_out_t, sel_weight) / 16];
+    rw1 = rr[offsetof(moe_route_out_t, sel_weight) / 16 + 1];
+    rd = rr[offsetof(moe_route_out_t, opaque) / 16];
   }
 
   // FUSED: the decision as workgroup 0 of this launch hands it over - eight 8-byte words, each carrying the
@@ -129,17 +146,32 @@ struct RecordWalker {
 
   __device__ __forceinline__ void init(const GemvParams &p, int wave) {
     const int G = FUSED ? (int)gridDim.x - 1 : (int)gridDim.x, b = FUSED ? (int)blockIdx.x - 1 : (int)blockIdx.x;
-    // the routing record first: these loads return before any weight load issued after them
+    // the routing record first: it is on its way while the shared records are set up
     if constexpr (!FUSED) load_record(p);
     const int routed = p.top_k * p.inter;
     const int shared = p.pass == 0 ? p.shared_inter : 0;
-    s0 = bound(b, shared, G);
-    ns = bound(b + 1, shared, G) - s0;
-    q0 = bound(b, routed, G);
-    nl = ns + bound(b + 1, routed, G) - q0;
-    idx = wave;
-    seg = -1;
-    row = 0;
+    // the workgroup's list: ns shared records from row s0, then nr routed entries from q0
+    const int s0 = bound(b, shared, G), ns = bound(b + 1, shared, G) - s0;
+    const int q0 = bound(b, routed, G), nl = ns + bound(b + 1, routed, G) - q0;
+    int first_sh, first_rt;  // list indices
+    if constexpr (STEP == 1) {
+      const int lb = wave * nl / NW, le = (wave + 1) * nl / NW;
+      first_sh = lb;
+      n_sh = max(0, min(le, ns) - lb);
+      first_rt = max(lb, ns);
+      n_rt = max(0, le - first_rt);
+    } else {
+      first_sh = wave;
+      n_sh = wave < ns ? (ns - wave + NW - 1) / NW : 0;
+      first_rt = wave + n_sh * NW;
+      n_rt = first_rt < nl ? (nl - first_rt + NW - 1) / NW : 0;
+    }
+    sh_at = s0 + first_sh;
+    r = q0 + (first_rt - ns);
+    left = 0;
+    next_at = 0;
+    run_wanted = true;
+    decided = false;
   }
 
   // masks instead of a select chain: a chain over adjacent members is turned into an indexed load from a
@@ -158,22 +190,21 @@ struct RecordWalker {
   }
 
   // list entries this wavefront still owns
-  __device__ __forceinline__ int remaining() const { return idx < nl ? (nl - idx + NW - 1) / NW : 0; }
+  __device__ __forceinline__ int remaining() const { return left + n_sh + n_rt; }
 
-  // Move to this wavefront's next list entry (there must be one: see remaining()) and describe its record, whether
-  // the pass covers it or not; returns whether it does.  The caller loads the record in any case, so that the
-  // number of loads in flight does not depend on the routing decision, and only skips the arithmetic.
-  __device__ __forceinline__ bool step(const GemvParams &p) {
-    const int I = p.inter, K = p.top_k;
-    if (idx < ns) {
+  // the wavefront's next run (there must be one): its shared records first, then its routed entries expert by expert
+  __device__ __forceinline__ void start_run(const GemvParams &p) {
+    if (n_sh > 0) {
       base = p.shared_blob;
       rows = p.shared_inter;
-      at = s0 + idx;
+      next_at = sh_at;
+      left = n_sh;
+      n_sh = 0;
       wt = 1.f;
-      idx += NW;
-      return true;
+      run_wanted = true;
+      return;
     }
-    if (seg < 0) {  // first routed entry: unpack the routing record, locate the entry
+    if (!decided) {  // first routed run: unpack the routing record
       bool ok = true;
       if constexpr (FUSED) {
         // (one wavefront per workgroup fetching for all eight through LDS was measured: no faster)
@@ -187,29 +218,47 @@ struct RecordWalker {
         miss_mask = p.pass == 1 ? 0u : ~0u;
         *p.b.gave_up = 1u;
       }
-      const int r = q0 + (idx - ns);
-      seg = r / I;
-      row = r - seg * I;
+      decided = true;
     }
-    const bool wanted = (((miss_mask >> seg) & 1u) != 0) == (p.pass == 1);
+    const int I = p.inter;
+    const int seg = (int)((uint32_t)r / (uint32_t)I), row = r - seg * I;
+    const int in_seg = (I - row + STEP - 1) / STEP;  // this wavefront's entries inside expert `seg` from here on
+    left = min(in_seg, n_rt);
+    n_rt -= left;
+    r += left * STEP;
     base = p.slot_pool + (int64_t)((slots >> (8 * seg)) & 0xffu) * p.slot_bytes;
     rows = I;
-    at = row;
+    next_at = row;
     wt = pick_weight(seg);
-    idx += NW;
-    row += NW;
-    while (row >= I && seg < K) {
-      row -= I;
-      ++seg;
-    }
-    return wanted;
+    run_wanted = (((miss_mask >> seg) & 1u) != 0) == (p.pass == 1);
+  }
+
+  // Move to this wavefront's next list entry (there must be one: see remaining()) and describe its record, whether
+  // the pass covers it or not; returns whether it does.  The caller loads the record in any case, so that the
+  // number of loads in flight does not depend on the routing decision, and only skips the arithmetic.
+  __device__ __forceinline__ bool step(const GemvParams &p) {
+    if (left == 0) start_run(p);
+    at = next_at;
+    next_at += STEP;
+    --left;
+    return run_wanted;
   }
 
   // advance to this wavefront's next record of the pass, skipping the others; false when the list is exhausted
   __device__ __forceinline__ bool next(const GemvParams &p) {
-    while (idx < nl)
-      if (step(p)) return true;
-    return false;
+    for (;;) {
+      if (left == 0) {
+        if (n_sh + n_rt == 0) return false;
+        start_run(p);
+      }
+      if (run_wanted) {
+        at = next_at;
+        next_at += STEP;
+        --left;
+        return true;
+      }
+      left = 0;  // the pass does not cover this expert: drop the whole run
+    }
   }
 };
 

@@ -185,6 +185,8 @@ int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, 
   if (!gemv_inter_supported(cfg->weight_fmt, cfg->inter) ||
       (cfg->shared_inter > 0 && !gemv_inter_supported(cfg->weight_fmt, cfg->shared_inter)))
     return fail(MOE_EINVAL, "intermediate size unsupported for this weight format (int8: multiple of 8, int4: multiple of 128)");
+  if ((int64_t)cfg->top_k * cfg->inter + cfg->shared_inter > (int64_t)1 << 22)
+    return fail(MOE_EINVAL, "more than 2^22 expert records per layer-token");
   if (!(cfg->lambda >= 0.f) || !std::isfinite(cfg->lambda)) return fail(MOE_EINVAL, "lambda must be finite and >= 0");
   if (cfg->delta_mode < MOE_DELTA_RUNNING_MEAN || cfg->delta_mode > MOE_DELTA_TOKEN) return fail(MOE_EINVAL, "bad delta_mode");
   if (cfg->delta_mode == MOE_DELTA_FIXED && !std::isfinite(cfg->delta_fixed)) return fail(MOE_EINVAL, "delta_fixed must be finite");
@@ -555,6 +557,7 @@ int moe_expert_forward_static(int32_t weight_fmt, int32_t act_fmt, int32_t hidde
       (shared_inter > 0 && !gemv_inter_supported(weight_fmt, shared_inter)))
     return fail(MOE_EINVAL, "intermediate size unsupported for this weight format");
   if (top_k <= 0 || top_k > MOE_MAX_TOPK) return fail(MOE_EINVAL, "top_k must be in 1..%d", MOE_MAX_TOPK);
+  if ((int64_t)top_k * inter + shared_inter > (int64_t)1 << 22) return fail(MOE_EINVAL, "more than 2^22 expert records");
   if (n_slots <= 0 || n_slots > 256) return fail(MOE_EINVAL, "n_slots must be in 1..256");
   if (!slot_pool_dev || !sel_slot_host || !sel_weight_host || !x_dev || !y_dev) return fail(MOE_EINVAL, "NULL argument");
   if (shared_inter > 0 && !shared_blob_dev) return fail(MOE_EINVAL, "shared_inter > 0 needs shared_blob_dev");

@@ -23,7 +23,7 @@ BlobLayout blob_layout(int fmt, int hidden, int inter) {
       break;
     case MOE_W_INT4_G128:  // record carries its (gate, up) group scales; tail: down scales [I/128][d], fp16
       L.row_bytes = d / 2;
-      L.rec_bytes = 3 * L.row_bytes + (d / 128) * 4;
+      L.rec_bytes = int4_record_bytes(d);
       tail_bytes = (I / 128) * d * 2;
       break;
     default: return L;
@@ -93,7 +93,7 @@ __global__ void pack_int8_kernel(const int8_t *gate, const int8_t *up, const int
 // gathered nibble by nibble; the record ends with its (gate, up) scale pairs, the down scales form the tail.
 __global__ void pack_int4_kernel(const uint8_t *gate, const uint8_t *up, const uint8_t *down, const uint16_t *gs,
                                  const uint16_t *us, const uint16_t *ds, uint8_t *blob, int d, int I) {
-  const int64_t row_bytes = d / 2, groups = d / 128, rec_bytes = 3 * row_bytes + groups * 4;
+  const int64_t row_bytes = d / 2, groups = d / 128, rec_bytes = int4_record_bytes(d);
   const int64_t chunks_per_row = row_bytes / 16;
   const int64_t n_chunks = (int64_t)I * 3 * chunks_per_row;
   const int64_t stride = (int64_t)gridDim.x * blockDim.x;

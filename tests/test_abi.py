@@ -44,8 +44,10 @@ def test_blob_bytes(B):
     pad = lambda n: (n + 255) // 256 * 256
     # int8: offset-binary bytes + tail of fp16 scales (gate [I], up [I], down [d])
     assert B.moe_blob_bytes(B.MOE_W_INT8_PC, 4096, 14336) == pad(3 * 4096 * 14336 + (2 * 14336 + 4096) * 2)
-    # int4: nibbles + (gate, up) group scales inside each record + tail of down scales [I/128][d]
-    assert B.moe_blob_bytes(B.MOE_W_INT4_G128, 2048, 1408) == pad(1408 * (3 * 1024 + 16 * 4) + 11 * 2048 * 2)
+    # int4: nibbles + (gate, up) group scales inside each record (padded to a 128-byte line) + tail of down scales
+    # [I/128][d]
+    assert B.moe_blob_bytes(B.MOE_W_INT4_G128, 2048, 1408) == pad(1408 * (3 * 1024 + 128) + 11 * 2048 * 2)
+    assert B.moe_blob_bytes(B.MOE_W_INT4_G128, 4096, 256) == pad(256 * (3 * 2048 + 128) + 2 * 4096 * 2)
     assert B.moe_blob_bytes(B.MOE_W_INT4_G128, 2048, 1400) == 0  # rows of W_down not a multiple of the group
     assert B.moe_blob_bytes(B.MOE_W_INT8_PC, 2048, 12) == 0
     assert B.moe_blob_bytes(B.MOE_W_BF16, 100, 64) == 0  # hidden not a multiple of 512
