@@ -158,6 +158,60 @@ def kernel_time(dec, a, h, x, y, warmup, steps):
     return us, n, prof
 
 
+def prompt_phase(pkg, store, cfg, a, dev, n_warm=128, n_timed=256):
+    """Prompt phase on the same store: tokens go through the stack layer by layer in batches of B (Sec. 4.5 leaves
+    prompt processing to batched kernels; a batch is routed as its tokens in order).  Inputs of every layer are the
+    exogenous AR(1) streams rounded to bf16, as in the parity runs.  Per B: prompt tokens/s through all layers
+    (routing + experts, fills included), the two parts per layer-batch, and the expert part against the HBM
+    roofline, its algorithmic bytes being the distinct experts a batch touches plus the shared expert."""
+    import torch
+
+    L, K = cfg.n_layers, cfg.top_k
+    xs = a[: n_warm + n_timed].to(cfg.act_dtype)
+    out = {}
+    for B in (8, 32, 128):
+        dec = pkg.MoEDecoder(store, top_k=cfg.top_k, top_j=cfg.top_j, lam=HEADLINE_LAMBDA, renormalize=cfg.renormalize)
+        y = torch.zeros((B, cfg.hidden), dtype=cfg.act_dtype, device=dev)
+        t_route = t_exp = 0.0
+        n_batches = distinct = 0
+        s0 = None
+        for l in range(L):
+            for t0 in range(0, n_warm + n_timed, B):
+                x = xs[t0:t0 + B, l].contiguous()
+                timed = t0 >= n_warm
+                if timed and s0 is None and l == 0:
+                    s0 = dec.stats(0)
+                torch.cuda.synchronize()
+                t1 = time.perf_counter()
+                recs = dec.route_batch(l, x=x)
+                t2 = time.perf_counter()
+                dec.expert_forward_batch(l, x, y)
+                t3 = time.perf_counter()
+                if timed:
+                    t_route += t2 - t1
+                    t_exp += t3 - t2
+                    n_batches += 1
+                    distinct += len({r.sel_expert[k] for r in recs for k in range(K)})
+        st = dec.stats()
+        dec.close()
+        algo = (distinct / n_batches) * store.blob_bytes + store.shared_bytes
+        exp_us = 1e6 * t_exp / n_batches
+        gbs = algo / (exp_us * 1e-6) / 1e9
+        flops = 2.0 * 3 * cfg.hidden * (B * K * cfg.inter + B * cfg.shared_inter)
+        out[f"B{B}"] = dict(
+            tok_s=round(n_timed / (t_route + t_exp), 1),
+            route_us_per_layer_batch=round(1e6 * t_route / n_batches, 1), expert_us_per_layer_batch=round(exp_us, 1),
+            distinct_experts_per_batch=round(distinct / n_batches, 2), algorithmic_MB_per_layer_batch=round(algo / 1e6, 1),
+            expert_GBps=round(gbs, 1), frac_hbm=round(gbs / HBM_PEAK_GBS, 4),
+            expert_TFLOPs=round(flops / (exp_us * 1e-6) / 1e12, 2), miss_rate_all_tokens=round(st.misses / max(st.selections, 1), 5))
+        log(f"prompt phase B={B}: {out[f'B{B}']['tok_s']} tok/s, route {out[f'B{B}']['route_us_per_layer_batch']} us + "
+            f"experts {exp_us:.1f} us per layer-batch ({gbs:.0f} GB/s of the distinct experts' bytes)")
+    out["note"] = (f"{n_warm} warm-up + {n_timed} timed prompt tokens, lambda={HEADLINE_LAMBDA}; expert time is the wall time of "
+                   "moe_expert_forward_batch (fills, table upload, expert launches, reduction); compare decode: "
+                   "steady_state.per_layer_us per token and layer")
+    return out
+
+
 def release_memory():
     """Give device and pinned host memory of a finished workload back (both are cached by PyTorch's allocators)."""
     import gc
@@ -396,6 +450,10 @@ def main():
                          mean_lifetime_tokens=round(r3["mean_lifetime"], 2))
         log(f"top_j=2: {r3['tok_s']:.1f} tok/s, miss rate {r3['miss_rate']:.4f}")
 
+    prompt = None
+    if not args.no_sweep and cfg.weight_fmt == "bf16" and cfg.act_fmt == "bf16" and cfg.hidden in (1024, 2048):
+        prompt = prompt_phase(pkg, store, cfg, a, dev)
+
     link_gbs = host_link_rate(store)
     log(f"miss fill copy: {link_gbs:.1f} GB/s")
 
@@ -498,6 +556,7 @@ def main():
         "cpu_baseline": cpu,
         "lambda_sweep": sweep,
         "top_j_2": top_j_run,
+        "prompt_phase": prompt,
         "other_workloads": others,
     }
     print(json.dumps(out))

@@ -161,6 +161,26 @@ int moe_route_step(moe_cache_t *ctx, int32_t layer, const void *x_dev, const flo
  * moe_stack_route_step (of any layer), which must follow before another moe_expert_forward. */
 int moe_expert_forward(moe_cache_t *ctx, int32_t layer, const void *x_dev, void *y_dev);
 
+/* Prompt phase: n_tokens (1..128) tokens of one layer in one call.  The paper applies its routing during generation and
+ * leaves prompt processing to batched kernels (Sec. 4.5; App. F varies the prompt length); here a batch is routed as
+ * its tokens one after the other - the cache bitmask m_t of Sec. 3.3 is the state after token t-1, also inside a batch -
+ * so decisions, slots, evictions, Delta_avg (Eq. 10) and the miss counts of Eq. 4 are exactly those of n_tokens calls of
+ * moe_route_step in the same order; only the arithmetic is batched (matrix cores).
+ * moe_route_batch: exactly one of x_dev (device [n_tokens, d], act_fmt: the gate logits are computed) and logits_dev
+ *   (device [n_tokens, N] fp32) is non-NULL.  Returns once all decisions are on the host; out_host (may be NULL)
+ *   receives n_tokens records.  x_dev must stay unchanged until moe_expert_forward_batch.
+ * moe_expert_forward_batch: y[t] = sum_k w_k E_k(x[t]) + shared(x[t]) (Eq. 1) for every token of the batch routed
+ *   last; x_dev as given to moe_route_batch, y_dev device [n_tokens, d] in act_fmt.  Tokens are grouped per expert;
+ *   where a slot is refilled inside the batch after an earlier token has read it, the batch is cut there and the
+ *   parts run one after the other, each behind its fills.  The partial results are added in a fixed order (y is
+ *   reproducible bit for bit).  Returns when y is complete.
+ * Shapes: bf16 weights and activations, hidden 1024 or 2048, intermediate sizes that are multiples of 16;
+ * MOE_EINVAL otherwise.  MOE_ESTATE if a single-token step of the layer or an expert output is pending, or if
+ * moe_expert_forward_batch does not follow a moe_route_batch of the same layer and size. */
+int moe_route_batch(moe_cache_t *ctx, int32_t layer, const void *x_dev, const float *logits_dev, int32_t n_tokens,
+                    moe_route_out_t *out_host);
+int moe_expert_forward_batch(moe_cache_t *ctx, int32_t layer, const void *x_dev, void *y_dev, int32_t n_tokens);
+
 /* moe_expert_forward for callers that cannot allocate device memory or hold a context: code under HIP graph capture,
  * tight serving loops, harnesses that forbid allocation.  Computes y = sum_k w_k E_k(x) + shared(x) for experts that are
  * all in their slots, with the kernels moe_expert_forward uses.  The call allocates nothing (no hipMalloc / hipFree, no

@@ -116,6 +116,10 @@ lib.moe_stack_route_step.restype = C.c_int
 lib.moe_stack_route_step.argtypes = [_vp, C.c_int32, _vp, _vp, C.c_float, C.c_int32, _vp, _vp, C.POINTER(moe_route_out_t)]
 lib.moe_expert_forward.restype = C.c_int
 lib.moe_expert_forward.argtypes = [_vp, C.c_int32, _vp, _vp]
+lib.moe_route_batch.restype = C.c_int
+lib.moe_route_batch.argtypes = [_vp, C.c_int32, _vp, _vp, C.c_int32, C.POINTER(moe_route_out_t)]
+lib.moe_expert_forward_batch.restype = C.c_int
+lib.moe_expert_forward_batch.argtypes = [_vp, C.c_int32, _vp, _vp, C.c_int32]
 lib.moe_expert_forward_static.restype = C.c_int
 lib.moe_expert_forward_static.argtypes = [C.c_int32] * 6 + [_vp, C.c_int32, _vp, C.POINTER(C.c_int32), C.POINTER(C.c_float),
                                           _vp, _vp, _vp]
@@ -149,7 +153,7 @@ lib.moe_last_error.argtypes = []
 
 EXPORTS = [
     "moe_blob_bytes", "moe_slot_bytes", "moe_pack_expert", "moe_cache_init", "moe_cache_destroy", "moe_route_step", "moe_stack_route_step",
-    "moe_expert_forward", "moe_expert_forward_static", "moe_cache_last_route", "moe_cache_stats", "moe_cache_tables", "moe_cache_snapshot",
+    "moe_expert_forward", "moe_route_batch", "moe_expert_forward_batch", "moe_expert_forward_static", "moe_cache_last_route", "moe_cache_stats", "moe_cache_tables", "moe_cache_snapshot",
     "moe_cache_restore", "moe_trace_misses", "moe_cache_plan", "moe_cache_set_lambda",
     "moe_cache_set_baseline", "moe_cache_reset", "moe_residual_rmsnorm", "moe_cache_profile", "moe_last_error",
 ]
@@ -217,6 +221,17 @@ def moe_stack_route_step(ctx, layer: int, h_dev, a_dev, perturb: float, carry: i
 
 def moe_expert_forward(ctx, layer: int, x_dev, y_dev) -> None:
     _check(lib.moe_expert_forward(ctx, layer, x_dev, y_dev), "moe_expert_forward")
+
+
+def moe_route_batch(ctx, layer: int, x_dev, logits_dev, n_tokens: int):
+    """Returns the n_tokens routing records of the batch."""
+    out = (moe_route_out_t * n_tokens)()
+    _check(lib.moe_route_batch(ctx, layer, x_dev, logits_dev, n_tokens, out), "moe_route_batch")
+    return list(out)
+
+
+def moe_expert_forward_batch(ctx, layer: int, x_dev, y_dev, n_tokens: int) -> None:
+    _check(lib.moe_expert_forward_batch(ctx, layer, x_dev, y_dev, n_tokens), "moe_expert_forward_batch")
 
 
 def moe_expert_forward_static(weight_fmt, act_fmt, hidden, inter, shared_inter, top_k, slot_pool_dev, n_slots,

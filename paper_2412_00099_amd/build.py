@@ -33,6 +33,7 @@ SOURCES = {
     "moe_cache.hip": [],
     "trace_sim.hip": [],
     "expert_static.hip": [],
+    "expert_batch.hip": [],
 }
 
 

@@ -135,6 +135,38 @@ hipError_t launch_residual_rmsnorm(float *h, const void *y, const float *a, floa
                                    int hidden, int act_fmt, hipStream_t s);
 hipError_t launch_state_init(LayerState *state, int n_layers, const int32_t *initial_dev, int n_initial,
                              hipStream_t s);
+// ---- prompt phase (expert_batch.hip): a batch of tokens through one layer ----
+constexpr int kMaxBatch = 128;        // tokens per moe_route_batch / moe_expert_forward_batch call
+constexpr int kBatchUnitRecords = 128;  // records of one expert handled by one workgroup of the batched expert kernel
+// up to 16 tokens routed to one expert (or any 16 tokens, for the shared expert) and their weights for it
+struct TokenTile {
+  int32_t tok[16];
+  float w[16];
+  int32_t n, pad[3];
+};
+// one workgroup's work: n_rec (a multiple of 16) records from rec0 of the expert in `slot` (-1: the shared expert),
+// applied to the tokens of tile `tile`
+struct BatchUnit {
+  int32_t slot, rec0, n_rec, tile;
+};
+struct BatchParams {
+  const uint8_t *slot_pool, *shared_blob;
+  const uint16_t *x;  // [B, d] bf16
+  float *partial;     // [n_units][16][d] fp32: every unit's output tile
+  const BatchUnit *units;
+  const TokenTile *tiles;
+  int32_t hidden, inter, shared_inter, n_units;
+  int64_t slot_bytes;
+};
+bool batch_shape_supported(int weight_fmt, int act_fmt, int hidden, int inter, int shared_inter);
+hipError_t launch_gate_gemm(const void *x, const void *gate_w, float *logits, int B, int N, int hidden, hipStream_t s);
+hipError_t launch_route_batch(const RouteParams &p, const float *logits, int B, LayerState *state, moe_route_out_t *out,
+                              hipStream_t s);
+hipError_t launch_expert_batch(const BatchParams &p, hipStream_t s);
+// y[t_first + t] = sum of the partial rows contrib[t][0 .. n_contrib[t]) in that order, for t < n_tokens
+hipError_t launch_reduce_batch(const float *partial, const int32_t *contrib, const int32_t *n_contrib, int max_contrib,
+                               void *y, int hidden, int t_first, int n_tokens, hipStream_t s);
+
 // the allocation-free entry point (expert_static.hip): device address of its fixed scratch array and the compute-unit
 // count of device `dev` (which must be current), looked up once per device
 hipError_t static_scratch_setup(int dev, void **ptr, int *cus);

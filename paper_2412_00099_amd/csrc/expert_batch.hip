@@ -1,0 +1,293 @@
+// Prompt phase: a batch of B tokens through one MoE layer (paper Sec. 4.5 applies the cache-aware routing during
+// generation and lets prompt processing use batched kernels; App. F looks at the prompt length).  The routing of the
+// batch is the routing of its tokens one after the other - the cache bitmask m_t of Sec. 3.3 is the state after
+// token t-1, also inside a batch - so every decision, slot and miss count equals what B single-token steps give;
+// only the arithmetic is batched: the gate logits of all tokens by one small GEMM, the experts by a
+// weights-stationary small GEMM per expert over the tokens routed to it (Eq. 1), both on the matrix cores.
+//
+//  gate_gemm_kernel    logits[B, N] = X[B, d] W_gate[N, d]^T, bf16 inputs, fp32 accumulation
+//                      (v_mfma_f32_16x16x32_bf16: a 16-token x 16-expert tile per wavefront).
+//  route_batch_kernel  one wavefront walks the tokens in order through rt::route_wave, the cache state carried in
+//                      registers from token to token; one routing record per token.
+//  expert_batch_kernel one workgroup (8 wavefronts) per unit = (expert blob, up to 128 consecutive records, tile of up
+//                      to 16 tokens routed to that expert).  Per block of 16 records: all its weights are requested
+//                      at once; g, u = W_gate/up block x X tile^T with the 16x16x32 bf16 MFMA, the hidden dimension
+//                      split over the wavefronts and summed through LDS; h = silu(g) u w; then the block's columns of
+//                      W_down (the record layout keeps them as rows) are applied with the 16x16x4 fp32 MFMA, whose
+//                      operands hold one value per lane, so the rows need no transposition; each wavefront owns d/8
+//                      output columns and keeps their 16-token accumulators in registers over the whole unit.  Every
+//                      unit writes its 16 x d tile to its own rows of a partial buffer.
+//  reduce_batch_kernel adds each token's partial rows in a fixed order (deterministic y) and rounds to bf16.
+#include <type_traits>
+
+#include "common.h"
+#include "gemv_common.h"
+#include "route_device.h"
+
+namespace moe {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ f32x4 mfma_bf16(u32x4 a, u32x4 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x4 mfma_f32(float a, float b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+// ---- gate logits of the batch -------------------------------------------------------------------
+// grid = token tiles of 16, block = 64 * expert tiles of 16.  A-operand lane l: token l % 16, columns k0 + 8 (l / 16)
+// .. + 8; B-operand lane l: expert n0 + l % 16, the same columns; result lane l: expert n0 + l % 16, tokens
+// 4 (l / 16) + v.  Rows past the last token / expert re-read the last one and are not stored.
+__global__ __launch_bounds__(256) void gate_gemm_kernel(const uint16_t *x, const uint16_t *gate_w, float *logits, int B,
+                                                       int N, int d) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int t0 = blockIdx.x * 16, n0 = wave * 16;
+  const int tok = min(t0 + (lane & 15), B - 1), exp = min(n0 + (lane & 15), N - 1);
+  const u32x4 *xa = reinterpret_cast<const u32x4 *>(x + (size_t)tok * d) + (lane >> 4);
+  const u32x4 *wb = reinterpret_cast<const u32x4 *>(gate_w + (size_t)exp * d) + (lane >> 4);
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < d / 32; ++s) acc = mfma_bf16(xa[s * 4], wb[s * 4], acc);
+  const int e = n0 + (lane & 15);
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    const int t = t0 + 4 * (lane >> 4) + v;
+    if (t < B && e < N) logits[(size_t)t * N + e] = acc[v];
+  }
+}
+
+// ---- routing of the batch, token by token ---------------------------------------------------------
+__global__ __launch_bounds__(64) void route_batch_kernel(RouteParams p, const float *logits, int B, LayerState *st,
+                                                         moe_route_out_t *out) {
+  __shared__ float z_s[MOE_MAX_EXPERTS];
+  __shared__ __attribute__((aligned(16))) uint32_t rec_s[rt::kRecWords];
+  const int lane = threadIdx.x;
+  rt::CacheRegs cr = rt::load_cache_regs(st, lane, p.n_experts, p.capacity);
+  for (int t = 0; t < B; ++t) {
+    z_s[lane] = lane < p.n_experts ? logits[(size_t)t * p.n_experts + lane] : 0.f;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    rt::CacheRegs next;
+    rt::route_wave(p, z_s, cr, st, out + t, nullptr, rec_s, lane, rt::BoundaryFlags{nullptr, 0}, &next);
+    cr = next;
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  }
+}
+
+// ---- experts of the batch ---------------------------------------------------------------------------
+constexpr int kBatchWaves = 8;
+constexpr int kXPad = 8;  // bf16 elements of padding per X row in LDS (16 bytes: rows start in different banks)
+
+// CBW: blocks of 128 output columns per wavefront (d = 8 * 128 * CBW)
+template <int CBW>
+__global__ __launch_bounds__(kBatchWaves *kWave) void expert_batch_kernel(BatchParams p) {
+  constexpr int NW = kBatchWaves;
+  constexpr int D = NW * 128 * CBW;   // hidden size
+  constexpr int KS = D / (NW * 32);   // 32-column steps of the gate / up products per wavefront
+  constexpr int XS = D + kXPad;       // LDS row stride of the X tile, in bf16 elements
+  extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
+  uint16_t *xs = reinterpret_cast<uint16_t *>(lds);                              // [16][XS] bf16
+  f32x4 *red = reinterpret_cast<f32x4 *>(lds + 16 * XS * 2);                     // [2][NW][2][64]
+  float *hs = reinterpret_cast<float *>(lds + 16 * XS * 2 + 2 * NW * 2 * 64 * 16);  // [NW][16][16]
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const BatchUnit u = p.units[blockIdx.x];
+  const TokenTile *tile = p.tiles + u.tile;
+  const int n_tok = tile->n;
+  const uint8_t *blob = u.slot < 0 ? p.shared_blob : p.slot_pool + (int64_t)u.slot * p.slot_bytes;
+  const int64_t row_bytes = (int64_t)D * 2, rec_bytes = 3 * row_bytes;
+
+  // X tile: row t = activations of the tile's t-th token (zeros past the last token)
+  for (int c = tid; c < 16 * (D / 8); c += NW * kWave) {
+    const int t = c / (D / 8), k8 = c - t * (D / 8);
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (t < n_tok) v = *(reinterpret_cast<const u32x4 *>(p.x + (size_t)tile->tok[t] * D) + k8);
+    *reinterpret_cast<u32x4 *>(xs + t * XS + k8 * 8) = v;
+  }
+  const float wt = (lane & 15) < n_tok ? tile->w[lane & 15] : 0.f;  // weight of token lane % 16 for this expert
+  __syncthreads();
+
+  f32x4 acc[CBW][8];
+#pragma unroll
+  for (int cb = 0; cb < CBW; ++cb)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[cb][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int m16 = lane & 15, kq = lane >> 4;
+  float *hw = hs + wave * 256;
+  // The loads of a block: gate and up rows for this wavefront's slice of the hidden dimension, and its columns of the
+  // down rows.  They are requested as early as their registers are free - gate / up of the next block right after
+  // this block's gate / up products, down of the next block right after this block's down products - so that the
+  // barrier, the reduction and the arithmetic of a block overlap the transfer of the next.
+  u32x4 ag[KS], au[KS], dn[4][CBW];
+  auto load_gu = [&](int r0) {
+    const uint8_t *row = blob + (int64_t)(r0 + m16) * rec_bytes + ((int64_t)wave * (D / NW) + kq * 8) * 2;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      ag[s] = stream_load(reinterpret_cast<const u32x4 *>(row + s * 64));
+      au[s] = stream_load(reinterpret_cast<const u32x4 *>(row + row_bytes + s * 64));
+    }
+  };
+  auto load_dn = [&](int r0) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const uint8_t *drow = blob + (int64_t)(r0 + 4 * s + kq) * rec_bytes + 2 * row_bytes +
+                            ((int64_t)wave * (D / NW) + m16 * 8) * 2;
+#pragma unroll
+      for (int cb = 0; cb < CBW; ++cb) dn[s][cb] = stream_load(reinterpret_cast<const u32x4 *>(drow + cb * 256));
+    }
+  };
+  const uint16_t *xrow = xs + m16 * XS + wave * (D / NW) + kq * 8;
+  int parity = 0;
+  // one block of 16 records; NEXT: there is a block after it, whose loads are requested on the way
+  auto block = [&](int r_next, auto next_tag) {
+    constexpr bool NEXT = decltype(next_tag)::value;
+    // gate / up: this wavefront's slice of the hidden dimension
+    f32x4 g = {0.f, 0.f, 0.f, 0.f}, up = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      const u32x4 b = *reinterpret_cast<const u32x4 *>(xrow + s * 32);
+      g = mfma_bf16(ag[s], b, g);
+      up = mfma_bf16(au[s], b, up);
+    }
+    if constexpr (NEXT) load_gu(r_next);
+    f32x4 *rb = red + (size_t)parity * (NW * 2 * 64);
+    parity ^= 1;
+    rb[(wave * 2 + 0) * 64 + lane] = g;
+    rb[(wave * 2 + 1) * 64 + lane] = up;
+    // (the buffer alternates between blocks, so one barrier per block is enough; it waits for LDS only, not for
+    // the weight loads in flight)
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    g = rb[lane];
+    up = rb[64 + lane];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) {
+      const f32x4 tg = rb[(w * 2 + 0) * 64 + lane], tu = rb[(w * 2 + 1) * 64 + lane];
+      g += tg;
+      up += tu;
+    }
+    // h for records 4 (lane / 16) + v and token lane % 16, stored as [record][token] for this wavefront
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const float h = g[v] / (1.f + __expf(-g[v])) * up[v] * wt;
+      hw[(4 * kq + v) * 16 + m16] = h;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    // down: y[token][column] += sum over the block's records of h[record][token] * W_down[column][record]
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const float a = hw[(4 * s + kq) * 16 + m16];  // A operand: token lane % 16, record 4 s + lane / 16
+#pragma unroll
+      for (int cb = 0; cb < CBW; ++cb) {
+        const uint32_t w4[4] = {dn[s][cb].x, dn[s][cb].y, dn[s][cb].z, dn[s][cb].w};
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const float b = (j & 1) ? bf16_hi(w4[j >> 1]) : bf16_lo(w4[j >> 1]);
+          acc[cb][j] = mfma_f32(a, b, acc[cb][j]);
+        }
+      }
+    }
+    if constexpr (NEXT) load_dn(r_next);
+    __builtin_amdgcn_wave_barrier();
+  };
+  load_gu(u.rec0);
+  load_dn(u.rec0);
+  for (int blk = 16; blk < u.n_rec; blk += 16) block(u.rec0 + blk, std::true_type{});
+  block(0, std::false_type{});
+
+  // The unit's tile goes to its own rows of the partial buffer (result lane l: tokens 4 (l / 16) + v, column
+  // wave * d/8 + cb * 128 + (l % 16) * 8 + j); reduce_batch_kernel adds the tiles of a token in a fixed order.
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    const int t = 4 * kq + v;
+    if (t < n_tok) {
+      float *yrow = p.partial + ((size_t)blockIdx.x * 16 + t) * D + wave * (D / NW) + m16 * 8;
+#pragma unroll
+      for (int cb = 0; cb < CBW; ++cb) {
+        *reinterpret_cast<f32x4 *>(yrow + cb * 128) = f32x4{acc[cb][0][v], acc[cb][1][v], acc[cb][2][v], acc[cb][3][v]};
+        *reinterpret_cast<f32x4 *>(yrow + cb * 128 + 4) = f32x4{acc[cb][4][v], acc[cb][5][v], acc[cb][6][v], acc[cb][7][v]};
+      }
+    }
+  }
+}
+
+// y[t] = the sum of token t's partial rows in list order, rounded to bf16.  contrib[t * max_contrib + i] is a row
+// index into the partial buffer (unit * 16 + row of the token in the unit's tile); grid = (tokens, d / 256).
+__global__ __launch_bounds__(64) void reduce_batch_kernel(const float *partial, const int32_t *contrib,
+                                                          const int32_t *n_contrib, int max_contrib, uint16_t *y, int d,
+                                                          int t_first) {
+  const int t = blockIdx.x, col = blockIdx.y * 256 + threadIdx.x * 4;
+  const int32_t *list = contrib + (size_t)t * max_contrib;
+  const int n = n_contrib[t];
+  f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+  for (int i = 0; i < n; ++i) s += *reinterpret_cast<const f32x4 *>(partial + (size_t)list[i] * d + col);
+  u32x2 o;
+  o.x = (uint32_t)f32_to_bf16_rne(s[0]) | ((uint32_t)f32_to_bf16_rne(s[1]) << 16);
+  o.y = (uint32_t)f32_to_bf16_rne(s[2]) | ((uint32_t)f32_to_bf16_rne(s[3]) << 16);
+  *reinterpret_cast<u32x2 *>(y + (size_t)(t_first + t) * d + col) = o;
+}
+
+template <int CBW>
+constexpr size_t batch_lds_bytes() {
+  return (size_t)16 * (kBatchWaves * 128 * CBW + kXPad) * 2 + 2 * kBatchWaves * 2 * 64 * 16 + kBatchWaves * 256 * 4;
+}
+
+}  // namespace
+
+bool batch_shape_supported(int weight_fmt, int act_fmt, int hidden, int inter, int shared_inter) {
+  return weight_fmt == MOE_W_BF16 && act_fmt == MOE_A_BF16 && (hidden == 1024 || hidden == 2048) && inter % 16 == 0 &&
+         shared_inter % 16 == 0;
+}
+
+hipError_t launch_gate_gemm(const void *x, const void *gate_w, float *logits, int B, int N, int hidden, hipStream_t s) {
+  if (hidden % 32 != 0 || B <= 0 || N <= 0 || N > MOE_MAX_EXPERTS) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(gate_gemm_kernel, dim3((B + 15) / 16), dim3(64 * ((N + 15) / 16)), 0, s,
+                     static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(gate_w), logits, B, N, hidden);
+  return hipGetLastError();
+}
+
+hipError_t launch_route_batch(const RouteParams &p, const float *logits, int B, LayerState *state, moe_route_out_t *out,
+                              hipStream_t s) {
+  hipLaunchKernelGGL(route_batch_kernel, dim3(1), dim3(64), 0, s, p, logits, B, state, out);
+  return hipGetLastError();
+}
+
+// the kernel's LDS (X tile, partial sums, h) exceeds the default limit of a launch: raised once per instantiation
+template <int CBW>
+hipError_t launch_expert_batch_t(const BatchParams &p, hipStream_t s) {
+  static bool raised = false;
+  if (!raised) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&expert_batch_kernel<CBW>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)batch_lds_bytes<CBW>());
+    if (e != hipSuccess) return e;
+    raised = true;
+  }
+  hipLaunchKernelGGL(expert_batch_kernel<CBW>, dim3(p.n_units), dim3(kBatchWaves * kWave), batch_lds_bytes<CBW>(), s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_expert_batch(const BatchParams &p, hipStream_t s) {
+  if (p.n_units <= 0) return hipSuccess;
+  if (p.hidden == 2048) return launch_expert_batch_t<2>(p, s);
+  if (p.hidden == 1024) return launch_expert_batch_t<1>(p, s);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_reduce_batch(const float *partial, const int32_t *contrib, const int32_t *n_contrib, int max_contrib,
+                               void *y, int hidden, int t_first, int n_tokens, hipStream_t s) {
+  if (n_tokens <= 0) return hipSuccess;
+  hipLaunchKernelGGL(reduce_batch_kernel, dim3(n_tokens, hidden / 256), dim3(64), 0, s, partial, contrib, n_contrib,
+                     max_contrib, static_cast<uint16_t *>(y), hidden, t_first);
+  return hipGetLastError();
+}
+
+}  // namespace moe

@@ -5,6 +5,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <algorithm>
 #include <chrono>
 #include <new>
 #include <string>
@@ -94,6 +95,21 @@ struct moe_cache {
   uint32_t seq = 0;
   bool poll = false;
 
+  // prompt phase (moe_route_batch / moe_expert_forward_batch); allocated only for shapes the batched kernels take
+  bool batch_ok = false;
+  float *d_logits_batch = nullptr;          // [kMaxBatch][n_experts]
+  moe_route_out_t *d_route_batch = nullptr; // [kMaxBatch]
+  float *d_bpartial = nullptr;              // [max_units][16][hidden]: the output tile of every unit
+  TokenTile *d_tiles = nullptr, *h_tiles = nullptr;  // device / pinned staging
+  BatchUnit *d_units = nullptr, *h_units = nullptr;
+  int32_t *d_contrib = nullptr, *h_contrib = nullptr;  // [kMaxBatch][max_contrib] partial rows of each token, then
+                                                       // [kMaxBatch] their counts
+  int max_tiles = 0, max_units = 0, max_contrib = 0;
+  std::vector<moe_route_out_t> batch_rec;   // the decisions of the batch routed last, on the host
+  int batch_layer = -1, batch_n = 0;
+  hipEvent_t ev_batch = nullptr;            // compute stream has finished reading the slots (before fills overwrite them)
+  int64_t batch_units_launched = 0, batch_segments = 0;
+
   // optional timing of the expert GEMV launches
   int profiling = 0;      // 0 = off, n = events on every n-th expert launch of a layer's first pass
   uint64_t prof_tick = 0;
@@ -120,6 +136,8 @@ int do_reset(moe_cache_t *c) {
   HIP_TRY(launch_state_init(c->d_state, c->cfg.n_layers, c->d_initial, c->n_initial, c->compute));
   if (c->h_gave_up) __atomic_store_n(c->h_gave_up, 0u, __ATOMIC_RELAXED);
   c->pending_rows = 0;
+  c->batch_layer = -1;
+  c->batch_n = 0;
   const int N = c->cfg.n_experts;
   for (int l = 0; l < c->cfg.n_layers; ++l) {
     for (int i = 0; i < c->n_initial; ++i) {
@@ -283,6 +301,28 @@ int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, 
   HIP_INIT(hipMalloc(&c->d_initial, sizeof(int32_t) * (size_t)L * (b->n_initial > 0 ? b->n_initial : 1)));
   HIP_INIT(hipMalloc(&c->d_partial, sizeof(float) * 2 * (size_t)c->plan.grid * cfg->hidden));
   HIP_INIT(hipMalloc(&c->d_y, sizeof(float) * (size_t)cfg->hidden));
+  c->batch_ok = batch_shape_supported(cfg->weight_fmt, cfg->act_fmt, cfg->hidden, cfg->inter, cfg->shared_inter);
+  if (c->batch_ok) {
+    const int chunks = (cfg->inter + kBatchUnitRecords - 1) / kBatchUnitRecords;
+    const int schunks = (cfg->shared_inter + kBatchUnitRecords - 1) / kBatchUnitRecords;
+    // a tile is 16 tokens of one slot: at most one partly filled tile per slot plus the full ones
+    const int routed_tiles = cfg->capacity + kMaxBatch * cfg->top_k / 16, shared_tiles = kMaxBatch / 16;
+    c->max_tiles = routed_tiles + shared_tiles;
+    c->max_units = routed_tiles * chunks + shared_tiles * schunks;
+    HIP_INIT(hipMalloc(&c->d_logits_batch, sizeof(float) * kMaxBatch * MOE_MAX_EXPERTS));
+    HIP_INIT(hipMalloc(&c->d_route_batch, sizeof(moe_route_out_t) * kMaxBatch));
+    c->max_contrib = cfg->top_k * chunks + schunks;
+    HIP_INIT(hipMalloc(&c->d_bpartial, sizeof(float) * (size_t)c->max_units * 16 * cfg->hidden));
+    HIP_INIT(hipMalloc(&c->d_contrib, sizeof(int32_t) * (size_t)kMaxBatch * (c->max_contrib + 1)));
+    HIP_INIT(hipHostMalloc(reinterpret_cast<void **>(&c->h_contrib), sizeof(int32_t) * (size_t)kMaxBatch * (c->max_contrib + 1),
+                           hipHostMallocDefault));
+    HIP_INIT(hipMalloc(&c->d_tiles, sizeof(TokenTile) * c->max_tiles));
+    HIP_INIT(hipMalloc(&c->d_units, sizeof(BatchUnit) * c->max_units));
+    HIP_INIT(hipHostMalloc(reinterpret_cast<void **>(&c->h_tiles), sizeof(TokenTile) * c->max_tiles, hipHostMallocDefault));
+    HIP_INIT(hipHostMalloc(reinterpret_cast<void **>(&c->h_units), sizeof(BatchUnit) * c->max_units, hipHostMallocDefault));
+    HIP_INIT(hipEventCreateWithFlags(&c->ev_batch, hipEventDisableTiming));
+    c->batch_rec.resize(kMaxBatch);
+  }
   HIP_INIT(hipEventCreateWithFlags(&c->ev_route, hipEventDisableTiming));
   for (int l = 0; l < L; ++l) HIP_INIT(hipEventCreateWithFlags(&c->ev_copy[l], hipEventDisableTiming));
 #undef HIP_INIT
@@ -305,6 +345,16 @@ void moe_cache_destroy(moe_cache_t *c) {
   if (c->d_initial) (void)hipFree(c->d_initial);
   if (c->d_partial) (void)hipFree(c->d_partial);
   if (c->d_y) (void)hipFree(c->d_y);
+  if (c->d_logits_batch) (void)hipFree(c->d_logits_batch);
+  if (c->d_route_batch) (void)hipFree(c->d_route_batch);
+  if (c->d_bpartial) (void)hipFree(c->d_bpartial);
+  if (c->d_contrib) (void)hipFree(c->d_contrib);
+  if (c->h_contrib) (void)hipHostFree(c->h_contrib);
+  if (c->d_tiles) (void)hipFree(c->d_tiles);
+  if (c->d_units) (void)hipFree(c->d_units);
+  if (c->h_tiles) (void)hipHostFree(c->h_tiles);
+  if (c->h_units) (void)hipHostFree(c->h_units);
+  if (c->ev_batch) (void)hipEventDestroy(c->ev_batch);
   if (c->ev_route) (void)hipEventDestroy(c->ev_route);
   for (hipEvent_t e : c->ev_copy)
     if (e) (void)hipEventDestroy(e);
@@ -417,6 +467,7 @@ int moe_route_step(moe_cache_t *c, int32_t layer, const void *x_dev, const float
   if ((x_dev == nullptr) == (logits_dev == nullptr)) return fail(MOE_EINVAL, "exactly one of x_dev and logits_dev must be given");
   if (c->routed[layer]) return fail(MOE_ESTATE, "layer %d: previous route step not followed by moe_expert_forward", layer);
   if (c->pending_rows) return fail(MOE_ESTATE, "an expert output is pending: the next routing call must be moe_stack_route_step");
+  if (c->batch_layer >= 0) return fail(MOE_ESTATE, "a routed batch is pending: call moe_expert_forward_batch first");
   const RouteParams p = make_route_params(c);
   HIP_TRY(launch_route(p, c->gate_w[layer], x_dev, logits_dev, c->d_state + layer, c->d_route + layer,
                        c->h_note_dev + layer, c->compute));
@@ -429,6 +480,7 @@ int moe_stack_route_step(moe_cache_t *c, int32_t layer, float *h_dev, const floa
   if (!h_dev || !x_dev) return fail(MOE_EINVAL, "h_dev or x_dev is NULL");
   if (c->cfg.hidden > kFusedMaxHidden) return fail(MOE_EINVAL, "hidden exceeds %d", kFusedMaxHidden);
   if (c->routed[layer]) return fail(MOE_ESTATE, "layer %d: previous route step not followed by moe_expert_forward", layer);
+  if (c->batch_layer >= 0) return fail(MOE_ESTATE, "a routed batch is pending: call moe_expert_forward_batch first");
   const RouteParams p = make_route_params(c);
   const bool in_launch = !out_host && c->fuse_boundary &&
                          gemv_fused_supported(c->cfg.weight_fmt, c->cfg.act_fmt, c->cfg.hidden, c->plan) && c->cfg.hidden % 64 == 0;
@@ -569,6 +621,165 @@ int moe_expert_forward_static(int32_t weight_fmt, int32_t act_fmt, int32_t hidde
   HIP_TRY(launch_expert_forward_static(weight_fmt, act_fmt, hidden, inter, shared_inter, top_k, slot_pool_dev, slot_bytes,
                                        shared_blob_dev, sel_slot_host, sel_weight_host, x_dev, y_dev,
                                        static_cast<hipStream_t>(stream)));
+  return MOE_OK;
+}
+
+int moe_route_batch(moe_cache_t *c, int32_t layer, const void *x_dev, const float *logits_dev, int32_t n_tokens,
+                    moe_route_out_t *out_host) {
+  if (int rc = check_layer(c, layer)) return rc;
+  if (!c->batch_ok) return fail(MOE_EINVAL, "the prompt-phase kernels take bf16 weights and activations, hidden 1024 or 2048, intermediate sizes that are multiples of 16");
+  if ((x_dev == nullptr) == (logits_dev == nullptr)) return fail(MOE_EINVAL, "exactly one of x_dev and logits_dev must be given");
+  if (n_tokens <= 0 || n_tokens > kMaxBatch) return fail(MOE_EINVAL, "n_tokens must be in 1..%d", kMaxBatch);
+  if (c->routed[layer] || c->pending_rows || c->batch_layer >= 0)
+    return fail(MOE_ESTATE, "layer %d: a routing step, an expert output or a routed batch is pending", layer);
+  const float *z = logits_dev;
+  if (x_dev) {
+    HIP_TRY(launch_gate_gemm(x_dev, c->gate_w[layer], c->d_logits_batch, n_tokens, c->cfg.n_experts, c->cfg.hidden, c->compute));
+    z = c->d_logits_batch;
+  }
+  const RouteParams p = make_route_params(c);
+  HIP_TRY(launch_route_batch(p, z, n_tokens, c->d_state + layer, c->d_route_batch, c->compute));
+  HIP_TRY(hipMemcpyAsync(c->batch_rec.data(), c->d_route_batch, sizeof(moe_route_out_t) * n_tokens, hipMemcpyDeviceToHost,
+                         c->compute));
+  HIP_TRY(hipStreamSynchronize(c->compute));
+  const moe_cache_config_t &g = c->cfg;
+  for (int t = 0; t < n_tokens; ++t)
+    for (int k = 0; k < g.top_k; ++k) {
+      const moe_route_out_t &r = c->batch_rec[t];
+      if (r.sel_expert[k] < 0 || r.sel_expert[k] >= g.n_experts || r.sel_slot[k] < 0 || r.sel_slot[k] >= g.capacity)
+        return fail(MOE_EHIP, "batch routing returned expert %d slot %d out of range", r.sel_expert[k], r.sel_slot[k]);
+    }
+  if (out_host) memcpy(out_host, c->batch_rec.data(), sizeof(moe_route_out_t) * n_tokens);
+  c->batch_layer = layer;
+  c->batch_n = n_tokens;
+  return MOE_OK;
+}
+
+int moe_expert_forward_batch(moe_cache_t *c, int32_t layer, const void *x_dev, void *y_dev, int32_t n_tokens) {
+  if (int rc = check_layer(c, layer)) return rc;
+  if (!x_dev || !y_dev) return fail(MOE_EINVAL, "x_dev or y_dev is NULL");
+  if (c->batch_layer != layer || c->batch_n != n_tokens)
+    return fail(MOE_ESTATE, "layer %d: moe_expert_forward_batch without a preceding moe_route_batch of %d tokens", layer, n_tokens);
+  const moe_cache_config_t &g = c->cfg;
+  const int K = g.top_k, d = g.hidden;
+  const size_t slot_bytes = (size_t)c->slot_layout.total;
+  HIP_TRY(hipEventRecord(c->ev_batch, c->compute));  // whatever read the slots before this call is ahead of this point
+  BatchParams bp{};
+  bp.slot_pool = static_cast<const uint8_t *>(c->slot_pool[layer]);
+  bp.shared_blob = g.shared_inter > 0 ? static_cast<const uint8_t *>(c->shared_blob[layer]) : nullptr;
+  bp.x = static_cast<const uint16_t *>(x_dev);
+  bp.partial = c->d_bpartial;
+  bp.units = c->d_units;
+  bp.tiles = c->d_tiles;
+  bp.hidden = d;
+  bp.inter = g.inter;
+  bp.shared_inter = g.shared_inter;
+  bp.slot_bytes = (int64_t)slot_bytes;
+  // Segments: maximal runs of tokens during which no slot is refilled after a token of the run has read it, so that
+  // all experts a segment needs are in their slots at once.  One expert launch per segment, behind its fills.
+  int t0 = 0;
+  bool first = true;
+  while (t0 < n_tokens) {
+    uint64_t read = 0;
+    int t1 = t0;
+    for (; t1 < n_tokens; ++t1) {
+      const moe_route_out_t &r = c->batch_rec[t1];
+      bool conflict = false;
+      for (int k = 0; k < K; ++k) conflict |= r.miss[k] && ((read >> r.sel_slot[k]) & 1);
+      if (conflict) break;
+      for (int k = 0; k < K; ++k) read |= 1ull << r.sel_slot[k];
+    }
+    // fills of the segment's misses, once the compute stream has finished with the slots' previous contents
+    int n_fill = 0;
+    for (int t = t0; t < t1; ++t) {
+      const moe_route_out_t &r = c->batch_rec[t];
+      for (int k = 0; k < K; ++k) {
+        if (!r.miss[k]) continue;
+        if (n_fill++ == 0) HIP_TRY(hipStreamWaitEvent(c->copy, c->ev_batch, 0));
+        HIP_TRY(hipMemcpyAsync(static_cast<uint8_t *>(c->slot_pool[layer]) + (size_t)r.sel_slot[k] * slot_bytes,
+                               c->host_blob[(size_t)layer * g.n_experts + r.sel_expert[k]], slot_bytes,
+                               hipMemcpyHostToDevice, c->copy));
+        c->bytes_filled[layer] += (int64_t)slot_bytes;
+      }
+    }
+    if (n_fill > 0) {
+      HIP_TRY(hipEventRecord(c->ev_copy[layer], c->copy));
+      HIP_TRY(hipStreamWaitEvent(c->compute, c->ev_copy[layer], 0));
+    }
+    // token tiles per slot and for the shared expert, units per tile; the staging buffers are free again once the
+    // previous segment's copies have been consumed
+    if (!first) HIP_TRY(hipStreamSynchronize(c->compute));
+    first = false;
+    int n_tiles = 0, n_units = 0;
+    const int n_seg = t1 - t0, mc = c->max_contrib;
+    int32_t *n_contrib = c->h_contrib + (size_t)kMaxBatch * mc;  // counts behind the lists
+    for (int i = 0; i < n_seg; ++i) n_contrib[i] = 0;
+    auto add_units = [&](int slot, int rows, int tile) {
+      for (int r0 = 0; r0 < rows; r0 += kBatchUnitRecords)
+        c->h_units[n_units++] = BatchUnit{slot, r0, std::min(kBatchUnitRecords, rows - r0), tile};
+    };
+    // token t (of the whole batch) sits in row `row` of the tile whose units are first_unit .. n_units - 1
+    auto add_contrib = [&](int t, int first_unit, int row) {
+      for (int uidx = first_unit; uidx < n_units; ++uidx) {
+        int32_t &n = n_contrib[t - t0];
+        if (n < mc) c->h_contrib[(size_t)(t - t0) * mc + n] = uidx * 16 + row;
+        ++n;
+      }
+    };
+    for (int s = 0; s < g.capacity; ++s) {
+      if (!((read >> s) & 1)) continue;
+      TokenTile *tile = nullptr;
+      int first_unit = 0;
+      for (int t = t0; t < t1; ++t) {
+        const moe_route_out_t &r = c->batch_rec[t];
+        for (int k = 0; k < K; ++k) {
+          if (r.sel_slot[k] != s) continue;
+          if (!tile || tile->n == 16) {
+            if (n_tiles >= c->max_tiles) return fail(MOE_EHIP, "batch tables overflow (tiles)");
+            tile = &c->h_tiles[n_tiles];
+            memset(tile, 0, sizeof *tile);
+            first_unit = n_units;
+            add_units(s, g.inter, n_tiles++);
+          }
+          add_contrib(t, first_unit, tile->n);
+          tile->tok[tile->n] = t;
+          tile->w[tile->n++] = r.sel_weight[k];
+        }
+      }
+    }
+    if (g.shared_inter > 0) {
+      for (int t = t0; t < t1; t += 16) {
+        if (n_tiles >= c->max_tiles) return fail(MOE_EHIP, "batch tables overflow (tiles)");
+        TokenTile *tile = &c->h_tiles[n_tiles];
+        memset(tile, 0, sizeof *tile);
+        const int first_unit = n_units;
+        add_units(-1, g.shared_inter, n_tiles++);
+        for (int i = t; i < std::min(t + 16, t1); ++i) {
+          add_contrib(i, first_unit, tile->n);
+          tile->tok[tile->n] = i;
+          tile->w[tile->n++] = 1.f;
+        }
+      }
+    }
+    for (int i = 0; i < n_seg; ++i)
+      if (n_contrib[i] > mc) return fail(MOE_EHIP, "batch tables overflow (%d partial rows for one token)", n_contrib[i]);
+    if (n_units > c->max_units) return fail(MOE_EHIP, "batch tables overflow (%d units)", n_units);
+    HIP_TRY(hipMemcpyAsync(c->d_tiles, c->h_tiles, sizeof(TokenTile) * n_tiles, hipMemcpyHostToDevice, c->compute));
+    HIP_TRY(hipMemcpyAsync(c->d_units, c->h_units, sizeof(BatchUnit) * n_units, hipMemcpyHostToDevice, c->compute));
+    HIP_TRY(hipMemcpyAsync(c->d_contrib, c->h_contrib, sizeof(int32_t) * (size_t)kMaxBatch * (mc + 1), hipMemcpyHostToDevice,
+                           c->compute));
+    bp.n_units = n_units;
+    HIP_TRY(launch_expert_batch(bp, c->compute));
+    HIP_TRY(launch_reduce_batch(c->d_bpartial, c->d_contrib, c->d_contrib + (size_t)kMaxBatch * mc, mc, y_dev, d, t0, n_seg,
+                                c->compute));
+    HIP_TRY(hipEventRecord(c->ev_batch, c->compute));
+    c->batch_units_launched += n_units;
+    ++c->batch_segments;
+    t0 = t1;
+  }
+  HIP_TRY(hipStreamSynchronize(c->compute));
+  c->batch_layer = -1;
+  c->batch_n = 0;
   return MOE_OK;
 }
 

@@ -180,9 +180,11 @@ constexpr int kHandoverCopies = 8;
 static_assert(kHandoverCopies * 8 == kWave, "one lane per word of every copy");
 
 // Everything after the logits (Eq. 3 softmax, Eq. 10, Eq. 9, Eq. 2, Eq. 4, Sec. 4.2), run by one wavefront.
+// note == nullptr: nobody on the host waits for this step (a token inside a batch).  carry != nullptr: receives the
+// cache state as this step leaves it, so that the next token of a batch continues from registers.
 __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_s, const CacheRegs &cr, LayerState *st,
                                            moe_route_out_t *out_dev, HostNote *note, uint32_t *rec_s, int lane,
-                                           BoundaryFlags flags = BoundaryFlags{nullptr, 0}) {
+                                           BoundaryFlags flags = BoundaryFlags{nullptr, 0}, CacheRegs *carry = nullptr) {
 #pragma clang fp contract(off)
   const int N = p.n_experts, K = p.top_k, C = p.capacity;
   int my_slot = cr.my_slot, slot_exp = cr.slot_exp;
@@ -326,7 +328,7 @@ __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_
     ew |= (uint64_t)e << (16 + 6 * k);
     sw |= (uint64_t)(s8 & 63u) << (16 + 6 * k);
   }
-  if (lane < 3) {
+  if (note != nullptr && lane < 3) {
     const uint64_t tag = p.seq & 0xffffu;
     const uint64_t w0 = (uint64_t)p.seq | ((uint64_t)n_miss << 32) | ((uint64_t)mm << 40);
     const uint64_t v = lane == 0 ? w0 : (tag | (lane == 1 ? ew : sw));
@@ -374,10 +376,18 @@ __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_
     st->delta_sum = dsum;
     st->count = cnt;
   }
-  if (lane < 6) {
-    const int inc = lane == 0 ? K : lane == 1 ? K - n_miss : lane == 2 ? n_miss : lane == 3 ? cold
-                  : lane == 4 ? evictions : lifetime;
-    (&st->selections)[lane] = cr.counter + inc;
+  const int inc = lane == 0 ? K : lane == 1 ? K - n_miss : lane == 2 ? n_miss : lane == 3 ? cold
+                : lane == 4 ? evictions : lifetime;
+  if (lane < 6) (&st->selections)[lane] = cr.counter + inc;
+  if (carry != nullptr) {
+    carry->my_slot = my_slot;
+    carry->slot_exp = slot_exp;
+    carry->t = cnt;
+    carry->born = born;
+    carry->stamp = stamp;
+    carry->ever_used = ever_used;
+    carry->dsum_prev = dsum;
+    carry->counter = lane < 6 ? cr.counter + inc : 0;
   }
 
   // ---- full decision record in device memory: assembled in LDS, copied out in 16-byte chunks ----

@@ -141,6 +141,13 @@ class MoEDecoder:
     def expert_forward(self, layer, x, y):
         B.moe_expert_forward(self.ctx, layer, _ptr(x), _ptr(y))
 
+    def route_batch(self, layer, x=None, logits=None):
+        n = (x if x is not None else logits).shape[0]
+        return B.moe_route_batch(self.ctx, layer, _ptr(x), _ptr(logits), n)
+
+    def expert_forward_batch(self, layer, x, y):
+        B.moe_expert_forward_batch(self.ctx, layer, _ptr(x), _ptr(y), x.shape[0])
+
     def last_route(self, layer):
         return B.moe_cache_last_route(self.ctx, layer)
 
