@@ -161,53 +161,60 @@ def kernel_time(dec, a, h, x, y, warmup, steps):
 def prompt_phase(pkg, store, cfg, a, dev, n_warm=128, n_timed=256):
     """Prompt phase on the same store: tokens go through the stack layer by layer in batches of B (Sec. 4.5 leaves
     prompt processing to batched kernels; a batch is routed as its tokens in order).  Inputs of every layer are the
-    exogenous AR(1) streams rounded to bf16, as in the parity runs.  Per B: prompt tokens/s through all layers
-    (routing + experts, fills included), the two parts per layer-batch, and the expert part against the HBM
-    roofline, its algorithmic bytes being the distinct experts a batch touches plus the shared expert."""
+    exogenous AR(1) streams rounded to bf16, as in the parity runs.  Per B, at the headline strength (fills
+    included) and miss-free (overwhelming prior: what the kernels themselves reach): prompt tokens/s through all
+    layers, routing and expert part per layer-batch, and the expert part against the HBM roofline - its algorithmic
+    bytes are the distinct experts a batch touches plus the shared expert, each read once."""
     import torch
 
     L, K = cfg.n_layers, cfg.top_k
     xs = a[: n_warm + n_timed].to(cfg.act_dtype)
     out = {}
     for B in (8, 32, 128):
-        dec = pkg.MoEDecoder(store, top_k=cfg.top_k, top_j=cfg.top_j, lam=HEADLINE_LAMBDA, renormalize=cfg.renormalize)
-        y = torch.zeros((B, cfg.hidden), dtype=cfg.act_dtype, device=dev)
-        t_route = t_exp = 0.0
-        n_batches = distinct = 0
-        s0 = None
-        for l in range(L):
-            for t0 in range(0, n_warm + n_timed, B):
-                x = xs[t0:t0 + B, l].contiguous()
-                timed = t0 >= n_warm
-                if timed and s0 is None and l == 0:
-                    s0 = dec.stats(0)
-                torch.cuda.synchronize()
-                t1 = time.perf_counter()
-                recs = dec.route_batch(l, x=x)
-                t2 = time.perf_counter()
-                dec.expert_forward_batch(l, x, y)
-                t3 = time.perf_counter()
-                if timed:
-                    t_route += t2 - t1
-                    t_exp += t3 - t2
-                    n_batches += 1
-                    distinct += len({r.sel_expert[k] for r in recs for k in range(K)})
-        st = dec.stats()
-        dec.close()
-        algo = (distinct / n_batches) * store.blob_bytes + store.shared_bytes
-        exp_us = 1e6 * t_exp / n_batches
-        gbs = algo / (exp_us * 1e-6) / 1e9
-        flops = 2.0 * 3 * cfg.hidden * (B * K * cfg.inter + B * cfg.shared_inter)
-        out[f"B{B}"] = dict(
-            tok_s=round(n_timed / (t_route + t_exp), 1),
-            route_us_per_layer_batch=round(1e6 * t_route / n_batches, 1), expert_us_per_layer_batch=round(exp_us, 1),
-            distinct_experts_per_batch=round(distinct / n_batches, 2), algorithmic_MB_per_layer_batch=round(algo / 1e6, 1),
-            expert_GBps=round(gbs, 1), frac_hbm=round(gbs / HBM_PEAK_GBS, 4),
-            expert_TFLOPs=round(flops / (exp_us * 1e-6) / 1e12, 2), miss_rate_all_tokens=round(st.misses / max(st.selections, 1), 5))
-        log(f"prompt phase B={B}: {out[f'B{B}']['tok_s']} tok/s, route {out[f'B{B}']['route_us_per_layer_batch']} us + "
-            f"experts {exp_us:.1f} us per layer-batch ({gbs:.0f} GB/s of the distinct experts' bytes)")
-    out["note"] = (f"{n_warm} warm-up + {n_timed} timed prompt tokens, lambda={HEADLINE_LAMBDA}; expert time is the wall time of "
-                   "moe_expert_forward_batch (fills, table upload, expert launches, reduction); compare decode: "
+        res = {}
+        for label, lam in (("lambda_0.5", HEADLINE_LAMBDA), ("miss_free", 1e6)):
+            dec = pkg.MoEDecoder(store, top_k=cfg.top_k, top_j=cfg.top_j, lam=lam, renormalize=cfg.renormalize)
+            y = torch.zeros((B, cfg.hidden), dtype=cfg.act_dtype, device=dev)
+            t_route = t_exp = 0.0
+            n_batches = distinct = misses0 = sel0 = 0
+            for l in range(L):
+                for t0 in range(0, n_warm + n_timed, B):
+                    x = xs[t0:t0 + B, l].contiguous()
+                    if t0 == n_warm:
+                        s = dec.stats(l)
+                        misses0 += s.misses
+                        sel0 += s.selections
+                    torch.cuda.synchronize()
+                    t1 = time.perf_counter()
+                    recs = dec.route_batch(l, x=x)
+                    t2 = time.perf_counter()
+                    dec.expert_forward_batch(l, x, y)
+                    t3 = time.perf_counter()
+                    if t0 >= n_warm:
+                        t_route += t2 - t1
+                        t_exp += t3 - t2
+                        n_batches += 1
+                        distinct += len({r.sel_expert[k] for r in recs for k in range(K)})
+            st = dec.stats()
+            dec.close()
+            del dec
+            algo = (distinct / n_batches) * store.blob_bytes + store.shared_bytes
+            exp_us = 1e6 * t_exp / n_batches
+            gbs = algo / (exp_us * 1e-6) / 1e9
+            flops = 2.0 * 3 * cfg.hidden * (B * K * cfg.inter + B * cfg.shared_inter)
+            res[label] = dict(
+                tok_s=round(n_timed / (t_route + t_exp), 1),
+                route_us_per_layer_batch=round(1e6 * t_route / n_batches, 1), expert_us_per_layer_batch=round(exp_us, 1),
+                us_per_token_layer=round(1e6 * (t_route + t_exp) / n_batches / B, 2),
+                miss_rate=round((st.misses - misses0) / max(st.selections - sel0, 1), 5),
+                distinct_experts_per_batch=round(distinct / n_batches, 2),
+                algorithmic_MB_per_layer_batch=round(algo / 1e6, 1), expert_GBps=round(gbs, 1),
+                frac_hbm=round(gbs / HBM_PEAK_GBS, 4), expert_TFLOPs=round(flops / (exp_us * 1e-6) / 1e12, 2))
+            log(f"prompt phase B={B} {label}: {res[label]['tok_s']} tok/s, route {res[label]['route_us_per_layer_batch']} us + "
+                f"experts {exp_us:.1f} us per layer-batch ({gbs:.0f} GB/s of the distinct experts' bytes)")
+        out[f"B{B}"] = res
+    out["note"] = (f"{n_warm} warm-up + {n_timed} timed prompt tokens per layer; expert time is the wall time of "
+                   "moe_expert_forward_batch (fills, table upload, expert launches, reduction); decode for comparison: "
                    "steady_state.per_layer_us per token and layer")
     return out
 
@@ -435,6 +442,7 @@ def main():
         r2 = timed_run(dec2, a, h, x, y, OWN_WARMUP, own_steps)
         us2, n2, _ = kernel_time(dec2, a, h, x, y, OWN_WARMUP, own_steps)
         dec2.close()
+        del dec2
         alone = dict(tok_s=round(r2["tok_s"], 2), expert_kernel_us=round(us2, 3), launches=n2,
                      GBps=round(algo_bytes / (us2 * 1e-6) / 1e9, 1) if us2 > 0 else 0.0,
                      frac=round(algo_bytes / (us2 * 1e-6) / 1e9 / HBM_PEAK_GBS, 4) if us2 > 0 else 0.0)
@@ -446,6 +454,7 @@ def main():
         dec3 = pkg.MoEDecoder(store, top_k=cfg.top_k, top_j=2, lam=HEADLINE_LAMBDA, renormalize=cfg.renormalize)
         r3 = timed_run(dec3, a, h, x, y, OWN_WARMUP, own_steps)
         dec3.close()
+        del dec3
         top_j_run = dict(top_j=2, tok_s=round(r3["tok_s"], 2), miss_rate=round(r3["miss_rate"], 5),
                          mean_lifetime_tokens=round(r3["mean_lifetime"], 2))
         log(f"top_j=2: {r3['tok_s']:.1f} tok/s, miss rate {r3['miss_rate']:.4f}")
@@ -497,7 +506,7 @@ def main():
                      f"shared_I={cfg.shared_inter} top{cfg.top_k} cache={cfg.capacity}/{cfg.n_experts} rho={cfg.rho}")
     others = None
     if not args.no_others and args.workload == "c2_qwen_bf16" and not args.layers and not args.tokens:
-        del dec, store, a
+        del dec, store, a, h, x, y
         release_memory()
         others = {}
         # full depth each; the token counts keep the whole bench within minutes (a miss of the Mixtral-shaped stack
