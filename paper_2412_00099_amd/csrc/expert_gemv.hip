@@ -347,13 +347,28 @@ __global__ __launch_bounds__(256) void reduce_glue_kernel(const float *partial, 
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   const int chunk = (n_partial + 15) / 16;
   const int b0 = rg * chunk, b1 = min(n_partial, b0 + chunk);
+  if (chunk == 16 && b1 - b0 == 16) {
+    // the usual case (one partial row per compute unit of a 256-unit device): all sixteen rows requested at once,
+    // added in the same order as below
+    float4 t[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) t[i] = *reinterpret_cast<const float4 *>(partial + (int64_t)(b0 + i) * d + col);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      acc.x += t[i].x;
+      acc.y += t[i].y;
+      acc.z += t[i].z;
+      acc.w += t[i].w;
+    }
+  } else {
 #pragma unroll 8
-  for (int b = b0; b < b1; ++b) {
-    const float4 t = *reinterpret_cast<const float4 *>(partial + (int64_t)b * d + col);
-    acc.x += t.x;
-    acc.y += t.y;
-    acc.z += t.z;
-    acc.w += t.w;
+    for (int b = b0; b < b1; ++b) {
+      const float4 t = *reinterpret_cast<const float4 *>(partial + (int64_t)b * d + col);
+      acc.x += t.x;
+      acc.y += t.y;
+      acc.z += t.z;
+      acc.w += t.w;
+    }
   }
   // (keeps the two early loads where they are: without a use here they are moved into the branch below)
   asm volatile("" ::"v"(hv.x), "v"(hv.y), "v"(hv.z), "v"(hv.w), "v"(av.x), "v"(av.y), "v"(av.z), "v"(av.w));

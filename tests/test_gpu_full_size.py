@@ -33,9 +33,11 @@ def test_c2_full_layer_shape_coupled_stack():
     assert misses >= cfg.top_k * cfg.n_layers
 
 
-def test_c3_full_layer_shape():
-    cfg = CONFIGS["c3_olmoe_bf16"].with_(n_layers=1)
-    print("case c3 full per-layer shape, 1 layer, 24 tokens", flush=True)
+@pytest.mark.parametrize("capacity", [16, 32, 48])
+def test_c3_full_layer_shape(capacity):
+    """The three cache sizes of the workload (cache-size ablation, Sec. 4.8) at the full layer shape."""
+    cfg = CONFIGS["c3_olmoe_bf16"].with_(n_layers=1, capacity=capacity)
+    print(f"case c3 full per-layer shape, cache {capacity}, 1 layer, 24 tokens", flush=True)
     free_run(cfg, 0.5, 24, top_j=0, check_outputs_every=11, deferred=True)
 
 

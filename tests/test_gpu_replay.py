@@ -98,3 +98,38 @@ def test_c4_full_length():
 def test_c5_full_length():
     cfg = CONFIGS["c5_mixtral_int8"].with_(inter=64)
     replay_case(cfg, 0.5, cfg.n_tokens)
+
+
+def test_c2_prompt_phase_full_length():
+    """The prompt phase at the benchmarked shape: all 24 layers, 1024 tokens in batches of 128, each layer fed its
+    own exogenous stream (the batched path has no residual glue).  The device's logits of every token are replayed
+    through the oracle router token by token: all decisions of all 24 x 1024 routing steps, the final tables and
+    the counters are identical - a batch is its tokens in order."""
+    from oracle import prompt
+
+    cfg = CONFIGS["c2_qwen_bf16"]
+    L, N, K, C, T, B = cfg.n_layers, cfg.n_experts, cfg.top_k, cfg.capacity, cfg.n_tokens, 128
+    print(f"case prompt replay {cfg.name} L={L} T={T} B={B}", flush=True)
+    store, dec = build(cfg, lam=0.5)
+    xs = workloads.ar1_stream(cfg, T, device=DEV).to(cfg.act_dtype)
+    y = torch.zeros((B, cfg.hidden), dtype=cfg.act_dtype, device=DEV)
+    total = 0
+    for l in range(L):
+        router = routing.CachePriorRouter(N, K, C, 0.5, cfg.top_j, cfg.renormalize)
+        for t0 in range(0, T, B):
+            x = xs[t0:t0 + B, l].contiguous()
+            recs = dec.route_batch(l, x=x)
+            dec.expert_forward_batch(l, x, y)
+            z = np.array([r.logits[:N] for r in recs], np.float32)
+            refs = prompt.route_batch(router, z)
+            for j, (r, ref) in enumerate(zip(recs, refs)):
+                ctx = f"layer {l} token {t0 + j}"
+                assert list(r.sel_expert[:K]) == ref.sel.tolist(), ctx
+                assert list(r.sel_slot[:K]) == ref.slot and [bool(m) for m in r.miss[:K]] == ref.miss, ctx
+                assert list(r.evicted[:K]) == ref.evicted and np.float32(r.delta) == ref.delta, ctx
+        check_tables(dec, l, router, N, C)
+        total += router.stats.misses
+    st = dec.stats()
+    assert st.misses == total and st.selections == T * L * K and st.bytes_filled == total * store.blob_bytes
+    print(f"prompt replay: {T * L} routing steps identical, misses {total} (rate {total / (T * L * K):.5f})", flush=True)
+    dec.close()
