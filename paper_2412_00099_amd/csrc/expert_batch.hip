@@ -6,7 +6,7 @@
 // weights-stationary small GEMM per expert over the tokens routed to it (Eq. 1), both on the matrix cores.
 //
 //  gate_gemm_kernel    logits[B, N] = X[B, d] W_gate[N, d]^T, bf16 inputs, fp32 accumulation
-//                      (v_mfma_f32_16x16x32_bf16: a 16-token x 16-expert tile per wavefront).
+//                      (v_mfma_f32_16x16x32_bf16: a 16-token x 16-expert tile per four wavefronts, which split d).
 //  route_batch_kernel  one wavefront walks the tokens in order through rt::route_wave, the cache state carried in
 //                      registers from token to token; one routing record per token.
 //  expert_batch_kernel one workgroup (8 wavefronts) per unit = (expert blob, up to 128 consecutive records, tile of up
@@ -38,18 +38,44 @@ __device__ __forceinline__ f32x4 mfma_f32(float a, float b, f32x4 c) {
 }
 
 // ---- gate logits of the batch -------------------------------------------------------------------
-// grid = token tiles of 16, block = 64 * expert tiles of 16.  A-operand lane l: token l % 16, columns k0 + 8 (l / 16)
-// .. + 8; B-operand lane l: expert n0 + l % 16, the same columns; result lane l: expert n0 + l % 16, tokens
-// 4 (l / 16) + v.  Rows past the last token / expert re-read the last one and are not stored.
-__global__ __launch_bounds__(256) void gate_gemm_kernel(const uint16_t *x, const uint16_t *gate_w, float *logits, int B,
-                                                       int N, int d) {
+// grid = token tiles of 16, block = (expert tiles of 16) x kGateSplit wavefronts: wavefront (et, ks) multiplies the
+// ks-th part of the hidden dimension, all its operands requested eight steps at a time; the parts are added through
+// LDS in a fixed order.  A-operand lane l: token l % 16, columns k0 + 8 (l / 16) .. + 8; B-operand lane l: expert
+// n0 + l % 16, the same columns; result lane l: expert n0 + l % 16, tokens 4 (l / 16) + v.  Rows past the last token /
+// expert re-read the last one and are not stored.
+constexpr int kGateSplit = 4;
+__global__ __launch_bounds__(1024) void gate_gemm_kernel(const uint16_t *x, const uint16_t *gate_w, float *logits, int B,
+                                                        int N, int d) {
+  __shared__ f32x4 part[kGateSplit][MOE_MAX_EXPERTS / 16][kWave];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int t0 = blockIdx.x * 16, n0 = wave * 16;
+  const int et = wave / kGateSplit, ks = wave % kGateSplit;
+  const int t0 = blockIdx.x * 16, n0 = et * 16;
   const int tok = min(t0 + (lane & 15), B - 1), exp = min(n0 + (lane & 15), N - 1);
-  const u32x4 *xa = reinterpret_cast<const u32x4 *>(x + (size_t)tok * d) + (lane >> 4);
-  const u32x4 *wb = reinterpret_cast<const u32x4 *>(gate_w + (size_t)exp * d) + (lane >> 4);
+  const int steps = d / (32 * kGateSplit);  // a multiple of 8 (the launcher checks)
+  const u32x4 *xa = reinterpret_cast<const u32x4 *>(x + (size_t)tok * d) + (lane >> 4) + (size_t)ks * steps * 4;
+  const u32x4 *wb = reinterpret_cast<const u32x4 *>(gate_w + (size_t)exp * d) + (lane >> 4) + (size_t)ks * steps * 4;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  for (int s = 0; s < d / 32; ++s) acc = mfma_bf16(xa[s * 4], wb[s * 4], acc);
+  for (int s0 = 0; s0 < steps; s0 += 8) {
+    u32x4 a[8], b[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      a[s] = xa[(s0 + s) * 4];
+      b[s] = wb[(s0 + s) * 4];
+    }
+#pragma unroll
+    for (int s = 0; s < 8; ++s) acc = mfma_bf16(a[s], b[s], acc);
+  }
+  part[ks][et][lane] = acc;
+  __syncthreads();
+  if (ks != 0) return;
+#pragma unroll
+  for (int q = 1; q < kGateSplit; ++q) {
+    const f32x4 t = part[q][et][lane];
+    acc[0] += t[0];
+    acc[1] += t[1];
+    acc[2] += t[2];
+    acc[3] += t[3];
+  }
   const int e = n0 + (lane & 15);
 #pragma unroll
   for (int v = 0; v < 4; ++v) {
@@ -59,19 +85,26 @@ __global__ __launch_bounds__(256) void gate_gemm_kernel(const uint16_t *x, const
 }
 
 // ---- routing of the batch, token by token ---------------------------------------------------------
-__global__ __launch_bounds__(64) void route_batch_kernel(RouteParams p, const float *logits, int B, LayerState *st,
-                                                         moe_route_out_t *out) {
-  __shared__ float z_s[MOE_MAX_EXPERTS];
+// All logits of the batch are brought into LDS first (by four wavefronts), and the cache state goes back to device
+// memory after the last token only: the walk itself then issues no load, so nothing in it waits for memory (the
+// records it stores are not waited for).
+constexpr int kRouteBatchThreads = 256;
+__global__ __launch_bounds__(kRouteBatchThreads) void route_batch_kernel(RouteParams p, const float *logits, int B,
+                                                                         LayerState *st, moe_route_out_t *out) {
+  __shared__ float z_all[kMaxBatch * MOE_MAX_EXPERTS];
   __shared__ __attribute__((aligned(16))) uint32_t rec_s[rt::kRecWords];
-  const int lane = threadIdx.x;
-  rt::CacheRegs cr = rt::load_cache_regs(st, lane, p.n_experts, p.capacity);
+  const int lane = threadIdx.x & 63, N = p.n_experts;
+  rt::CacheRegs cr = rt::load_cache_regs(st, lane, N, p.capacity);  // (every wavefront: on its way during the fill)
+  for (int i = threadIdx.x; i < B * N; i += kRouteBatchThreads) {
+    const int t = i / N;
+    z_all[t * MOE_MAX_EXPERTS + (i - t * N)] = logits[i];
+  }
+  __syncthreads();
+  if (threadIdx.x >= 64) return;
   for (int t = 0; t < B; ++t) {
-    z_s[lane] = lane < p.n_experts ? logits[(size_t)t * p.n_experts + lane] : 0.f;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     rt::CacheRegs next;
-    rt::route_wave(p, z_s, cr, st, out + t, nullptr, rec_s, lane, rt::BoundaryFlags{nullptr, 0}, &next);
+    rt::route_wave(p, z_all + t * MOE_MAX_EXPERTS, cr, st, out + t, nullptr, rec_s, lane, rt::BoundaryFlags{nullptr, 0},
+                   &next, t == B - 1);
     cr = next;
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -249,15 +282,16 @@ bool batch_shape_supported(int weight_fmt, int act_fmt, int hidden, int inter, i
 }
 
 hipError_t launch_gate_gemm(const void *x, const void *gate_w, float *logits, int B, int N, int hidden, hipStream_t s) {
-  if (hidden % 32 != 0 || B <= 0 || N <= 0 || N > MOE_MAX_EXPERTS) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(gate_gemm_kernel, dim3((B + 15) / 16), dim3(64 * ((N + 15) / 16)), 0, s,
+  if (hidden % (32 * kGateSplit * 8) != 0 || B <= 0 || N <= 0 || N > MOE_MAX_EXPERTS) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(gate_gemm_kernel, dim3((B + 15) / 16), dim3(64 * kGateSplit * ((N + 15) / 16)), 0, s,
                      static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(gate_w), logits, B, N, hidden);
   return hipGetLastError();
 }
 
 hipError_t launch_route_batch(const RouteParams &p, const float *logits, int B, LayerState *state, moe_route_out_t *out,
                               hipStream_t s) {
-  hipLaunchKernelGGL(route_batch_kernel, dim3(1), dim3(64), 0, s, p, logits, B, state, out);
+  if (B <= 0 || B > kMaxBatch) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(route_batch_kernel, dim3(1), dim3(kRouteBatchThreads), 0, s, p, logits, B, state, out);
   return hipGetLastError();
 }
 

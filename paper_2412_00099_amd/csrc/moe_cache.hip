@@ -98,14 +98,14 @@ struct moe_cache {
   // prompt phase (moe_route_batch / moe_expert_forward_batch); allocated only for shapes the batched kernels take
   bool batch_ok = false;
   float *d_logits_batch = nullptr;          // [kMaxBatch][n_experts]
-  moe_route_out_t *d_route_batch = nullptr; // [kMaxBatch]
+  moe_route_out_t *batch_rec = nullptr;      // [kMaxBatch] the decisions of the batch routed last: pinned host memory
+  moe_route_out_t *batch_rec_dev = nullptr;  // the routing kernel's view of it (the records go straight to the host)
   float *d_bpartial = nullptr;              // [max_units][16][hidden]: the output tile of every unit
   TokenTile *d_tiles = nullptr, *h_tiles = nullptr;  // device / pinned staging
   BatchUnit *d_units = nullptr, *h_units = nullptr;
   int32_t *d_contrib = nullptr, *h_contrib = nullptr;  // [kMaxBatch][max_contrib] partial rows of each token, then
                                                        // [kMaxBatch] their counts
   int max_tiles = 0, max_units = 0, max_contrib = 0;
-  std::vector<moe_route_out_t> batch_rec;   // the decisions of the batch routed last, on the host
   int batch_layer = -1, batch_n = 0;
   hipEvent_t ev_batch = nullptr;            // compute stream has finished reading the slots (before fills overwrite them)
   int64_t batch_units_launched = 0, batch_segments = 0;
@@ -310,7 +310,8 @@ int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, 
     c->max_tiles = routed_tiles + shared_tiles;
     c->max_units = routed_tiles * chunks + shared_tiles * schunks;
     HIP_INIT(hipMalloc(&c->d_logits_batch, sizeof(float) * kMaxBatch * MOE_MAX_EXPERTS));
-    HIP_INIT(hipMalloc(&c->d_route_batch, sizeof(moe_route_out_t) * kMaxBatch));
+    HIP_INIT(hipHostMalloc(reinterpret_cast<void **>(&c->batch_rec), sizeof(moe_route_out_t) * kMaxBatch, hipHostMallocMapped));
+    HIP_INIT(hipHostGetDevicePointer(reinterpret_cast<void **>(&c->batch_rec_dev), c->batch_rec, 0));
     c->max_contrib = cfg->top_k * chunks + schunks;
     HIP_INIT(hipMalloc(&c->d_bpartial, sizeof(float) * (size_t)c->max_units * 16 * cfg->hidden));
     HIP_INIT(hipMalloc(&c->d_contrib, sizeof(int32_t) * (size_t)kMaxBatch * (c->max_contrib + 1)));
@@ -321,7 +322,6 @@ int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, 
     HIP_INIT(hipHostMalloc(reinterpret_cast<void **>(&c->h_tiles), sizeof(TokenTile) * c->max_tiles, hipHostMallocDefault));
     HIP_INIT(hipHostMalloc(reinterpret_cast<void **>(&c->h_units), sizeof(BatchUnit) * c->max_units, hipHostMallocDefault));
     HIP_INIT(hipEventCreateWithFlags(&c->ev_batch, hipEventDisableTiming));
-    c->batch_rec.resize(kMaxBatch);
   }
   HIP_INIT(hipEventCreateWithFlags(&c->ev_route, hipEventDisableTiming));
   for (int l = 0; l < L; ++l) HIP_INIT(hipEventCreateWithFlags(&c->ev_copy[l], hipEventDisableTiming));
@@ -346,7 +346,7 @@ void moe_cache_destroy(moe_cache_t *c) {
   if (c->d_partial) (void)hipFree(c->d_partial);
   if (c->d_y) (void)hipFree(c->d_y);
   if (c->d_logits_batch) (void)hipFree(c->d_logits_batch);
-  if (c->d_route_batch) (void)hipFree(c->d_route_batch);
+  if (c->batch_rec) (void)hipHostFree(c->batch_rec);
   if (c->d_bpartial) (void)hipFree(c->d_bpartial);
   if (c->d_contrib) (void)hipFree(c->d_contrib);
   if (c->h_contrib) (void)hipHostFree(c->h_contrib);
@@ -638,9 +638,7 @@ int moe_route_batch(moe_cache_t *c, int32_t layer, const void *x_dev, const floa
     z = c->d_logits_batch;
   }
   const RouteParams p = make_route_params(c);
-  HIP_TRY(launch_route_batch(p, z, n_tokens, c->d_state + layer, c->d_route_batch, c->compute));
-  HIP_TRY(hipMemcpyAsync(c->batch_rec.data(), c->d_route_batch, sizeof(moe_route_out_t) * n_tokens, hipMemcpyDeviceToHost,
-                         c->compute));
+  HIP_TRY(launch_route_batch(p, z, n_tokens, c->d_state + layer, c->batch_rec_dev, c->compute));
   HIP_TRY(hipStreamSynchronize(c->compute));
   const moe_cache_config_t &g = c->cfg;
   for (int t = 0; t < n_tokens; ++t)
@@ -649,7 +647,7 @@ int moe_route_batch(moe_cache_t *c, int32_t layer, const void *x_dev, const floa
       if (r.sel_expert[k] < 0 || r.sel_expert[k] >= g.n_experts || r.sel_slot[k] < 0 || r.sel_slot[k] >= g.capacity)
         return fail(MOE_EHIP, "batch routing returned expert %d slot %d out of range", r.sel_expert[k], r.sel_slot[k]);
     }
-  if (out_host) memcpy(out_host, c->batch_rec.data(), sizeof(moe_route_out_t) * n_tokens);
+  if (out_host) memcpy(out_host, c->batch_rec, sizeof(moe_route_out_t) * n_tokens);
   c->batch_layer = layer;
   c->batch_n = n_tokens;
   return MOE_OK;

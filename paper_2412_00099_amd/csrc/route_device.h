@@ -181,10 +181,12 @@ static_assert(kHandoverCopies * 8 == kWave, "one lane per word of every copy");
 
 // Everything after the logits (Eq. 3 softmax, Eq. 10, Eq. 9, Eq. 2, Eq. 4, Sec. 4.2), run by one wavefront.
 // note == nullptr: nobody on the host waits for this step (a token inside a batch).  carry != nullptr: receives the
-// cache state as this step leaves it, so that the next token of a batch continues from registers.
+// cache state as this step leaves it, so that the next token of a batch continues from registers; store_state =
+// false then leaves the state in device memory as it was (only the last token of a batch writes it back).
 __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_s, const CacheRegs &cr, LayerState *st,
                                            moe_route_out_t *out_dev, HostNote *note, uint32_t *rec_s, int lane,
-                                           BoundaryFlags flags = BoundaryFlags{nullptr, 0}, CacheRegs *carry = nullptr) {
+                                           BoundaryFlags flags = BoundaryFlags{nullptr, 0}, CacheRegs *carry = nullptr,
+                                           bool store_state = true) {
 #pragma clang fp contract(off)
   const int N = p.n_experts, K = p.top_k, C = p.capacity;
   int my_slot = cr.my_slot, slot_exp = cr.slot_exp;
@@ -365,20 +367,22 @@ __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_
   }
 
   // ---- state back to device memory ------------------------------------------------------------
-  if (active) {
-    st->expert_slot[lane] = my_slot;
-    st->stamp[lane] = stamp;
-    st->born[lane] = born;
-  }
-  if (lane < C) st->slot_expert[lane] = slot_exp;
-  if (lane == 0) {
-    st->ever_used = ever_used;
-    st->delta_sum = dsum;
-    st->count = cnt;
-  }
   const int inc = lane == 0 ? K : lane == 1 ? K - n_miss : lane == 2 ? n_miss : lane == 3 ? cold
                 : lane == 4 ? evictions : lifetime;
-  if (lane < 6) (&st->selections)[lane] = cr.counter + inc;
+  if (store_state) {
+    if (active) {
+      st->expert_slot[lane] = my_slot;
+      st->stamp[lane] = stamp;
+      st->born[lane] = born;
+    }
+    if (lane < C) st->slot_expert[lane] = slot_exp;
+    if (lane == 0) {
+      st->ever_used = ever_used;
+      st->delta_sum = dsum;
+      st->count = cnt;
+    }
+    if (lane < 6) (&st->selections)[lane] = cr.counter + inc;
+  }
   if (carry != nullptr) {
     carry->my_slot = my_slot;
     carry->slot_exp = slot_exp;
