@@ -7,8 +7,9 @@
 //
 //  gate_gemm_kernel    logits[B, N] = X[B, d] W_gate[N, d]^T, bf16 inputs, fp32 accumulation
 //                      (v_mfma_f32_16x16x32_bf16: a 16-token x 16-expert tile per four wavefronts, which split d).
-//  route_batch_kernel  one wavefront walks the tokens in order through rt::route_wave, the cache state carried in
-//                      registers from token to token; one routing record per token.
+//  route_batch_kernel  sixteen wavefronts route sixteen tokens at a time through rt::route_wave against the current
+//                      cache state; a token that misses an expert is routed alone and updates the state (see there);
+//                      one routing record per token.
 //  expert_batch_kernel one workgroup (8 wavefronts) per unit = (expert blob, up to 128 consecutive records, tile of up
 //                      to 16 tokens routed to that expert).  Per block of 16 records: all its weights are requested
 //                      at once; g, u = W_gate/up block x X tile^T with the 16x16x32 bf16 MFMA, the hidden dimension
@@ -84,31 +85,138 @@ __global__ __launch_bounds__(1024) void gate_gemm_kernel(const uint16_t *x, cons
   }
 }
 
-// ---- routing of the batch, token by token ---------------------------------------------------------
-// All logits of the batch are brought into LDS first (by four wavefronts), and the cache state goes back to device
-// memory after the last token only: the walk itself then issues no load, so nothing in it waits for memory (the
-// records it stores are not waited for).
-constexpr int kRouteBatchThreads = 256;
-__global__ __launch_bounds__(kRouteBatchThreads) void route_batch_kernel(RouteParams p, const float *logits, int B,
+// ---- routing of the batch ---------------------------------------------------------------------------
+// The decisions are those of the tokens routed one after the other (the cache mask of Sec. 3.3 is the state after the
+// previous token), but a token that misses nothing leaves the cache as it found it except for the recency stamps of
+// its experts - and stamps only matter to a later miss.  So sixteen wavefronts route the next sixteen tokens at once
+// against the current state (rt::route_wave, unchanged, its record kept in LDS); the tokens up to the first one that
+// misses an expert are accepted as they are: records copied out, stamps merged (a later token's stamp is larger, so
+// the merge is a maximum), counters advanced.  The token with the miss is then routed by one wavefront against the
+// merged state, which it updates, and the window moves on behind it.  What does not depend on the cache - Eq. 10's
+// running sum of logit ranges - is prepared for all tokens first (the same additions in the same order).
+// Miss-free batches cost one round per sixteen tokens; a miss costs one extra round.
+constexpr int kRouteWaves = 16;
+struct BatchCacheState {  // LayerState's tables while the batch is routed (LDS)
+  int32_t my_slot[MOE_MAX_EXPERTS], slot_exp[MOE_MAX_EXPERTS], born[MOE_MAX_EXPERTS];
+  long long stamp[MOE_MAX_EXPERTS];
+  long long counter[6];
+  uint64_t ever_used;
+  int32_t count0;  // tokens routed before this batch
+};
+
+__device__ __forceinline__ rt::CacheRegs batch_cache_regs(const BatchCacheState &s, int lane, int t, float dsum_prev) {
+  rt::CacheRegs cr;
+  cr.my_slot = s.my_slot[lane];
+  cr.slot_exp = s.slot_exp[lane];
+  cr.born = s.born[lane];
+  cr.stamp = s.stamp[lane];
+  cr.counter = lane < 6 ? s.counter[lane] : 0;
+  cr.ever_used = s.ever_used;
+  cr.t = s.count0 + t;
+  cr.dsum_prev = dsum_prev;
+  return cr;
+}
+
+__global__ __launch_bounds__(kRouteWaves *kWave) void route_batch_kernel(RouteParams p, const float *logits, int B,
                                                                          LayerState *st, moe_route_out_t *out) {
   __shared__ float z_all[kMaxBatch * MOE_MAX_EXPERTS];
-  __shared__ __attribute__((aligned(16))) uint32_t rec_s[rt::kRecWords];
-  const int lane = threadIdx.x & 63, N = p.n_experts;
-  rt::CacheRegs cr = rt::load_cache_regs(st, lane, N, p.capacity);  // (every wavefront: on its way during the fill)
-  for (int i = threadIdx.x; i < B * N; i += kRouteBatchThreads) {
+  __shared__ float range_s[kMaxBatch];
+  __shared__ float dsum_s[kMaxBatch + 1];  // Eq. 10's sum before token t
+  __shared__ __attribute__((aligned(16))) uint32_t asm_s[kRouteWaves][rt::kRecWords];    // route_wave's work buffer
+  __shared__ __attribute__((aligned(16))) uint32_t stage_s[kRouteWaves][rt::kRecWords];  // a wavefront's record
+  __shared__ BatchCacheState cs;
+  __shared__ int first_miss_s;
+  const int tid = threadIdx.x, lane = tid & 63, N = p.n_experts, K = p.top_k;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+  if (wave == 0) {
+    const rt::CacheRegs cr = rt::load_cache_regs(st, lane, N, p.capacity);
+    cs.my_slot[lane] = cr.my_slot;
+    cs.slot_exp[lane] = cr.slot_exp;
+    cs.born[lane] = cr.born;
+    cs.stamp[lane] = cr.stamp;
+    if (lane < 6) cs.counter[lane] = cr.counter;
+    if (lane == 0) {
+      cs.ever_used = cr.ever_used;
+      cs.count0 = cr.t;
+      dsum_s[0] = cr.dsum_prev;
+    }
+  }
+  for (int i = tid; i < B * N; i += kRouteWaves * kWave) {
     const int t = i / N;
     z_all[t * MOE_MAX_EXPERTS + (i - t * N)] = logits[i];
   }
   __syncthreads();
-  if (threadIdx.x >= 64) return;
-  for (int t = 0; t < B; ++t) {
-    rt::CacheRegs next;
-    rt::route_wave(p, z_all + t * MOE_MAX_EXPERTS, cr, st, out + t, nullptr, rec_s, lane, rt::BoundaryFlags{nullptr, 0},
-                   &next, t == B - 1);
-    cr = next;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  for (int t = wave; t < B; t += kRouteWaves) {
+    const bool active = lane < N;
+    const float z = active ? z_all[t * MOE_MAX_EXPERTS + lane] : 0.f;
+    const float r = rt::wave_max(active ? z : -INFINITY) - rt::wave_min(active ? z : INFINITY);
+    if (lane == 0) range_s[t] = r;
+  }
+  __syncthreads();
+  if (tid == 0) {
+#pragma clang fp contract(off)
+    float acc = dsum_s[0];
+    for (int t = 0; t < B; ++t) {
+      acc = acc + range_s[t];
+      dsum_s[t + 1] = acc;
+    }
+  }
+
+  int t0 = 0;
+  while (t0 < B) {  // (t0 and everything that steers the loop is the same in every thread)
+    if (tid == 0) first_miss_s = B;
+    __syncthreads();
+    const int t = t0 + wave;
+    rt::CacheRegs cr, next;
+    if (t < B) {
+      cr = batch_cache_regs(cs, lane, t, dsum_s[t]);
+      int n_miss = 0;
+      rt::route_wave(p, z_all + t * MOE_MAX_EXPERTS, cr, st, reinterpret_cast<moe_route_out_t *>(stage_s[wave]), nullptr,
+                     asm_s[wave], lane, rt::BoundaryFlags{nullptr, 0}, &next, false, &n_miss);
+      if (n_miss > 0 && lane == 0) atomicMin(&first_miss_s, t);
+    }
+    __syncthreads();
+    const int window_end = min(t0 + kRouteWaves, B);
+    const int fm = min(first_miss_s, window_end);  // tokens t0 .. fm-1 stand as they are
+    if (t < fm) {
+      if (lane < rt::kRecWords / 4)
+        reinterpret_cast<u32x4 *>(out + t)[lane] = reinterpret_cast<const u32x4 *>(stage_s[wave])[lane];
+      if (lane < N && next.stamp != cr.stamp) atomicMax(&cs.stamp[lane], (long long)next.stamp);
+    }
+    if (tid < 2) cs.counter[tid] += (long long)K * (fm - t0);  // selections and hits
+    __syncthreads();
+    t0 = fm;
+    if (fm < window_end) {
+      // token fm misses at least one expert: routed against the merged state, which it updates
+      if (wave == 0) {
+        cr = batch_cache_regs(cs, lane, fm, dsum_s[fm]);
+        rt::route_wave(p, z_all + fm * MOE_MAX_EXPERTS, cr, st, out + fm, nullptr, asm_s[0], lane,
+                       rt::BoundaryFlags{nullptr, 0}, &next, false);
+        cs.my_slot[lane] = next.my_slot;
+        cs.slot_exp[lane] = next.slot_exp;
+        cs.born[lane] = next.born;
+        cs.stamp[lane] = next.stamp;
+        if (lane < 6) cs.counter[lane] = next.counter;
+        if (lane == 0) cs.ever_used = next.ever_used;
+      }
+      t0 = fm + 1;
+    }
+  }
+  __syncthreads();
+  if (wave == 0) {
+    if (lane < N) {
+      st->expert_slot[lane] = cs.my_slot[lane];
+      st->stamp[lane] = cs.stamp[lane];
+      st->born[lane] = cs.born[lane];
+    }
+    if (lane < p.capacity) st->slot_expert[lane] = cs.slot_exp[lane];
+    if (lane < 6) (&st->selections)[lane] = cs.counter[lane];
+    if (lane == 0) {
+      st->ever_used = cs.ever_used;
+      st->delta_sum = dsum_s[B];
+      st->count = cs.count0 + B;
+    }
   }
 }
 
@@ -291,7 +399,7 @@ hipError_t launch_gate_gemm(const void *x, const void *gate_w, float *logits, in
 hipError_t launch_route_batch(const RouteParams &p, const float *logits, int B, LayerState *state, moe_route_out_t *out,
                               hipStream_t s) {
   if (B <= 0 || B > kMaxBatch) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(route_batch_kernel, dim3(1), dim3(kRouteBatchThreads), 0, s, p, logits, B, state, out);
+  hipLaunchKernelGGL(route_batch_kernel, dim3(1), dim3(kRouteWaves * kWave), 0, s, p, logits, B, state, out);
   return hipGetLastError();
 }
 

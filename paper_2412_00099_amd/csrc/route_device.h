@@ -181,12 +181,13 @@ static_assert(kHandoverCopies * 8 == kWave, "one lane per word of every copy");
 
 // Everything after the logits (Eq. 3 softmax, Eq. 10, Eq. 9, Eq. 2, Eq. 4, Sec. 4.2), run by one wavefront.
 // note == nullptr: nobody on the host waits for this step (a token inside a batch).  carry != nullptr: receives the
-// cache state as this step leaves it, so that the next token of a batch continues from registers; store_state =
-// false then leaves the state in device memory as it was (only the last token of a batch writes it back).
+// cache state as this step leaves it, so that a batch continues from registers; store_state = false then leaves the
+// state in device memory as it was.  n_miss_out, when given, receives the number of misses of the step.  out_dev may
+// point into LDS (a record that is copied out later, or dropped).
 __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_s, const CacheRegs &cr, LayerState *st,
                                            moe_route_out_t *out_dev, HostNote *note, uint32_t *rec_s, int lane,
                                            BoundaryFlags flags = BoundaryFlags{nullptr, 0}, CacheRegs *carry = nullptr,
-                                           bool store_state = true) {
+                                           bool store_state = true, int *n_miss_out = nullptr) {
 #pragma clang fp contract(off)
   const int N = p.n_experts, K = p.top_k, C = p.capacity;
   int my_slot = cr.my_slot, slot_exp = cr.slot_exp;
@@ -266,6 +267,7 @@ __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_
   const bool miss = sel && !resident;
   const uint64_t miss_mask = ballot(miss);
   const int n_miss = (int)__builtin_popcountll(miss_mask);
+  if (n_miss_out != nullptr) *n_miss_out = n_miss;
 
   // expert weights from the unmodified logits (Sec. 3.3), optional renormalisation (Sec. 2.1)
   if (p.renormalize) {
