@@ -101,11 +101,20 @@ struct moe_cache {
   moe_route_out_t *batch_rec = nullptr;      // [kMaxBatch] the decisions of the batch routed last: pinned host memory
   moe_route_out_t *batch_rec_dev = nullptr;  // the routing kernel's view of it (the records go straight to the host)
   float *d_bpartial = nullptr;              // [max_units][16][hidden]: the output tile of every unit
-  TokenTile *d_tiles = nullptr, *h_tiles = nullptr;  // device / pinned staging
+  // the tables of a launch, one block of pinned memory and its device copy (one transfer per launch):
+  //   [max_tiles] tiles | [max_units] units | [kMaxBatch] partial rows per token | [kMaxBatch][max_contrib] their lists
+  uint8_t *h_tables = nullptr, *d_tables = nullptr;
+  size_t off_units = 0, off_contrib = 0;
+  TokenTile *d_tiles = nullptr, *h_tiles = nullptr;
   BatchUnit *d_units = nullptr, *h_units = nullptr;
-  int32_t *d_contrib = nullptr, *h_contrib = nullptr;  // [kMaxBatch][max_contrib] partial rows of each token, then
-                                                       // [kMaxBatch] their counts
+  int32_t *d_contrib = nullptr, *h_contrib = nullptr;
   int max_tiles = 0, max_units = 0, max_contrib = 0;
+  int n_cus = 0;
+  std::vector<BatchUnit> units_built;       // the units of a segment in the order they are made (tile by tile)
+  std::vector<int32_t> unit_pos;            // their places in the launch
+  std::vector<int32_t> xcd_queue[8];        // units per XCD, while the launch order is worked out
+  std::vector<int32_t> unit_group_owner;    // per (blob, block of records): the XCD of its group
+  std::vector<int32_t> tile_slot, tile_first_unit;
   int batch_layer = -1, batch_n = 0;
   hipEvent_t ev_batch = nullptr;            // compute stream has finished reading the slots (before fills overwrite them)
   int64_t batch_units_launched = 0, batch_segments = 0;
@@ -271,6 +280,7 @@ int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, 
   int cus = 0;
   HIP_INIT(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
   HIP_INIT(static_scratch_setup(dev, nullptr, nullptr));  // moe_expert_forward_static's scratch array on this device
+  c->n_cus = cus;
   c->plan = gemv_plan(cus, cfg->top_k * cfg->inter + cfg->shared_inter, cfg->weight_fmt, cfg->act_fmt);
   // the host learns a routing decision by polling the three self-tagged words the router stores into mapped host
   // memory (each complete in itself, no ordering between them); MOE_HOST_SYNC=event waits on a stream event instead
@@ -303,24 +313,29 @@ int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, 
   HIP_INIT(hipMalloc(&c->d_y, sizeof(float) * (size_t)cfg->hidden));
   c->batch_ok = batch_shape_supported(cfg->weight_fmt, cfg->act_fmt, cfg->hidden, cfg->inter, cfg->shared_inter);
   if (c->batch_ok) {
-    const int chunks = (cfg->inter + kBatchUnitRecords - 1) / kBatchUnitRecords;
-    const int schunks = (cfg->shared_inter + kBatchUnitRecords - 1) / kBatchUnitRecords;
+    // (units of fewer records are only made while a launch stays within one workgroup per compute unit, below)
+    const int chunks = std::max((cfg->inter + kBatchUnitRecords - 1) / kBatchUnitRecords, 1);
+    const int schunks = std::max((cfg->shared_inter + kBatchUnitRecords - 1) / kBatchUnitRecords, cfg->shared_inter > 0 ? 1 : 0);
     // a tile is 16 tokens of one slot: at most one partly filled tile per slot plus the full ones
     const int routed_tiles = cfg->capacity + kMaxBatch * cfg->top_k / 16, shared_tiles = kMaxBatch / 16;
     c->max_tiles = routed_tiles + shared_tiles;
-    c->max_units = routed_tiles * chunks + shared_tiles * schunks;
+    c->max_units = std::max(routed_tiles * chunks + shared_tiles * schunks, cus);
     HIP_INIT(hipMalloc(&c->d_logits_batch, sizeof(float) * kMaxBatch * MOE_MAX_EXPERTS));
     HIP_INIT(hipHostMalloc(reinterpret_cast<void **>(&c->batch_rec), sizeof(moe_route_out_t) * kMaxBatch, hipHostMallocMapped));
     HIP_INIT(hipHostGetDevicePointer(reinterpret_cast<void **>(&c->batch_rec_dev), c->batch_rec, 0));
-    c->max_contrib = cfg->top_k * chunks + schunks;
+    c->max_contrib = std::max(cfg->top_k * chunks + schunks, cus);
     HIP_INIT(hipMalloc(&c->d_bpartial, sizeof(float) * (size_t)c->max_units * 16 * cfg->hidden));
-    HIP_INIT(hipMalloc(&c->d_contrib, sizeof(int32_t) * (size_t)kMaxBatch * (c->max_contrib + 1)));
-    HIP_INIT(hipHostMalloc(reinterpret_cast<void **>(&c->h_contrib), sizeof(int32_t) * (size_t)kMaxBatch * (c->max_contrib + 1),
-                           hipHostMallocDefault));
-    HIP_INIT(hipMalloc(&c->d_tiles, sizeof(TokenTile) * c->max_tiles));
-    HIP_INIT(hipMalloc(&c->d_units, sizeof(BatchUnit) * c->max_units));
-    HIP_INIT(hipHostMalloc(reinterpret_cast<void **>(&c->h_tiles), sizeof(TokenTile) * c->max_tiles, hipHostMallocDefault));
-    HIP_INIT(hipHostMalloc(reinterpret_cast<void **>(&c->h_units), sizeof(BatchUnit) * c->max_units, hipHostMallocDefault));
+    c->off_units = (sizeof(TokenTile) * c->max_tiles + 255) / 256 * 256;
+    c->off_contrib = (c->off_units + sizeof(BatchUnit) * c->max_units + 255) / 256 * 256;
+    const size_t table_bytes = c->off_contrib + sizeof(int32_t) * (size_t)kMaxBatch * (c->max_contrib + 1);
+    HIP_INIT(hipMalloc(&c->d_tables, table_bytes));
+    HIP_INIT(hipHostMalloc(reinterpret_cast<void **>(&c->h_tables), table_bytes, hipHostMallocDefault));
+    c->h_tiles = reinterpret_cast<TokenTile *>(c->h_tables);
+    c->d_tiles = reinterpret_cast<TokenTile *>(c->d_tables);
+    c->h_units = reinterpret_cast<BatchUnit *>(c->h_tables + c->off_units);
+    c->d_units = reinterpret_cast<BatchUnit *>(c->d_tables + c->off_units);
+    c->h_contrib = reinterpret_cast<int32_t *>(c->h_tables + c->off_contrib);
+    c->d_contrib = reinterpret_cast<int32_t *>(c->d_tables + c->off_contrib);
     HIP_INIT(hipEventCreateWithFlags(&c->ev_batch, hipEventDisableTiming));
   }
   HIP_INIT(hipEventCreateWithFlags(&c->ev_route, hipEventDisableTiming));
@@ -348,12 +363,8 @@ void moe_cache_destroy(moe_cache_t *c) {
   if (c->d_logits_batch) (void)hipFree(c->d_logits_batch);
   if (c->batch_rec) (void)hipHostFree(c->batch_rec);
   if (c->d_bpartial) (void)hipFree(c->d_bpartial);
-  if (c->d_contrib) (void)hipFree(c->d_contrib);
-  if (c->h_contrib) (void)hipHostFree(c->h_contrib);
-  if (c->d_tiles) (void)hipFree(c->d_tiles);
-  if (c->d_units) (void)hipFree(c->d_units);
-  if (c->h_tiles) (void)hipHostFree(c->h_tiles);
-  if (c->h_units) (void)hipHostFree(c->h_units);
+  if (c->d_tables) (void)hipFree(c->d_tables);
+  if (c->h_tables) (void)hipHostFree(c->h_tables);
   if (c->ev_batch) (void)hipEventDestroy(c->ev_batch);
   if (c->ev_route) (void)hipEventDestroy(c->ev_route);
   for (hipEvent_t e : c->ev_copy)
@@ -710,36 +721,28 @@ int moe_expert_forward_batch(moe_cache_t *c, int32_t layer, const void *x_dev, v
     first = false;
     int n_tiles = 0, n_units = 0;
     const int n_seg = t1 - t0, mc = c->max_contrib;
-    int32_t *n_contrib = c->h_contrib + (size_t)kMaxBatch * mc;  // counts behind the lists
+    int32_t *n_contrib = c->h_contrib;                 // [kMaxBatch] counts, then the lists
+    int32_t *contrib = c->h_contrib + kMaxBatch;       // [n_seg][mc]
     for (int i = 0; i < n_seg; ++i) n_contrib[i] = 0;
-    auto add_units = [&](int slot, int rows, int tile) {
-      for (int r0 = 0; r0 < rows; r0 += kBatchUnitRecords)
-        c->h_units[n_units++] = BatchUnit{slot, r0, std::min(kBatchUnitRecords, rows - r0), tile};
-    };
-    // token t (of the whole batch) sits in row `row` of the tile whose units are first_unit .. n_units - 1
-    auto add_contrib = [&](int t, int first_unit, int row) {
-      for (int uidx = first_unit; uidx < n_units; ++uidx) {
-        int32_t &n = n_contrib[t - t0];
-        if (n < mc) c->h_contrib[(size_t)(t - t0) * mc + n] = uidx * 16 + row;
-        ++n;
-      }
+    // tiles first: per slot the tokens routed to it, sixteen to a tile; then the shared expert's
+    std::vector<int32_t> &tile_slot = c->tile_slot;  // -1: the shared expert
+    tile_slot.clear();
+    auto new_tile = [&](int slot) -> TokenTile * {
+      if (n_tiles >= c->max_tiles) return nullptr;
+      TokenTile *tile = &c->h_tiles[n_tiles++];
+      memset(tile, 0, sizeof *tile);
+      tile_slot.push_back(slot);
+      return tile;
     };
     for (int s = 0; s < g.capacity; ++s) {
       if (!((read >> s) & 1)) continue;
       TokenTile *tile = nullptr;
-      int first_unit = 0;
       for (int t = t0; t < t1; ++t) {
         const moe_route_out_t &r = c->batch_rec[t];
         for (int k = 0; k < K; ++k) {
           if (r.sel_slot[k] != s) continue;
-          if (!tile || tile->n == 16) {
-            if (n_tiles >= c->max_tiles) return fail(MOE_EHIP, "batch tables overflow (tiles)");
-            tile = &c->h_tiles[n_tiles];
-            memset(tile, 0, sizeof *tile);
-            first_unit = n_units;
-            add_units(s, g.inter, n_tiles++);
-          }
-          add_contrib(t, first_unit, tile->n);
+          if (!tile || tile->n == 16) tile = new_tile(s);
+          if (!tile) return fail(MOE_EHIP, "batch tables overflow (tiles)");
           tile->tok[tile->n] = t;
           tile->w[tile->n++] = r.sel_weight[k];
         }
@@ -747,28 +750,91 @@ int moe_expert_forward_batch(moe_cache_t *c, int32_t layer, const void *x_dev, v
     }
     if (g.shared_inter > 0) {
       for (int t = t0; t < t1; t += 16) {
-        if (n_tiles >= c->max_tiles) return fail(MOE_EHIP, "batch tables overflow (tiles)");
-        TokenTile *tile = &c->h_tiles[n_tiles];
-        memset(tile, 0, sizeof *tile);
-        const int first_unit = n_units;
-        add_units(-1, g.shared_inter, n_tiles++);
+        TokenTile *tile = new_tile(-1);
+        if (!tile) return fail(MOE_EHIP, "batch tables overflow (tiles)");
         for (int i = t; i < std::min(t + 16, t1); ++i) {
-          add_contrib(i, first_unit, tile->n);
           tile->tok[tile->n] = i;
           tile->w[tile->n++] = 1.f;
         }
       }
     }
+    // Records per unit: as few as keep the whole launch within one workgroup per compute unit (a unit costs about
+    // 8 us of start-up and 8 us per block of sixteen records, so a short batch finishes sooner spread over more
+    // compute units), at most kBatchUnitRecords (more tiles than that: several rounds of full-size units).
+    int unit_rec = kBatchUnitRecords;
+    for (int cand = kBatchMinUnitRecords; cand < kBatchUnitRecords; cand += 16) {
+      int total = 0;
+      for (int i = 0; i < n_tiles; ++i) {
+        const int rows = tile_slot[i] < 0 ? g.shared_inter : g.inter;
+        total += (rows + cand - 1) / cand;
+      }
+      if (total <= c->n_cus) {
+        unit_rec = cand;
+        break;
+      }
+    }
+    c->units_built.clear();
+    c->tile_first_unit.assign(n_tiles + 1, 0);
+    for (int i = 0; i < n_tiles; ++i) {
+      const int rows = tile_slot[i] < 0 ? g.shared_inter : g.inter;
+      c->tile_first_unit[i] = n_units;
+      for (int r0 = 0; r0 < rows; r0 += unit_rec, ++n_units)
+        c->units_built.push_back(BatchUnit{tile_slot[i], r0, std::min(unit_rec, rows - r0), i});
+    }
+    c->tile_first_unit[n_tiles] = n_units;
+    if (n_units > c->max_units) return fail(MOE_EHIP, "batch tables overflow (%d units)", n_units);
+    // Launch order.  The units that read the same records (one blob, one block of records; one unit per token tile)
+    // should share them in an L2: workgroups go to the XCDs round-robin by index, so such a group gets consecutive
+    // places of one XCD (indices 8 apart), the groups spread over the XCDs by length.  Made tile by tile, the units
+    // of a group would sit a tile's unit count apart - at C2 on eight different XCDs, each fetching the block from HBM.
+    std::vector<int32_t> &pos = c->unit_pos;
+    {
+      const int max_chunks = (std::max(g.inter, g.shared_inter) + unit_rec - 1) / unit_rec;
+      pos.assign(n_units, -1);
+      for (auto &q : c->xcd_queue) q.clear();
+      std::vector<int32_t> &owner = c->unit_group_owner;  // per (blob, block of records): the XCD of its group
+      owner.assign((size_t)(g.capacity + 1) * max_chunks, -1);
+      auto key = [&](const BatchUnit &bu) { return (bu.slot + 1) * max_chunks + bu.rec0 / unit_rec; };
+      for (int u = 0; u < n_units; ++u) {
+        int32_t &x = owner[(size_t)key(c->units_built[u])];
+        if (x < 0) {  // a new group: to the XCD with the shortest queue
+          x = 0;
+          for (int i = 1; i < 8; ++i)
+            if (c->xcd_queue[i].size() < c->xcd_queue[x].size()) x = i;
+        }
+        c->xcd_queue[x].push_back(u);
+      }
+      for (auto &q : c->xcd_queue)  // a group's units side by side in its queue
+        std::stable_sort(q.begin(), q.end(), [&](int32_t ua, int32_t ub) { return key(c->units_built[ua]) < key(c->units_built[ub]); });
+      int placed = 0;
+      for (size_t i = 0; placed < n_units; ++i)
+        for (int x = 0; x < 8; ++x)
+          if (i < c->xcd_queue[x].size()) {
+            const int32_t u = c->xcd_queue[x][i];
+            pos[u] = placed;
+            c->h_units[placed++] = c->units_built[u];
+          }
+    }
+    // per token: the rows of the partial buffer that hold its share of y (unit place * 16 + row in the tile), in a
+    // fixed order: tiles in the order made, a tile's units by record
+    for (int i = 0; i < n_tiles; ++i) {
+      const TokenTile &tile = c->h_tiles[i];
+      for (int row = 0; row < tile.n; ++row) {
+        const int t = tile.tok[row];
+        for (int u = c->tile_first_unit[i]; u < c->tile_first_unit[i + 1]; ++u) {
+          int32_t &n = n_contrib[t - t0];
+          if (n < mc) contrib[(size_t)(t - t0) * mc + n] = pos[u] * 16 + row;
+          ++n;
+        }
+      }
+    }
     for (int i = 0; i < n_seg; ++i)
       if (n_contrib[i] > mc) return fail(MOE_EHIP, "batch tables overflow (%d partial rows for one token)", n_contrib[i]);
-    if (n_units > c->max_units) return fail(MOE_EHIP, "batch tables overflow (%d units)", n_units);
-    HIP_TRY(hipMemcpyAsync(c->d_tiles, c->h_tiles, sizeof(TokenTile) * n_tiles, hipMemcpyHostToDevice, c->compute));
-    HIP_TRY(hipMemcpyAsync(c->d_units, c->h_units, sizeof(BatchUnit) * n_units, hipMemcpyHostToDevice, c->compute));
-    HIP_TRY(hipMemcpyAsync(c->d_contrib, c->h_contrib, sizeof(int32_t) * (size_t)kMaxBatch * (mc + 1), hipMemcpyHostToDevice,
-                           c->compute));
+    HIP_TRY(hipMemcpyAsync(c->d_tables, c->h_tables, c->off_contrib + sizeof(int32_t) * ((size_t)kMaxBatch + (size_t)n_seg * mc),
+                           hipMemcpyHostToDevice, c->compute));
     bp.n_units = n_units;
     HIP_TRY(launch_expert_batch(bp, c->compute));
-    HIP_TRY(launch_reduce_batch(c->d_bpartial, c->d_contrib, c->d_contrib + (size_t)kMaxBatch * mc, mc, y_dev, d, t0, n_seg,
+    HIP_TRY(launch_reduce_batch(c->d_bpartial, c->d_contrib + kMaxBatch, c->d_contrib, mc, y_dev, d, t0, n_seg,
                                 c->compute));
     HIP_TRY(hipEventRecord(c->ev_batch, c->compute));
     c->batch_units_launched += n_units;
