@@ -193,3 +193,49 @@ def test_batch_equals_single_token_path_and_errors():
         dec3.route_batch(0, logits=z)
     assert e.value.code == pkg.MOE_EINVAL
     dec3.close()
+
+
+@pytest.mark.parametrize("mode", ["lru", "strong_prior", "max_rank", "cumsum", "delta_fixed", "delta_token", "renorm_topj"])
+@pytest.mark.parametrize("C", [3, 12])
+def test_batch_routing_equals_token_by_token_in_every_mode(mode, C):
+    """The batch routing accepts the tokens of a window up to the first miss and routes the missing token alone:
+    in every routing mode, with frequent (C = 3) and rare (C = 12) misses, its records, tables and counters must be
+    those of the single-token steps (which the routing tests hold against the oracle), bit for bit."""
+    import paper_2412_00099_amd as pkg
+
+    kw = dict(lru=dict(lam=0.0), strong_prior=dict(lam=2.0), max_rank=dict(route_mode=pkg.MOE_ROUTE_MAX_RANK, max_rank=8, top_j=1),
+              cumsum=dict(route_mode=pkg.MOE_ROUTE_CUMSUM, cumsum_p=0.7), delta_fixed=dict(lam=0.5, delta_fixed=1.25),
+              delta_token=dict(lam=0.7, delta_per_token=True), renorm_topj=dict(lam=0.5, top_j=1))[mode]
+    N, K = 16, 3
+    cfg = BASE.with_(n_layers=1, hidden=1024, n_experts=N, inter=32, shared_inter=32, top_k=K, capacity=C,
+                     renormalize=mode == "renorm_topj", seed=930 + C)
+    print(f"case batch routing vs single tokens: {mode} C={C}", flush=True)
+    store_a, one = build(cfg, **kw)
+    store_b, many = build(cfg, **kw)
+    batches = [128, 1, 37, 16, 17, 128, 5]
+    T = sum(batches)
+    zs = workloads.logits_stream(cfg, T, layer=0, scale=1.5).to(DEV)
+    x = torch.zeros((128, cfg.hidden), dtype=cfg.act_dtype, device=DEV)
+    y = torch.zeros_like(x)
+    t0 = 0
+    for b in batches:
+        recs = many.route_batch(0, logits=zs[t0:t0 + b].contiguous())
+        many.expert_forward_batch(0, x[:b], y[:b])
+        for j in range(b):
+            ref = one.route_step(0, logits=zs[t0 + j])
+            one.expert_forward(0, x[0], y[0])
+            fa, fb = route_fields(ref, K), route_fields(recs[j], K)
+            for key in fa:
+                assert np.array_equal(fa[key], fb[key]), (t0 + j, key, fa[key], fb[key])
+            assert list(ref.logits[:N]) == list(recs[j].logits[:N])
+        t0 += b
+    ta, tb = one.tables(0), many.tables(0)
+    for field in ("expert_slot", "slot_expert", "stamp"):
+        assert list(getattr(ta, field)) == list(getattr(tb, field)), field
+    assert (ta.count, ta.delta_sum) == (tb.count, tb.delta_sum)
+    sa, sb = one.stats(0), many.stats(0)
+    for field in ("tokens", "selections", "hits", "misses", "cold_misses", "evictions", "lifetime_sum", "bytes_filled"):
+        assert getattr(sa, field) == getattr(sb, field), field
+    assert sa.misses >= K and (mode != "lru" or C != 3 or sa.misses > T // 4)
+    one.close()
+    many.close()
