@@ -360,17 +360,28 @@ __global__ __launch_bounds__(kBatchWaves *kWave) void expert_batch_kernel(BatchP
   }
 }
 
-// y[t] = the sum of token t's partial rows in list order, rounded to bf16.  contrib[t * max_contrib + i] is a row
-// index into the partial buffer (unit * 16 + row of the token in the unit's tile); grid = (tokens, d / 256).
-__global__ __launch_bounds__(64) void reduce_batch_kernel(const float *partial, const int32_t *contrib,
-                                                          const int32_t *n_contrib, int max_contrib, uint16_t *y, int d,
-                                                          int t_first) {
-  const int t = blockIdx.x, col = blockIdx.y * 256 + threadIdx.x * 4;
+// y[t] = the sum of token t's partial rows, rounded to bf16.  contrib[t * max_contrib + i] is a row index into the
+// partial buffer (unit * 16 + row of the token in the unit's tile); grid = (tokens, d / 256), eight wavefronts per
+// workgroup: wavefront g adds the g-th eighth of the list in list order (several loads in flight), the eight sums are
+// added in order of g - a fixed tree, so y does not change from run to run.
+constexpr int kReduceGroups = 8;
+__global__ __launch_bounds__(kReduceGroups *kWave) void reduce_batch_kernel(const float *partial, const int32_t *contrib,
+                                                                           const int32_t *n_contrib, int max_contrib,
+                                                                           uint16_t *y, int d, int t_first) {
+  __shared__ f32x4 part_s[kReduceGroups][kWave];
+  const int t = blockIdx.x, lane = threadIdx.x & 63, g = threadIdx.x >> 6;
+  const int col = blockIdx.y * 256 + lane * 4;
   const int32_t *list = contrib + (size_t)t * max_contrib;
-  const int n = n_contrib[t];
+  const int n = n_contrib[t], chunk = (n + kReduceGroups - 1) / kReduceGroups;
+  const int i0 = g * chunk, i1 = min(n, i0 + chunk);
   f32x4 s = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-  for (int i = 0; i < n; ++i) s += *reinterpret_cast<const f32x4 *>(partial + (size_t)list[i] * d + col);
+#pragma unroll 8
+  for (int i = i0; i < i1; ++i) s += *reinterpret_cast<const f32x4 *>(partial + (size_t)list[i] * d + col);
+  part_s[g][lane] = s;
+  __syncthreads();
+  if (g != 0) return;
+#pragma unroll
+  for (int k = 1; k < kReduceGroups; ++k) s += part_s[k][lane];
   u32x2 o;
   o.x = (uint32_t)f32_to_bf16_rne(s[0]) | ((uint32_t)f32_to_bf16_rne(s[1]) << 16);
   o.y = (uint32_t)f32_to_bf16_rne(s[2]) | ((uint32_t)f32_to_bf16_rne(s[3]) << 16);
@@ -427,7 +438,7 @@ hipError_t launch_expert_batch(const BatchParams &p, hipStream_t s) {
 hipError_t launch_reduce_batch(const float *partial, const int32_t *contrib, const int32_t *n_contrib, int max_contrib,
                                void *y, int hidden, int t_first, int n_tokens, hipStream_t s) {
   if (n_tokens <= 0) return hipSuccess;
-  hipLaunchKernelGGL(reduce_batch_kernel, dim3(n_tokens, hidden / 256), dim3(64), 0, s, partial, contrib, n_contrib,
+  hipLaunchKernelGGL(reduce_batch_kernel, dim3(n_tokens, hidden / 256), dim3(kReduceGroups * kWave), 0, s, partial, contrib, n_contrib,
                      max_contrib, static_cast<uint16_t *>(y), hidden, t_first);
   return hipGetLastError();
 }
