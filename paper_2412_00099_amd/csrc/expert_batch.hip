@@ -6,7 +6,7 @@
 // weights-stationary small GEMM per expert over the tokens routed to it (Eq. 1), both on the matrix cores.
 //
 //  gate_gemm_kernel    logits[B, N] = X[B, d] W_gate[N, d]^T, bf16 inputs, fp32 accumulation
-//                      (v_mfma_f32_16x16x32_bf16: a 16-token x 16-expert tile per four wavefronts, which split d).
+//                      (v_mfma_f32_16x16x32_bf16: a 16-token x 16-expert tile per eight wavefronts, which split d).
 //  route_batch_kernel  sixteen wavefronts route sixteen tokens at a time through rt::route_wave against the current
 //                      cache state; a token that misses an expert is routed alone and updates the state (see there);
 //                      one routing record per token.
@@ -39,39 +39,37 @@ __device__ __forceinline__ f32x4 mfma_f32(float a, float b, f32x4 c) {
 }
 
 // ---- gate logits of the batch -------------------------------------------------------------------
-// grid = token tiles of 16, block = (expert tiles of 16) x kGateSplit wavefronts: wavefront (et, ks) multiplies the
-// ks-th part of the hidden dimension, all its operands requested eight steps at a time; the parts are added through
-// LDS in a fixed order.  A-operand lane l: token l % 16, columns k0 + 8 (l / 16) .. + 8; B-operand lane l: expert
+// grid = (token tiles of 16, expert tiles of 16), block = kGateSplit wavefronts: wavefront ks multiplies the ks-th
+// part of the hidden dimension, all its operands requested at once (one round trip); the parts are added through LDS
+// in a fixed order.  A-operand lane l: token l % 16, columns k0 + 8 (l / 16) .. + 8; B-operand lane l: expert
 // n0 + l % 16, the same columns; result lane l: expert n0 + l % 16, tokens 4 (l / 16) + v.  Rows past the last token /
 // expert re-read the last one and are not stored.
-constexpr int kGateSplit = 4;
-__global__ __launch_bounds__(1024) void gate_gemm_kernel(const uint16_t *x, const uint16_t *gate_w, float *logits, int B,
-                                                        int N, int d) {
-  __shared__ f32x4 part[kGateSplit][MOE_MAX_EXPERTS / 16][kWave];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int et = wave / kGateSplit, ks = wave % kGateSplit;
-  const int t0 = blockIdx.x * 16, n0 = et * 16;
+constexpr int kGateSplit = 8;
+// STEPS: 32-column steps per wavefront (hidden = 32 * kGateSplit * STEPS)
+template <int STEPS>
+__global__ __launch_bounds__(kGateSplit *kWave) void gate_gemm_kernel(const uint16_t *x, const uint16_t *gate_w,
+                                                                     float *logits, int B, int N, int d) {
+  __shared__ f32x4 part[kGateSplit][kWave];
+  const int lane = threadIdx.x & 63, ks = threadIdx.x >> 6;
+  const int t0 = blockIdx.x * 16, n0 = blockIdx.y * 16;
   const int tok = min(t0 + (lane & 15), B - 1), exp = min(n0 + (lane & 15), N - 1);
-  const int steps = d / (32 * kGateSplit);  // a multiple of 8 (the launcher checks)
-  const u32x4 *xa = reinterpret_cast<const u32x4 *>(x + (size_t)tok * d) + (lane >> 4) + (size_t)ks * steps * 4;
-  const u32x4 *wb = reinterpret_cast<const u32x4 *>(gate_w + (size_t)exp * d) + (lane >> 4) + (size_t)ks * steps * 4;
+  const u32x4 *xa = reinterpret_cast<const u32x4 *>(x + (size_t)tok * d) + (lane >> 4) + (size_t)ks * STEPS * 4;
+  const u32x4 *wb = reinterpret_cast<const u32x4 *>(gate_w + (size_t)exp * d) + (lane >> 4) + (size_t)ks * STEPS * 4;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  for (int s0 = 0; s0 < steps; s0 += 8) {
-    u32x4 a[8], b[8];
+  u32x4 a[STEPS], b[STEPS];
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      a[s] = xa[(s0 + s) * 4];
-      b[s] = wb[(s0 + s) * 4];
-    }
-#pragma unroll
-    for (int s = 0; s < 8; ++s) acc = mfma_bf16(a[s], b[s], acc);
+  for (int s = 0; s < STEPS; ++s) {
+    a[s] = xa[s * 4];
+    b[s] = wb[s * 4];
   }
-  part[ks][et][lane] = acc;
+#pragma unroll
+  for (int s = 0; s < STEPS; ++s) acc = mfma_bf16(a[s], b[s], acc);
+  part[ks][lane] = acc;
   __syncthreads();
   if (ks != 0) return;
 #pragma unroll
   for (int q = 1; q < kGateSplit; ++q) {
-    const f32x4 t = part[q][et][lane];
+    const f32x4 t = part[q][lane];
     acc[0] += t[0];
     acc[1] += t[1];
     acc[2] += t[2];
@@ -401,9 +399,15 @@ bool batch_shape_supported(int weight_fmt, int act_fmt, int hidden, int inter, i
 }
 
 hipError_t launch_gate_gemm(const void *x, const void *gate_w, float *logits, int B, int N, int hidden, hipStream_t s) {
-  if (hidden % (32 * kGateSplit * 8) != 0 || B <= 0 || N <= 0 || N > MOE_MAX_EXPERTS) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(gate_gemm_kernel, dim3((B + 15) / 16), dim3(64 * kGateSplit * ((N + 15) / 16)), 0, s,
-                     static_cast<const uint16_t *>(x), static_cast<const uint16_t *>(gate_w), logits, B, N, hidden);
+  if (B <= 0 || N <= 0 || N > MOE_MAX_EXPERTS) return hipErrorInvalidValue;
+  const dim3 g((B + 15) / 16, (N + 15) / 16), blk(kWave * kGateSplit);
+  const uint16_t *xp = static_cast<const uint16_t *>(x), *wp = static_cast<const uint16_t *>(gate_w);
+  if (hidden == 32 * kGateSplit * 8)
+    hipLaunchKernelGGL(gate_gemm_kernel<8>, g, blk, 0, s, xp, wp, logits, B, N, hidden);
+  else if (hidden == 32 * kGateSplit * 4)
+    hipLaunchKernelGGL(gate_gemm_kernel<4>, g, blk, 0, s, xp, wp, logits, B, N, hidden);
+  else
+    return hipErrorInvalidValue;
   return hipGetLastError();
 }
 
