@@ -137,8 +137,11 @@ hipError_t launch_state_init(LayerState *state, int n_layers, const int32_t *ini
                              hipStream_t s);
 // ---- prompt phase (expert_batch.hip): a batch of tokens through one layer ----
 constexpr int kMaxBatch = 128;        // tokens per moe_route_batch / moe_expert_forward_batch call
-constexpr int kBatchUnitRecords = 128;  // most records of one expert handled by one workgroup of the batched expert kernel
-constexpr int kBatchMinUnitRecords = 32; // fewest (short batches are spread over more compute units)
+// records of one expert handled by one workgroup of the batched expert kernel: the host picks a multiple of 16 between
+// kBatchMinUnitRecords and kBatchMaxUnitRecords per launch; buffers are sized for kBatchUnitRecords and up
+constexpr int kBatchUnitRecords = 128;
+constexpr int kBatchMinUnitRecords = 32;
+constexpr int kBatchMaxUnitRecords = 512;
 // up to 16 tokens routed to one expert (or any 16 tokens, for the shared expert) and their weights for it
 struct TokenTile {
   int32_t tok[16];

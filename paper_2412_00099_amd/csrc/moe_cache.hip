@@ -758,19 +758,27 @@ int moe_expert_forward_batch(moe_cache_t *c, int32_t layer, const void *x_dev, v
         }
       }
     }
-    // Records per unit: as few as keep the whole launch within one workgroup per compute unit (a unit costs about
-    // 8 us of start-up and 8 us per block of sixteen records, so a short batch finishes sooner spread over more
-    // compute units), at most kBatchUnitRecords (more tiles than that: several rounds of full-size units).
+    // Records per unit.  A unit costs about 8 us of start-up plus 0.5 us per record, and the launch runs in rounds of
+    // one workgroup per compute unit: take the size (a multiple of 16) with the smallest estimate rounds x unit time,
+    // the larger one when two are equal (fewer partial tiles to add up).  A short batch thus spreads over all
+    // compute units with small units, a long one avoids a last round that is nearly empty.
     int unit_rec = kBatchUnitRecords;
-    for (int cand = kBatchMinUnitRecords; cand < kBatchUnitRecords; cand += 16) {
-      int total = 0;
-      for (int i = 0; i < n_tiles; ++i) {
-        const int rows = tile_slot[i] < 0 ? g.shared_inter : g.inter;
-        total += (rows + cand - 1) / cand;
-      }
-      if (total <= c->n_cus) {
-        unit_rec = cand;
-        break;
+    {
+      double best = 1e30;
+      for (int cand = kBatchMinUnitRecords; cand <= kBatchMaxUnitRecords; cand += 16) {
+        int total = 0;
+        for (int i = 0; i < n_tiles; ++i) {
+          const int rows = tile_slot[i] < 0 ? g.shared_inter : g.inter;
+          total += (rows + cand - 1) / cand;
+        }
+        const int per_token = K * ((g.inter + cand - 1) / cand) + (g.shared_inter + cand - 1) / cand;
+        if (total > c->max_units || per_token > mc) continue;  // (what the tables are sized for)
+        const int rounds = (total + c->n_cus - 1) / c->n_cus;
+        const double est = rounds * (8.0 + 0.5 * cand);
+        if (est <= best) {
+          best = est;
+          unit_rec = cand;
+        }
       }
     }
     c->units_built.clear();
