@@ -241,16 +241,8 @@ __global__ __launch_bounds__(kBatchWaves *kWave) void expert_batch_kernel(BatchP
   const int n_tok = tile->n;
   const uint8_t *blob = u.slot < 0 ? p.shared_blob : p.slot_pool + (int64_t)u.slot * p.slot_bytes;
   const int64_t row_bytes = (int64_t)D * 2, rec_bytes = 3 * row_bytes;
-
-  // X tile: row t = activations of the tile's t-th token (zeros past the last token)
-  for (int c = tid; c < 16 * (D / 8); c += NW * kWave) {
-    const int t = c / (D / 8), k8 = c - t * (D / 8);
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (t < n_tok) v = *(reinterpret_cast<const u32x4 *>(p.x + (size_t)tile->tok[t] * D) + k8);
-    *reinterpret_cast<u32x4 *>(xs + t * XS + k8 * 8) = v;
-  }
   const float wt = (lane & 15) < n_tok ? tile->w[lane & 15] : 0.f;  // weight of token lane % 16 for this expert
-  __syncthreads();
+
 
   f32x4 acc[CBW][8];
 #pragma unroll
@@ -337,8 +329,33 @@ __global__ __launch_bounds__(kBatchWaves *kWave) void expert_batch_kernel(BatchP
     if constexpr (NEXT) load_dn(r_next);
     __builtin_amdgcn_wave_barrier();
   };
+  // the first block's weights do not depend on the tokens: requested before the X tile is staged
   load_gu(u.rec0);
   load_dn(u.rec0);
+  // X tile: row t = activations of the tile's t-th token (zeros past the last token); a thread's token indices first,
+  // then all its chunks of x at once (two round trips in all)
+  {
+    constexpr int PT = 16 * (D / 8) / (NW * kWave);  // 16-byte chunks per thread
+    int tok_of[PT];
+#pragma unroll
+    for (int i = 0; i < PT; ++i) {
+      const int t = (tid + i * NW * kWave) / (D / 8);
+      tok_of[i] = tile->tok[t < n_tok ? t : 0];
+    }
+    u32x4 v[PT];
+#pragma unroll
+    for (int i = 0; i < PT; ++i) {
+      const int c = tid + i * NW * kWave, t = c / (D / 8), k8 = c - t * (D / 8);
+      v[i] = *(reinterpret_cast<const u32x4 *>(p.x + (size_t)tok_of[i] * D) + k8);
+      if (t >= n_tok) v[i] = u32x4{0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (int i = 0; i < PT; ++i) {
+      const int c = tid + i * NW * kWave, t = c / (D / 8), k8 = c - t * (D / 8);
+      *reinterpret_cast<u32x4 *>(xs + t * XS + k8 * 8) = v[i];
+    }
+  }
+  __syncthreads();
   for (int blk = 16; blk < u.n_rec; blk += 16) block(u.rec0 + blk, std::true_type{});
   block(0, std::false_type{});
 
