@@ -159,7 +159,8 @@ struct BatchParams {
   float *partial;     // [n_units][16][d] fp32: every unit's output tile
   const BatchUnit *units;
   const TokenTile *tiles;
-  int32_t hidden, inter, shared_inter, n_units;
+  int32_t hidden, inter, shared_inter;
+  int32_t n_units, unit_base;  // the launch covers units unit_base .. unit_base + n_units - 1
   int64_t slot_bytes;
 };
 bool batch_shape_supported(int weight_fmt, int act_fmt, int hidden, int inter, int shared_inter);

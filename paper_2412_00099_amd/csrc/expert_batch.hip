@@ -236,7 +236,8 @@ __global__ __launch_bounds__(kBatchWaves *kWave) void expert_batch_kernel(BatchP
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const BatchUnit u = p.units[blockIdx.x];
+  const int unit = p.unit_base + (int)blockIdx.x;
+  const BatchUnit u = p.units[unit];
   const TokenTile *tile = p.tiles + u.tile;
   const int n_tok = tile->n;
   const uint8_t *blob = u.slot < 0 ? p.shared_blob : p.slot_pool + (int64_t)u.slot * p.slot_bytes;
@@ -365,7 +366,7 @@ __global__ __launch_bounds__(kBatchWaves *kWave) void expert_batch_kernel(BatchP
   for (int v = 0; v < 4; ++v) {
     const int t = 4 * kq + v;
     if (t < n_tok) {
-      float *yrow = p.partial + ((size_t)blockIdx.x * 16 + t) * D + wave * (D / NW) + m16 * 8;
+      float *yrow = p.partial + ((size_t)unit * 16 + t) * D + wave * (D / NW) + m16 * 8;
 #pragma unroll
       for (int cb = 0; cb < CBW; ++cb) {
         *reinterpret_cast<f32x4 *>(yrow + cb * 128) = f32x4{acc[cb][0][v], acc[cb][1][v], acc[cb][2][v], acc[cb][3][v]};

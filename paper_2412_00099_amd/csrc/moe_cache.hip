@@ -700,10 +700,12 @@ int moe_expert_forward_batch(moe_cache_t *c, int32_t layer, const void *x_dev, v
     }
     // fills of the segment's misses, once the compute stream has finished with the slots' previous contents
     int n_fill = 0;
+    uint64_t filled = 0;  // slots that receive an expert in this segment
     for (int t = t0; t < t1; ++t) {
       const moe_route_out_t &r = c->batch_rec[t];
       for (int k = 0; k < K; ++k) {
         if (!r.miss[k]) continue;
+        filled |= 1ull << r.sel_slot[k];
         if (n_fill++ == 0) HIP_TRY(hipStreamWaitEvent(c->copy, c->ev_batch, 0));
         HIP_TRY(hipMemcpyAsync(static_cast<uint8_t *>(c->slot_pool[layer]) + (size_t)r.sel_slot[k] * slot_bytes,
                                c->host_blob[(size_t)layer * g.n_experts + r.sel_expert[k]], slot_bytes,
@@ -711,10 +713,7 @@ int moe_expert_forward_batch(moe_cache_t *c, int32_t layer, const void *x_dev, v
         c->bytes_filled[layer] += (int64_t)slot_bytes;
       }
     }
-    if (n_fill > 0) {
-      HIP_TRY(hipEventRecord(c->ev_copy[layer], c->copy));
-      HIP_TRY(hipStreamWaitEvent(c->compute, c->ev_copy[layer], 0));
-    }
+    if (n_fill > 0) HIP_TRY(hipEventRecord(c->ev_copy[layer], c->copy));
     // token tiles per slot and for the shared expert, units per tile; the staging buffers are free again once the
     // previous segment's copies have been consumed
     if (!first) HIP_TRY(hipStreamSynchronize(c->compute));
@@ -795,33 +794,45 @@ int moe_expert_forward_batch(moe_cache_t *c, int32_t layer, const void *x_dev, v
     // should share them in an L2: workgroups go to the XCDs round-robin by index, so such a group gets consecutive
     // places of one XCD (indices 8 apart), the groups spread over the XCDs by length.  Made tile by tile, the units
     // of a group would sit a tile's unit count apart - at C2 on eight different XCDs, each fetching the block from HBM.
+    // Two groups: first the units whose experts were in their slots already (and the shared expert's), launched at
+    // once; behind them the units of the slots being filled, launched behind the fill event - so the first group
+    // computes while the fills stream.
     std::vector<int32_t> &pos = c->unit_pos;
+    int n_ready = 0;
     {
       const int max_chunks = (std::max(g.inter, g.shared_inter) + unit_rec - 1) / unit_rec;
       pos.assign(n_units, -1);
-      for (auto &q : c->xcd_queue) q.clear();
       std::vector<int32_t> &owner = c->unit_group_owner;  // per (blob, block of records): the XCD of its group
-      owner.assign((size_t)(g.capacity + 1) * max_chunks, -1);
       auto key = [&](const BatchUnit &bu) { return (bu.slot + 1) * max_chunks + bu.rec0 / unit_rec; };
-      for (int u = 0; u < n_units; ++u) {
-        int32_t &x = owner[(size_t)key(c->units_built[u])];
-        if (x < 0) {  // a new group: to the XCD with the shortest queue
-          x = 0;
-          for (int i = 1; i < 8; ++i)
-            if (c->xcd_queue[i].size() < c->xcd_queue[x].size()) x = i;
-        }
-        c->xcd_queue[x].push_back(u);
-      }
-      for (auto &q : c->xcd_queue)  // a group's units side by side in its queue
-        std::stable_sort(q.begin(), q.end(), [&](int32_t ua, int32_t ub) { return key(c->units_built[ua]) < key(c->units_built[ub]); });
       int placed = 0;
-      for (size_t i = 0; placed < n_units; ++i)
-        for (int x = 0; x < 8; ++x)
-          if (i < c->xcd_queue[x].size()) {
-            const int32_t u = c->xcd_queue[x][i];
-            pos[u] = placed;
-            c->h_units[placed++] = c->units_built[u];
+      for (int pass = 0; pass < 2; ++pass) {
+        for (auto &q : c->xcd_queue) q.clear();
+        owner.assign((size_t)(g.capacity + 1) * max_chunks, -1);
+        for (int u = 0; u < n_units; ++u) {
+          const BatchUnit &bu = c->units_built[u];
+          const bool waits = bu.slot >= 0 && ((filled >> bu.slot) & 1);
+          if (waits != (pass == 1)) continue;
+          int32_t &x = owner[(size_t)key(bu)];
+          if (x < 0) {  // a new group: to the XCD with the shortest queue
+            x = 0;
+            for (int i = 1; i < 8; ++i)
+              if (c->xcd_queue[i].size() < c->xcd_queue[x].size()) x = i;
           }
+          c->xcd_queue[x].push_back(u);
+        }
+        for (auto &q : c->xcd_queue)  // a group's units side by side in its queue
+          std::stable_sort(q.begin(), q.end(), [&](int32_t ua, int32_t ub) { return key(c->units_built[ua]) < key(c->units_built[ub]); });
+        size_t longest = 0;
+        for (auto &q : c->xcd_queue) longest = std::max(longest, q.size());
+        for (size_t i = 0; i < longest; ++i)
+          for (int x = 0; x < 8; ++x)
+            if (i < c->xcd_queue[x].size()) {
+              const int32_t u = c->xcd_queue[x][i];
+              pos[u] = placed;
+              c->h_units[placed++] = c->units_built[u];
+            }
+        if (pass == 0) n_ready = placed;
+      }
     }
     // per token: the rows of the partial buffer that hold its share of y (unit place * 16 + row in the tile), in a
     // fixed order: tiles in the order made, a tile's units by record
@@ -840,7 +851,12 @@ int moe_expert_forward_batch(moe_cache_t *c, int32_t layer, const void *x_dev, v
       if (n_contrib[i] > mc) return fail(MOE_EHIP, "batch tables overflow (%d partial rows for one token)", n_contrib[i]);
     HIP_TRY(hipMemcpyAsync(c->d_tables, c->h_tables, c->off_contrib + sizeof(int32_t) * ((size_t)kMaxBatch + (size_t)n_seg * mc),
                            hipMemcpyHostToDevice, c->compute));
-    bp.n_units = n_units;
+    bp.unit_base = 0;
+    bp.n_units = n_ready;
+    HIP_TRY(launch_expert_batch(bp, c->compute));
+    if (n_fill > 0) HIP_TRY(hipStreamWaitEvent(c->compute, c->ev_copy[layer], 0));
+    bp.unit_base = n_ready;
+    bp.n_units = n_units - n_ready;
     HIP_TRY(launch_expert_batch(bp, c->compute));
     HIP_TRY(launch_reduce_batch(c->d_bpartial, c->d_contrib + kMaxBatch, c->d_contrib, mc, y_dev, d, t0, n_seg,
                                 c->compute));
