@@ -15,9 +15,10 @@ Prints ONE JSON line.  `value` is tokens/s at the headline strength lambda = 0.5
 below refers to that run: `roofline` is its expert kernel (HIP start/stop events attached to every 5th first-pass
 launch on the compute stream, in a second pass over the same tokens, each behind a short hold of the stream);
 `boundary_as_separate_launch` times the same expert kernel as a launch of its own, with the routing in a launch
-before it; `lambda_sweep` / `top_j_2` vary the strength and the guaranteed top-J; `other_workloads` runs the other
-three stacks (expert kernel time, fraction of the HBM roofline, tok/s); `stream_ceiling_GBps` is what a plain
-elementwise kernel reaches on this device; `cpu_baseline` is the CPU oracle on the first tokens of the workload.
+before it; `lambda_sweep` / `top_j_2` vary the strength and the guaranteed top-J; `prompt_phase` runs the batched
+path (8 / 32 / 128 tokens of a layer per call) on the same store; `other_workloads` runs the other three stacks
+(expert kernel time, fraction of the HBM roofline, tok/s); `stream_ceiling_GBps` is what a plain elementwise kernel
+reaches on this device; `cpu_baseline` is the CPU oracle on the first tokens of the workload.
 """
 from __future__ import annotations
 
