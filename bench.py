@@ -232,7 +232,7 @@ def release_memory():
         torch._C._host_emptyCache()
 
 
-def other_workload(name, dev, n_tokens):
+def other_workload(name, dev, n_tokens, cache_sizes=()):
     """One of the other stacks at full depth: tok/s and miss rate at the headline strength over n_tokens (64 of
     them warm-up), then a miss-free pass (overwhelming prior) in which the expert kernel is timed."""
     import torch
@@ -272,9 +272,38 @@ def other_workload(name, dev, n_tokens):
     )
     log(f"{name}: {out['tok_s']} tok/s (miss rate {out['miss_rate']}), miss-free {out['miss_free_tok_s']} tok/s, "
         f"expert kernel {us:.2f} us = {gbs:.0f} GB/s")
+    sweep = {}
+    if cache_sizes:
+        # the cache-size ablation (Sec. 4.8) on the same tokens: miss rate and tok/s at the headline strength and
+        # with plain LRU routing (lambda = 0), per cache size
+        dec.set_lambda(0.0)
+        r0 = timed_run(dec, a, h, x, None, OWN_WARMUP, steps)
+        sweep[str(cfg.capacity)] = dict(tok_s=out["tok_s"], miss_rate=out["miss_rate"],
+                                        lru_tok_s=round(r0["tok_s"], 2), lru_miss_rate=round(r0["miss_rate"], 5))
     dec.close()
-    del dec, store, a
+    del dec, store
     release_memory()
+    if cache_sizes:
+        for cap in cache_sizes:
+            c2 = cfg.with_(capacity=cap)
+            st = pkg.ExpertStore(n_layers=c2.n_layers, hidden=c2.hidden, n_experts=c2.n_experts, inter=c2.inter,
+                                 shared_inter=c2.shared_inter, capacity=cap, weight_fmt=c2.weight_fmt,
+                                 act_fmt=c2.act_fmt, device=dev)
+            st.fill_from(c2, workloads.expert_weights, workloads.shared_weights, workloads.gate_weight)
+            d2 = pkg.MoEDecoder(st, top_k=c2.top_k, top_j=c2.top_j, lam=HEADLINE_LAMBDA, renormalize=c2.renormalize)
+            torch.cuda.synchronize()
+            r2 = timed_run(d2, a, h, x, None, OWN_WARMUP, steps)
+            d2.set_lambda(0.0)
+            r0 = timed_run(d2, a, h, x, None, OWN_WARMUP, steps)
+            sweep[str(cap)] = dict(tok_s=round(r2["tok_s"], 2), miss_rate=round(r2["miss_rate"], 5),
+                                   lru_tok_s=round(r0["tok_s"], 2), lru_miss_rate=round(r0["miss_rate"], 5))
+            log(f"{name} cache {cap}/{c2.n_experts}: {r2['tok_s']:.1f} tok/s, miss rate {r2['miss_rate']:.4f}; "
+                f"LRU routing {r0['tok_s']:.1f} tok/s, miss rate {r0['miss_rate']:.4f}")
+            d2.close()
+            del d2, st
+            release_memory()
+        out["cache_size_sweep"] = sweep
+    del a
     return out
 
 
@@ -513,7 +542,7 @@ def main():
         # full depth each; the token counts keep the whole bench within minutes (a miss of the Mixtral-shaped stack
         # moves 176 MB over the host link)
         for name, n_tok in (("c3_olmoe_bf16", 1024), ("c4_dsv2lite_int4", 1024), ("c5_mixtral_int8", 192)):
-            others[name] = other_workload(name, dev, n_tok)
+            others[name] = other_workload(name, dev, n_tok, cache_sizes=(16, 48) if name == "c3_olmoe_bf16" else ())
 
     out = {
         "metric": "batch1_decode_tok_per_s",
