@@ -489,6 +489,28 @@ def main():
                          mean_lifetime_tokens=round(r3["mean_lifetime"], 2))
         log(f"top_j=2: {r3['tok_s']:.1f} tok/s, miss rate {r3['miss_rate']:.4f}")
 
+    # the training-free baselines the paper compares against, on the same tokens: Max-Rank (Eq. 6-7), Cumsum-Threshold
+    # (Eq. 8) and pruning to h - 1 experts (Sec. 4.2, misses normalised by K); miss rates only - their cost in task
+    # quality is what the paper measures and this synthetic stack cannot
+    baselines = None
+    if not args.no_sweep:
+        baselines = {}
+        cases = [("max_rank_M8", dict(route_mode=pkg.MOE_ROUTE_MAX_RANK, max_rank=8), cfg.top_k),
+                 ("max_rank_M16", dict(route_mode=pkg.MOE_ROUTE_MAX_RANK, max_rank=16), cfg.top_k),
+                 ("cumsum_p0.5", dict(route_mode=pkg.MOE_ROUTE_CUMSUM, cumsum_p=0.5), cfg.top_k),
+                 ("cumsum_p0.8", dict(route_mode=pkg.MOE_ROUTE_CUMSUM, cumsum_p=0.8), cfg.top_k)]
+        if cfg.top_k > 2:
+            cases.append((f"pruning_h{cfg.top_k}", dict(lam=0.0), cfg.top_k - 1))
+        for key, kw, k_used in cases:
+            kw = dict(dict(lam=0.0), **kw)
+            d4 = pkg.MoEDecoder(store, top_k=k_used, top_j=cfg.top_j, renormalize=cfg.renormalize, **kw)
+            r4 = timed_run(d4, a, h, x, y, OWN_WARMUP, own_steps)
+            d4.close()
+            del d4
+            misses_per_k = r4["misses"] / max(own_steps * cfg.n_layers * cfg.top_k, 1)
+            baselines[key] = dict(tok_s=round(r4["tok_s"], 2), miss_rate=round(misses_per_k, 5), experts_used=k_used)
+            log(f"baseline {key}: {r4['tok_s']:.1f} tok/s, miss rate {misses_per_k:.4f}")
+
     prompt = None
     if not args.no_sweep and cfg.weight_fmt == "bf16" and cfg.act_fmt == "bf16" and cfg.hidden in (1024, 2048):
         prompt = prompt_phase(pkg, store, cfg, a, dev)
@@ -594,7 +616,7 @@ def main():
         "boundary_as_separate_launch": alone,
         "cpu_baseline": cpu,
         "lambda_sweep": sweep,
-        "top_j_2": top_j_run,
+        "top_j_2": top_j_run, "baselines": baselines,
         "prompt_phase": prompt,
         "other_workloads": others,
     }
