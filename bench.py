@@ -131,6 +131,36 @@ def timed_run(dec, a, h, x, y, warmup, steps):
     )
 
 
+def routing_deviation(dec, cfg, a, h, x, warmup, steps, every=4):
+    """How far the selections move away from the router's own top-K, the price the method pays for its hits (the
+    paper measures it as perplexity / accuracy, which needs trained weights; this is the routing-level proxy):
+    a pass over the same tokens in which every `every`-th token's decision records are fetched, giving the mean
+    share of the original top-K's softmax mass that the selected experts keep, and the mean overlap with that top-K."""
+    import numpy as np
+
+    dec.reset()
+    decode_tokens(dec, a, h, x, None, 0, warmup)
+    K, N, L = cfg.top_k, cfg.n_experts, cfg.n_layers
+    kept = overlap = 0.0
+    n = 0
+    for t in range(warmup, warmup + steps):
+        if (t - warmup) % every:
+            decode_tokens(dec, a, h, x, None, t, t + 1)
+            continue
+        for l in range(L):
+            dec.stack_route_step(l, h, a[t, l], 1.0 if l == 0 else PERTURB, x, carry=l > 0, wait=False)
+            dec.expert_forward(l, x, None)
+            rec = dec.last_route(l)
+            z = np.array(rec.logits[:N], np.float64)
+            p = np.exp(z - z.max())
+            orig = np.argsort(-z, kind="stable")[:K]
+            sel = np.array(rec.sel_expert[:dec.top_k])
+            kept += p[sel].sum() / p[orig].sum()
+            overlap += len(set(sel.tolist()) & set(orig.tolist())) / K
+            n += 1
+    return dict(router_mass_kept=round(kept / max(n, 1), 4), topk_overlap=round(overlap / max(n, 1), 4))
+
+
 def stream_ceiling(dev, reps=6):
     """GB/s of a plain elementwise kernel (int64 add over 32 Mi elements: reads 256 MiB, writes 256 MiB), the best
     of a few launches timed with events: what HBM delivers to simple streaming code on this device.  The same
@@ -452,8 +482,10 @@ def main():
             r = timed_run(dec, a, h, x, y, OWN_WARMUP, own_steps)
             sweep[str(lam)] = dict(tok_s=round(r["tok_s"], 2), miss_rate=round(r["miss_rate"], 5),
                                    host_link_GB=round(r["host_link_bytes"] / 1e9, 3),
-                                   mean_lifetime_tokens=round(r["mean_lifetime"], 2))
-            log(f"lambda={lam}: {r['tok_s']:.1f} tok/s, miss rate {r['miss_rate']:.4f}")
+                                   mean_lifetime_tokens=round(r["mean_lifetime"], 2),
+                                   **routing_deviation(dec, cfg, a, h, x, OWN_WARMUP, own_steps))
+            log(f"lambda={lam}: {r['tok_s']:.1f} tok/s, miss rate {r['miss_rate']:.4f}, "
+                f"router mass kept {sweep[str(lam)]['router_mass_kept']:.4f}")
         # miss-free run: with an overwhelming prior the cache freezes after warm-up (Sec. 3.3)
         dec.set_lambda(1e6)
         r = timed_run(dec, a, h, x, y, OWN_WARMUP, own_steps)
@@ -461,6 +493,11 @@ def main():
                                   per_layer_us=round(1e3 * r["ms_per_step"] / cfg.n_layers, 3))
         log(f"miss-free: {r['tok_s']:.1f} tok/s")
         dec.set_lambda(HEADLINE_LAMBDA)
+        sweep[str(HEADLINE_LAMBDA)] = dict(tok_s=round(steady["tok_s"], 2), miss_rate=round(steady["miss_rate"], 5),
+                                           mean_lifetime_tokens=round(steady["mean_lifetime"], 2),
+                                           **routing_deviation(dec, cfg, a, h, x, OWN_WARMUP, own_steps))
+        log(f"lambda={HEADLINE_LAMBDA}: router mass kept {sweep[str(HEADLINE_LAMBDA)]['router_mass_kept']:.4f}, "
+            f"top-K overlap {sweep[str(HEADLINE_LAMBDA)]['topk_overlap']:.4f}")
 
     # the expert kernel as a launch of its own (layer boundary in a separate launch), for comparison: a second context
     # on the same store, created with the in-launch boundary switched off, over the same tokens
@@ -483,10 +520,11 @@ def main():
     if not args.no_sweep and cfg.top_k > 2:
         dec3 = pkg.MoEDecoder(store, top_k=cfg.top_k, top_j=2, lam=HEADLINE_LAMBDA, renormalize=cfg.renormalize)
         r3 = timed_run(dec3, a, h, x, y, OWN_WARMUP, own_steps)
+        top_j_run = dict(top_j=2, tok_s=round(r3["tok_s"], 2), miss_rate=round(r3["miss_rate"], 5),
+                         mean_lifetime_tokens=round(r3["mean_lifetime"], 2),
+                         **routing_deviation(dec3, cfg, a, h, x, OWN_WARMUP, own_steps))
         dec3.close()
         del dec3
-        top_j_run = dict(top_j=2, tok_s=round(r3["tok_s"], 2), miss_rate=round(r3["miss_rate"], 5),
-                         mean_lifetime_tokens=round(r3["mean_lifetime"], 2))
         log(f"top_j=2: {r3['tok_s']:.1f} tok/s, miss rate {r3['miss_rate']:.4f}")
 
     # the training-free baselines the paper compares against, on the same tokens: Max-Rank (Eq. 6-7), Cumsum-Threshold
@@ -505,11 +543,13 @@ def main():
             kw = dict(dict(lam=0.0), **kw)
             d4 = pkg.MoEDecoder(store, top_k=k_used, top_j=cfg.top_j, renormalize=cfg.renormalize, **kw)
             r4 = timed_run(d4, a, h, x, y, OWN_WARMUP, own_steps)
+            misses_per_k = r4["misses"] / max(own_steps * cfg.n_layers * cfg.top_k, 1)
+            baselines[key] = dict(tok_s=round(r4["tok_s"], 2), miss_rate=round(misses_per_k, 5), experts_used=k_used,
+                                  **routing_deviation(d4, cfg, a, h, x, OWN_WARMUP, own_steps))
             d4.close()
             del d4
-            misses_per_k = r4["misses"] / max(own_steps * cfg.n_layers * cfg.top_k, 1)
-            baselines[key] = dict(tok_s=round(r4["tok_s"], 2), miss_rate=round(misses_per_k, 5), experts_used=k_used)
-            log(f"baseline {key}: {r4['tok_s']:.1f} tok/s, miss rate {misses_per_k:.4f}")
+            log(f"baseline {key}: {r4['tok_s']:.1f} tok/s, miss rate {misses_per_k:.4f}, "
+                f"router mass kept {baselines[key]['router_mass_kept']:.4f}")
 
     prompt = None
     if not args.no_sweep and cfg.weight_fmt == "bf16" and cfg.act_fmt == "bf16" and cfg.hidden in (1024, 2048):
