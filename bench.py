@@ -43,7 +43,7 @@ PERTURB = 0.5
 # only for the kernel sources it was taken with: reported as null once their hash differs.
 GEMV_TRAFFIC = {
     "workload": "c2_qwen_bf16",
-    "sources_sha256": "9e5f8b5757b109fe578a515d0d8217d82c537fdfb63d5df4283176c00d5797bf",
+    "sources_sha256": "9370ef44b969884ca3c6c4ac2d31f139e5319bf85d152f644303d883049559e6",
     "fetch_kib": 68031.8, "fetch_scale": 2.0,
     "write_kib": 2054.0, "write_scale": 1.0,
 }
