@@ -26,6 +26,9 @@
  *                              words the router stores into mapped host memory
  *      MOE_FUSE_BOUNDARY=0|1   overrides the rule that decides whether a non-blocking moe_stack_route_step runs
  *                              inside the layer's expert launch (see moe_cache_plan)
+ *      MOE_POISON_FILLS=1      debugging aid: a slot is overwritten with 0xff bytes (NaNs in every format's
+ *                              scales or weights) on the copy stream right before its fill, so that anything
+ *                              computed from a slot before its fill has landed shows up as NaN in the output
  *      MOE_TAG_SPINS=n         polls before a workgroup stops waiting for the first workgroup of its own launch
  *                              (a test lowers it to reach the error path described at moe_stack_route_step)
  */

@@ -78,6 +78,7 @@ struct moe_cache {
   uint32_t *h_gave_up = nullptr;    // pinned, mapped: set by a wavefront that stopped waiting for the hand-over
   uint32_t *h_gave_up_dev = nullptr;
   bool fuse_boundary = true;        // run deferred boundaries inside the expert launch (see moe_cache_init)
+  bool poison_fills = false;        // debugging aid: a slot is overwritten with NaN patterns before its fill (MOE_POISON_FILLS)
   int tag_spins = 1 << 18;          // polls (about a tenth of a second) before a workgroup stops waiting for
                                     // workgroup 0; MOE_TAG_SPINS lowers it so that tests reach the error path
   int32_t *d_initial = nullptr;
@@ -307,6 +308,7 @@ int moe_cache_init(const moe_cache_config_t *cfg, const moe_cache_buffers_t *b, 
   // MOE_FUSE_BOUNDARY=0 / 1 in the environment overrides the rule.
   c->fuse_boundary = 3 * (int64_t)cfg->shared_inter >= (int64_t)cfg->top_k * cfg->inter + cfg->shared_inter;
   if (const char *s = getenv("MOE_FUSE_BOUNDARY")) c->fuse_boundary = atoi(s) != 0;
+  if (const char *s = getenv("MOE_POISON_FILLS")) c->poison_fills = atoi(s) != 0;
   if (const char *s = getenv("MOE_TAG_SPINS")) if (atoi(s) > 0) c->tag_spins = atoi(s);
   HIP_INIT(hipMalloc(&c->d_initial, sizeof(int32_t) * (size_t)L * (b->n_initial > 0 ? b->n_initial : 1)));
   HIP_INIT(hipMalloc(&c->d_partial, sizeof(float) * 2 * (size_t)c->plan.grid * cfg->hidden));
@@ -420,6 +422,10 @@ static int collect_route(moe_cache_t *c, int32_t layer, uint32_t seq, int *n_mis
       const int e = d.expert[k], s = d.slot[k];
       if (e >= g.n_experts || s >= g.capacity)
         return fail(MOE_EHIP, "route kernel returned expert %d slot %d out of range", e, s);
+      // (debugging aid: whatever uses the slot before the fill has landed then computes NaNs, which no parity
+      // test lets pass)
+      if (c->poison_fills)
+        HIP_TRY(hipMemsetAsync(static_cast<uint8_t *>(c->slot_pool[layer]) + (size_t)s * slot_bytes, 0xff, slot_bytes, c->copy));
       HIP_TRY(hipMemcpyAsync(static_cast<uint8_t *>(c->slot_pool[layer]) + (size_t)s * slot_bytes,
                              c->host_blob[(size_t)layer * g.n_experts + e], slot_bytes, hipMemcpyHostToDevice,
                              c->copy));
@@ -707,6 +713,9 @@ int moe_expert_forward_batch(moe_cache_t *c, int32_t layer, const void *x_dev, v
         if (!r.miss[k]) continue;
         filled |= 1ull << r.sel_slot[k];
         if (n_fill++ == 0) HIP_TRY(hipStreamWaitEvent(c->copy, c->ev_batch, 0));
+        if (c->poison_fills)
+          HIP_TRY(hipMemsetAsync(static_cast<uint8_t *>(c->slot_pool[layer]) + (size_t)r.sel_slot[k] * slot_bytes, 0xff,
+                                 slot_bytes, c->copy));
         HIP_TRY(hipMemcpyAsync(static_cast<uint8_t *>(c->slot_pool[layer]) + (size_t)r.sel_slot[k] * slot_bytes,
                                c->host_blob[(size_t)layer * g.n_experts + r.sel_expert[k]], slot_bytes,
                                hipMemcpyHostToDevice, c->copy));
