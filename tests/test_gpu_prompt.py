@@ -125,6 +125,13 @@ def test_batch_outputs_full_layer_shape():
     run_prompt_outputs(cfg, 0.5, [32, 128], every=9)
 
 
+def test_batch_outputs_olmoe_layer_shape():
+    """The OLMoE-shaped layer (64 experts of 1024, no shared expert, top-8, cache 32): batches of 128, 16 and 40;
+    outputs of every 11th token against the oracle."""
+    cfg = CONFIGS["c3_olmoe_bf16"].with_(n_layers=1)
+    run_prompt_outputs(cfg, 0.5, [128, 16, 40], every=11)
+
+
 def test_batch_outputs_are_reproducible():
     cfg = BASE.with_(n_layers=1, hidden=2048, n_experts=16, inter=96, shared_inter=160, top_k=4, capacity=6, seed=616)
     store, dec = build(cfg, lam=0.25)
