@@ -175,8 +175,9 @@ int moe_expert_forward(moe_cache_t *ctx, int32_t layer, const void *x_dev, void 
  * moe_expert_forward_batch: y[t] = sum_k w_k E_k(x[t]) + shared(x[t]) (Eq. 1) for every token of the batch routed
  *   last; x_dev as given to moe_route_batch, y_dev device [n_tokens, d] in act_fmt.  Tokens are grouped per expert;
  *   where a slot is refilled inside the batch after an earlier token has read it, the batch is cut there and the
- *   parts run one after the other, each behind its fills.  The partial results are added in a fixed order (y is
- *   reproducible bit for bit).  Returns when y is complete.
+ *   parts run one after the other; within a part the experts that are resident (and the shared expert) are computed
+ *   while the part's fills stream, the filled ones behind them.  The partial results are added in a fixed order (y
+ *   is reproducible bit for bit).  Returns when y is complete.
  * Shapes: bf16 weights and activations, hidden 1024 or 2048, intermediate sizes that are multiples of 16;
  * MOE_EINVAL otherwise.  MOE_ESTATE if a single-token step of the layer or an expert output is pending, or if
  * moe_expert_forward_batch does not follow a moe_route_batch of the same layer and size. */
