@@ -118,7 +118,6 @@ struct moe_cache {
   std::vector<int32_t> tile_slot, tile_first_unit;
   int batch_layer = -1, batch_n = 0;
   hipEvent_t ev_batch = nullptr;            // compute stream has finished reading the slots (before fills overwrite them)
-  int64_t batch_units_launched = 0, batch_segments = 0;
 
   // optional timing of the expert GEMV launches
   int profiling = 0;      // 0 = off, n = events on every n-th expert launch of a layer's first pass
@@ -870,8 +869,6 @@ int moe_expert_forward_batch(moe_cache_t *c, int32_t layer, const void *x_dev, v
     HIP_TRY(launch_reduce_batch(c->d_bpartial, c->d_contrib + kMaxBatch, c->d_contrib, mc, y_dev, d, t0, n_seg,
                                 c->compute));
     HIP_TRY(hipEventRecord(c->ev_batch, c->compute));
-    c->batch_units_launched += n_units;
-    ++c->batch_segments;
     t0 = t1;
   }
   HIP_TRY(hipStreamSynchronize(c->compute));
