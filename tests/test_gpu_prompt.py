@@ -202,7 +202,8 @@ def test_batch_equals_single_token_path_and_errors():
     dec3.close()
 
 
-@pytest.mark.parametrize("mode", ["lru", "strong_prior", "max_rank", "cumsum", "delta_fixed", "delta_token", "renorm_topj"])
+@pytest.mark.parametrize("mode", ["lru", "strong_prior", "max_rank", "cumsum", "delta_fixed", "delta_token", "renorm_topj",
+                                  "initial_residents"])
 @pytest.mark.parametrize("C", [3, 12])
 def test_batch_routing_equals_token_by_token_in_every_mode(mode, C):
     """The batch routing accepts the tokens of a window up to the first miss and routes the missing token alone:
@@ -212,7 +213,8 @@ def test_batch_routing_equals_token_by_token_in_every_mode(mode, C):
 
     kw = dict(lru=dict(lam=0.0), strong_prior=dict(lam=2.0), max_rank=dict(route_mode=pkg.MOE_ROUTE_MAX_RANK, max_rank=8, top_j=1),
               cumsum=dict(route_mode=pkg.MOE_ROUTE_CUMSUM, cumsum_p=0.7), delta_fixed=dict(lam=0.5, delta_fixed=1.25),
-              delta_token=dict(lam=0.7, delta_per_token=True), renorm_topj=dict(lam=0.5, top_j=1))[mode]
+              delta_token=dict(lam=0.7, delta_per_token=True), renorm_topj=dict(lam=0.5, top_j=1),
+              initial_residents=dict(lam=0.5, initial=[[5, 2, 9][:min(C, 3)]]))[mode]
     N, K = 16, 3
     cfg = BASE.with_(n_layers=1, hidden=1024, n_experts=N, inter=32, shared_inter=32, top_k=K, capacity=C,
                      renormalize=mode == "renorm_topj", seed=930 + C)
