@@ -43,8 +43,8 @@ PERTURB = 0.5
 # only for the kernel sources it was taken with: reported as null once their hash differs.
 GEMV_TRAFFIC = {
     "workload": "c2_qwen_bf16",
-    "sources_sha256": "9370ef44b969884ca3c6c4ac2d31f139e5319bf85d152f644303d883049559e6",
-    "fetch_kib": 68031.8, "fetch_scale": 2.0,
+    "sources_sha256": "e40fa05ac844eb380480d4b9c03a48162916dd8764aa353c21e86d3c46ac49f9",
+    "fetch_kib": 68035.1, "fetch_scale": 2.0,
     "write_kib": 2054.0, "write_scale": 1.0,
 }
 GEMV_SOURCES = ("expert_gemv.hip", "gemv_common.h", "route_device.h", "common.h")

@@ -319,18 +319,39 @@ __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_
     ever_used |= 1ull << s;
   }
 
+  // ---- the decision in selection order, into the record being assembled in LDS ----------------------------
+  rec_s[lane] = 0;
+  if (lane + 64 < kRecWords) rec_s[lane + 64] = 0;
+  __builtin_amdgcn_wave_barrier();
+  if (lane < MOE_MAX_TOPK) rec_s[W_EVICT + lane] = (uint32_t)-1;
+  if (active) rec_s[W_LOGITS + lane] = __float_as_uint(z);
+  __builtin_amdgcn_wave_barrier();
+  if (sel) {
+    const int k = rank_p;
+    rec_s[W_EXPERT + k] = (uint32_t)lane;
+    rec_s[W_SLOT + k] = (uint32_t)my_slot;
+    rec_s[W_WEIGHT + k] = __float_as_uint(w);
+    rec_s[W_MISS + k] = miss ? 1u : 0u;
+    rec_s[W_EVICT + k] = (uint32_t)my_evicted;
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   // ---- what the host needs (experts, slots, miss flags in selection order): three tagged 8-byte words ----
-  // stored to mapped host memory as early as possible, so the trip over the host link overlaps the rest
+  // stored to mapped host memory as early as possible, so the trip over the host link overlaps the rest.  Every
+  // lane packs them from the K entries just written (the same LDS words for all lanes: broadcast reads; a loop over
+  // the selected lanes with lane reads costs three times as long)
   uint32_t lo = 0, hi = 0, mm = 0;
   uint64_t ew = 0, sw = 0;
-  for (uint64_t m = sel_mask; m; m &= m - 1) {
-    const int e = (int)__builtin_ctzll(m);
-    const int k = readlane_i(rank_p, e);
-    const uint32_t s8 = (uint32_t)readlane_i(my_slot, e) & 0xffu;
-    if (k < 4) lo |= s8 << (8 * k); else hi |= s8 << (8 * (k - 4));
-    mm |= (uint32_t)((miss_mask >> e) & 1) << k;
-    ew |= (uint64_t)e << (16 + 6 * k);
-    sw |= (uint64_t)(s8 & 63u) << (16 + 6 * k);
+#pragma unroll
+  for (int k = 0; k < MOE_MAX_TOPK; ++k) {
+    if (k < K) {
+      const uint32_t e = rec_s[W_EXPERT + k], s8 = rec_s[W_SLOT + k] & 0xffu;
+      if (k < 4) lo |= s8 << (8 * k); else hi |= s8 << (8 * (k - 4));
+      mm |= rec_s[W_MISS + k] << k;
+      ew |= (uint64_t)e << (16 + 6 * k);
+      sw |= (uint64_t)(s8 & 63u) << (16 + 6 * k);
+    }
   }
   if (note != nullptr && lane < 3) {
     const uint64_t tag = p.seq & 0xffffu;
@@ -341,12 +362,6 @@ __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_
 
   // ---- expert kernels waiting in the same launch need weights, slots and miss flags (see BoundaryFlags)
   if (flags.handover != nullptr) {
-    if (lane <= MOE_MAX_TOPK) rec_s[W_WEIGHT + lane] = 0u;  // W_WEIGHT + 8 (= W_MISS) is rewritten further down
-    __builtin_amdgcn_wave_barrier();
-    if (sel) rec_s[W_WEIGHT + rank_p] = __float_as_uint(w);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     const int word = lane & 7;  // lane = copy * 8 + word
     uint64_t payload;
     if (word == 0) {
@@ -355,7 +370,8 @@ __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_
       payload = (uint64_t)(hi >> 16) | ((uint64_t)(mm & 0xffu) << 16);
     } else {
       const int bit = 48 * (word - 2), i = bit >> 5, sh = bit & 31;  // position in the 256-bit weight string
-      const uint64_t two = (uint64_t)rec_s[W_WEIGHT + i] | ((uint64_t)rec_s[W_WEIGHT + i + 1] << 32);
+      const uint32_t next = i + 1 < MOE_MAX_TOPK ? rec_s[W_WEIGHT + i + 1] : 0u;  // (the string ends with weight 7)
+      const uint64_t two = (uint64_t)rec_s[W_WEIGHT + i] | ((uint64_t)next << 32);
       payload = (two >> sh) & 0xffffffffffffull;
     }
     __hip_atomic_store(flags.handover + lane, (payload << 16) | (uint64_t)(flags.tag & 0xffffu), __ATOMIC_RELAXED,
@@ -397,20 +413,6 @@ __device__ __forceinline__ void route_wave(const RouteParams &p, const float *z_
   }
 
   // ---- full decision record in device memory: assembled in LDS, copied out in 16-byte chunks ----
-  rec_s[lane] = 0;
-  if (lane + 64 < kRecWords) rec_s[lane + 64] = 0;
-  __builtin_amdgcn_wave_barrier();
-  if (lane < MOE_MAX_TOPK) rec_s[W_EVICT + lane] = (uint32_t)-1;
-  if (active) rec_s[W_LOGITS + lane] = __float_as_uint(z);
-  __builtin_amdgcn_wave_barrier();
-  if (sel) {
-    const int k = rank_p;
-    rec_s[W_EXPERT + k] = (uint32_t)lane;
-    rec_s[W_SLOT + k] = (uint32_t)my_slot;
-    rec_s[W_WEIGHT + k] = __float_as_uint(w);
-    rec_s[W_MISS + k] = miss ? 1u : 0u;
-    rec_s[W_EVICT + k] = (uint32_t)my_evicted;
-  }
   if (lane == 0) {
     // compact copy for the expert kernels: slots 8 bits each in selection order, miss flags as a mask
     rec_s[W_SEQ] = p.seq;
